@@ -1,0 +1,243 @@
+/*
+ * CPU oracle for the BiQGEMM lookup-table matrix multiply.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, single-threaded C in fp64, written
+ * from the paper (arxiv 2005.09904) so that a reader can check it against the
+ * text by eye.  It shares no code, header, table or constant with the GPU
+ * library and is never called by the product path; only tests, the smoke check
+ * and the benchmark's cpu_baseline leg load it.
+ *
+ * Notation follows the paper: m = output size, n = input size, b = batch,
+ * q = number of bit-planes (beta_w), mu = LUT-unit, C = ceil(n / mu) chunks.
+ *
+ * Readings taken where the paper is silent or garbled (each is also listed in
+ * the design notes of this repository):
+ *   - bit order inside a key: element j of a chunk is bit j (value 2^j),
+ *     +1 <-> bit 1, -1 <-> bit 0.  Follows Algorithm 1 (index 2^(i-1)+j adds
+ *     2*x_(i-1)) and Algorithm 3 (w_i = ((x >> i) & 1) * 2 - 1); agrees with
+ *     the printed example {-1,1,1,-1} -> 6 (Sec. III-B).
+ *   - Algorithm 1's first loop is read as r_0 = -(x_0 + ... + x_(mu-1)), the
+ *     entry of key 0 (all signs -1); as printed (r_0 = +sum) the later
+ *     "+ 2 x_(i-1)" steps would not give +-1 combinations.
+ *   - n not a multiple of mu: the last chunk is padded with x = 0 and key
+ *     bits 0; padding bits of a packed row are 0.
+ *   - alpha is one fp32 scalar per output row per plane: alpha[q][m] (Eq. 2).
+ *   - X is stored [b][n], Y is stored [b][m] (each input vector contiguous,
+ *     Definition 2's column-wise traversal of the n-by-b matrix).
+ *   - planes are concatenated vertically (Sec. III-B, Fig. of multi-bit
+ *     weights): keys[q][m][C], B[q][m][n].
+ *
+ * Every function returns 0 on success, a negative number on invalid input.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define BIQO_OK 0
+#define BIQO_EINVAL (-1)
+#define BIQO_EVALUE (-2) /* an element of B is not +1 or -1 */
+#define BIQO_ENOMEM (-3)
+
+/* C = ceil(n / mu): number of mu-element chunks of an input vector (Sec. III-B:
+ * 0 <= beta < n/mu, extended to a ragged tail). */
+long biqo_num_chunks(long n, int mu) { return (n + mu - 1) / mu; }
+
+/* Bytes of one packed row: the n sign bits, padded with zero bits to a
+ * multiple of 128 bits. */
+long biqo_row_stride_bytes(long n) { return ((n + 127) / 128) * 16; }
+
+/* Table II's weight footprint for q-bit binary coding: q*m*n bits. */
+long biqo_packed_bits(long m, long n, int q) { return (long)q * m * n; }
+
+static int check_dims(long m, long n, int q, long b, int mu) {
+    if (m < 1 || n < 1 || q < 1 || b < 1) return BIQO_EINVAL;
+    if (mu < 1 || mu > 16) return BIQO_EINVAL;
+    return BIQO_OK;
+}
+
+/*
+ * Key matrix K (Sec. III-B, Fig. "retrieving partial results"): for plane i,
+ * row r, chunk c the mu consecutive signs B_i[r, mu*c .. mu*c+mu-1] become the
+ * integer sum_j [B = +1] * 2^j.  keys is [q][m][C], one uint16 per key.
+ */
+int biqo_pack_keys(const int8_t* B, long m, long n, int q, int mu, uint16_t* keys) {
+    if (!B || !keys || check_dims(m, n, q, 1, mu)) return BIQO_EINVAL;
+    long C = biqo_num_chunks(n, mu);
+    for (int i = 0; i < q; ++i)
+        for (long r = 0; r < m; ++r)
+            for (long c = 0; c < C; ++c) {
+                unsigned key = 0;
+                for (int j = 0; j < mu; ++j) {
+                    long col = c * mu + j;
+                    if (col >= n) break; /* ragged tail: missing bits are 0 */
+                    int8_t s = B[((long)i * m + r) * n + col];
+                    if (s != 1 && s != -1) return BIQO_EVALUE;
+                    if (s == 1) key |= 1u << j;
+                }
+                keys[((long)i * m + r) * C + c] = (uint16_t)key;
+            }
+    return BIQO_OK;
+}
+
+/*
+ * The same signs as a byte stream: bit (col mod 8) of byte (col / 8) of a row
+ * is 1 iff B = +1; rows are biqo_row_stride_bytes(n) apart, plane-major
+ * [q][m][stride].  For mu = 8 byte c of a row is the key of chunk c.
+ */
+int biqo_pack_bitmap(const int8_t* B, long m, long n, int q, uint8_t* out) {
+    if (!B || !out || check_dims(m, n, q, 1, 1)) return BIQO_EINVAL;
+    long stride = biqo_row_stride_bytes(n);
+    memset(out, 0, (size_t)q * m * stride);
+    for (int i = 0; i < q; ++i)
+        for (long r = 0; r < m; ++r)
+            for (long col = 0; col < n; ++col) {
+                int8_t s = B[((long)i * m + r) * n + col];
+                if (s != 1 && s != -1) return BIQO_EVALUE;
+                if (s == 1) out[((long)i * m + r) * stride + col / 8] |= (uint8_t)(1u << (col % 8));
+            }
+    return BIQO_OK;
+}
+
+/* Reads the keys of LUT-unit mu back out of a packed byte stream: key bit j of
+ * chunk c is stream bit mu*c + j (0 past column n). */
+int biqo_keys_from_bitmap(const uint8_t* bitmap, long m, long n, int q, int mu, uint16_t* keys) {
+    if (!bitmap || !keys || check_dims(m, n, q, 1, mu)) return BIQO_EINVAL;
+    long stride = biqo_row_stride_bytes(n);
+    long C = biqo_num_chunks(n, mu);
+    for (long kr = 0; kr < (long)q * m; ++kr)
+        for (long c = 0; c < C; ++c) {
+            unsigned key = 0;
+            for (int j = 0; j < mu; ++j) {
+                long col = c * mu + j;
+                if (col >= n) break;
+                if ((bitmap[kr * stride + col / 8] >> (col % 8)) & 1u) key |= 1u << j;
+            }
+            keys[kr * C + c] = (uint16_t)key;
+        }
+    return BIQO_OK;
+}
+
+/*
+ * One lookup table by its definition q = M_mu . x (Sec. III-B, the equation
+ * defining q_alpha^beta; Definition 5 for M_mu): entry k is the sum over j of
+ * s_j(k) * x_j with s_j(k) = +1 if bit j of k is set, else -1.
+ */
+void biqo_lut_enum(const double* x, int mu, double* table) {
+    for (unsigned k = 0; k < (1u << mu); ++k) {
+        double acc = 0.0;
+        for (int j = 0; j < mu; ++j) acc += ((k >> j) & 1u) ? x[j] : -x[j];
+        table[k] = acc;
+    }
+}
+
+/*
+ * The same table by Algorithm 1 (dynamic programming), in the reading stated
+ * at the top of this file.  Returns the number of arithmetic operations it
+ * performed, which Eq. 6 states as 2^mu + mu - 1 per table.
+ */
+long biqo_lut_dp(const double* x, int mu, double* r) {
+    long ops = 0;
+    /* entry of key 0: every sign is -1 (mu operations: mu-1 adds, 1 negation) */
+    double s = x[0];
+    for (int i = 1; i < mu; ++i) { s += x[i]; ++ops; }
+    r[0] = -s; ++ops;
+    /* lower half: setting bit (i-1) of key j < 2^(i-1) flips x_(i-1) from - to + */
+    long k = 1;
+    for (int i = 1; i <= mu - 1; ++i)
+        for (long j = 0; j < (1L << (i - 1)); ++j) { r[k++] = r[j] + 2.0 * x[i - 1]; ++ops; }
+    /* upper half: the complement of a key has the negated sum */
+    for (long i = 1; i <= (1L << (mu - 1)); ++i) { r[(1L << mu) - i] = -r[i - 1]; ++ops; }
+    return ops;
+}
+
+/*
+ * All tables of an input matrix (Sec. III-B): Q[c][k][a] for chunk c, key k,
+ * input vector a; X is [b][n] fp32, Q is [C][2^mu][b] fp64.
+ */
+int biqo_build_lut(const float* X, long n, long b, int mu, double* Q) {
+    if (!X || !Q || check_dims(1, n, 1, b, mu)) return BIQO_EINVAL;
+    long C = biqo_num_chunks(n, mu);
+    long E = 1L << mu;
+    double xs[16], table[1 << 16];
+    for (long c = 0; c < C; ++c)
+        for (long a = 0; a < b; ++a) {
+            for (int j = 0; j < mu; ++j) {
+                long col = c * mu + j;
+                xs[j] = col < n ? (double)X[a * n + col] : 0.0;
+            }
+            biqo_lut_enum(xs, mu, table);
+            for (long k = 0; k < E; ++k) Q[(c * E + k) * b + a] = table[k];
+        }
+    return BIQO_OK;
+}
+
+/*
+ * Eq. 2 written out: W = sum_i alpha_i B_i reconstructed explicitly (one row
+ * at a time), then Y = W X.  fp64 throughout.  If rows != NULL only the nrows
+ * listed output rows are computed and Y is [b][nrows]; otherwise Y is [b][m].
+ */
+int biqo_gemm_dense_rows(const int8_t* B, const float* alpha, const float* X, long m, long n, int q,
+                         long b, const int64_t* rows, long nrows, double* Y) {
+    if (!B || !alpha || !X || !Y || check_dims(m, n, q, b, 1)) return BIQO_EINVAL;
+    long nout = rows ? nrows : m;
+    double* w = (double*)malloc((size_t)n * sizeof(double));
+    if (!w) return BIQO_ENOMEM;
+    for (long o = 0; o < nout; ++o) {
+        long r = rows ? (long)rows[o] : o;
+        if (r < 0 || r >= m) { free(w); return BIQO_EINVAL; }
+        for (long j = 0; j < n; ++j) w[j] = 0.0;
+        for (int i = 0; i < q; ++i) {
+            double a = (double)alpha[(long)i * m + r];
+            for (long j = 0; j < n; ++j) {
+                int8_t s = B[((long)i * m + r) * n + j];
+                if (s != 1 && s != -1) { free(w); return BIQO_EVALUE; }
+                w[j] += a * (double)s;
+            }
+        }
+        for (long c = 0; c < b; ++c) {
+            double acc = 0.0;
+            for (long j = 0; j < n; ++j) acc += w[j] * (double)X[c * n + j];
+            Y[c * nout + o] = acc;
+        }
+    }
+    free(w);
+    return BIQO_OK;
+}
+
+int biqo_gemm_dense(const int8_t* B, const float* alpha, const float* X, long m, long n, int q,
+                    long b, double* Y) {
+    return biqo_gemm_dense_rows(B, alpha, X, m, n, q, b, NULL, 0, Y);
+}
+
+/*
+ * The method itself, Algorithm 2 without tiling: build every table, then for
+ * each plane, row and input vector accumulate Q[c][K[i][r][c]][a] over the
+ * chunks, scale the plane's sum by alpha_i[r] and add the planes (Eq. 2 and
+ * the multi-bit paragraph of Sec. III-B).  keys is [q][m][C]; Y is [b][m].
+ */
+int biqo_gemm_lut(const uint16_t* keys, const float* alpha, const float* X, long m, long n, int q,
+                  long b, int mu, double* Y) {
+    if (!keys || !alpha || !X || !Y || check_dims(m, n, q, b, mu)) return BIQO_EINVAL;
+    long C = biqo_num_chunks(n, mu);
+    long E = 1L << mu;
+    double* Q = (double*)malloc((size_t)C * E * b * sizeof(double));
+    if (!Q) return BIQO_ENOMEM;
+    int rc = biqo_build_lut(X, n, b, mu, Q);
+    if (rc) { free(Q); return rc; }
+    for (long a = 0; a < b; ++a)
+        for (long r = 0; r < m; ++r) {
+            double y = 0.0;
+            for (int i = 0; i < q; ++i) {
+                double p = 0.0;
+                for (long c = 0; c < C; ++c) {
+                    unsigned k = keys[((long)i * m + r) * C + c];
+                    if (k >= (unsigned long)E) { free(Q); return BIQO_EINVAL; }
+                    p += Q[(c * E + k) * b + a];
+                }
+                y += (double)alpha[(long)i * m + r] * p;
+            }
+            Y[a * m + r] = y;
+        }
+    free(Q);
+    return BIQO_OK;
+}

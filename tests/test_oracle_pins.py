@@ -1,0 +1,310 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Nothing here touches the GPU library.  Every check compares the oracle with something
+other than itself: a value the paper prints, a closed form, an invariant, a library
+routine (numpy matmul on the explicitly reconstructed dense matrix) or brute force.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+from conftest import read_golden
+
+
+# --------------------------------------------------------------------------- packing
+
+def test_pack_printed_example(oracle):
+    # Sec. III-B: {-1, 1, 1, -1} -> 6 at mu = 4
+    for mu_s, signs_s, key_s in read_golden("paper_pack_example.txt"):
+        mu = int(mu_s)
+        signs = np.array([int(t) for t in signs_s.split()], dtype=np.int8)
+        keys = oracle.pack_keys(signs.reshape(1, 1, mu), mu)
+        assert keys.shape == (1, 1, 1)
+        assert int(keys[0, 0, 0]) == int(key_s)
+
+
+def test_pack_sign_and_bit_order_single_elements(oracle):
+    # one +1 at position j in an otherwise -1 chunk must give key 2**j (Algorithm 1's
+    # indexing 2^(i-1)+j <-> x_(i-1); Algorithm 3's (x >> i) & 1 <-> w_i)
+    for mu in range(1, 9):
+        for j in range(mu):
+            signs = -np.ones(mu, dtype=np.int8)
+            signs[j] = 1
+            assert int(oracle.pack_keys(signs.reshape(1, 1, mu), mu)[0, 0, 0]) == 1 << j
+        assert int(oracle.pack_keys(np.ones((1, 1, mu), np.int8), mu)[0, 0, 0]) == (1 << mu) - 1
+        assert int(oracle.pack_keys(-np.ones((1, 1, mu), np.int8), mu)[0, 0, 0]) == 0
+
+
+def _alg3_unpack(word: int, count: int):
+    # Algorithm 3 as printed: w_i = ((x >> i) & 1) * 2 - 1
+    return [((word >> i) & 1) * 2 - 1 for i in range(count)]
+
+
+def test_alg3_rule_matches_hand_rows():
+    for word_s, count_s, w_s in read_golden("paper_alg3_unpack.txt"):
+        assert _alg3_unpack(int(word_s, 16), int(count_s)) == [int(t) for t in w_s.split()]
+
+
+@pytest.mark.parametrize("m,n,q", [(3, 32, 1), (5, 77, 2), (2, 128, 3), (4, 300, 1), (1, 1, 1)])
+def test_bitmap_round_trip_through_alg3(oracle, m, n, q):
+    rng = np.random.default_rng(11 + n)
+    B = (rng.integers(0, 2, size=(q, m, n)) * 2 - 1).astype(np.int8)
+    bitmap = oracle.pack_bitmap(B)
+    stride = bitmap.shape[2]
+    assert stride == ((n + 127) // 128) * 16 == oracle.row_stride_bytes(n)
+    words = bitmap.reshape(q, m, stride // 4, 4).astype(np.uint32)
+    words = words[..., 0] | (words[..., 1] << 8) | (words[..., 2] << 16) | (words[..., 3] << 24)
+    for i in range(q):
+        for r in range(m):
+            unpacked = []
+            for w in words[i, r]:
+                unpacked += _alg3_unpack(int(w), 32)
+            assert unpacked[:n] == B[i, r].tolist()
+            # padding bits are zero, i.e. unpack to -1
+            assert all(v == -1 for v in unpacked[n:])
+
+
+def test_packed_size_matches_table2(oracle):
+    # Table II: 512x512 weights with 4 / 3 / 2 binary-coding bits take 0.131 / 0.098 / 0.066 MB
+    for wbits, abits, mb in read_golden("paper_table2_weight_memory.txt"):
+        if int(abits) != 32 or int(wbits) == 32:
+            continue
+        q = int(wbits)
+        bits = oracle.packed_bits(512, 512, q)
+        assert bits % 8 == 0
+        assert "%.3f" % (bits / 8 / 1e6) == mb
+        B = np.ones((q, 512, 512), dtype=np.int8)
+        assert oracle.pack_bitmap(B).nbytes == bits // 8  # n = 512 needs no row padding
+
+
+def test_keys_mu8_are_the_bitmap_bytes_and_mu4_nibbles(oracle):
+    rng = np.random.default_rng(5)
+    n = 200
+    B = (rng.integers(0, 2, size=(2, 7, n)) * 2 - 1).astype(np.int8)
+    bitmap = oracle.pack_bitmap(B)
+    k8 = oracle.pack_keys(B, 8)
+    k4 = oracle.pack_keys(B, 4)
+    assert np.array_equal(k8, bitmap[:, :, : n // 8].astype(np.uint16))
+    assert np.array_equal(k8, k4[:, :, 0::2] | (k4[:, :, 1::2] << 4))
+    for mu in range(1, 9):
+        assert np.array_equal(oracle.keys_from_bitmap(bitmap, n, mu), oracle.pack_keys(B, mu))
+
+
+def test_ragged_tail_key_bits_are_zero(oracle):
+    # n = 10, mu = 4 -> chunks {0..3}, {4..7}, {8, 9, pad, pad}
+    B = np.ones((1, 1, 10), dtype=np.int8)
+    assert oracle.pack_keys(B, 4)[0, 0].tolist() == [15, 15, 3]
+    assert oracle.num_chunks(10, 4) == 3
+    assert oracle.num_chunks(4096, 6) == 683
+
+
+def test_pack_rejects_values_other_than_plus_minus_one(oracle):
+    B = np.ones((1, 2, 8), dtype=np.int8)
+    B[0, 1, 3] = 0
+    with pytest.raises(oracle.OracleError):
+        oracle.pack_keys(B, 8)
+    with pytest.raises(oracle.OracleError):
+        oracle.pack_bitmap(B)
+
+
+# --------------------------------------------------------------------------- tables
+
+def _m_mu(mu: int) -> np.ndarray:
+    # Definition 5: all 2^mu sign vectors; row k is the pattern of integer k, LSB first
+    return np.array([[1.0 if (k >> j) & 1 else -1.0 for j in range(mu)] for k in range(1 << mu)])
+
+
+@pytest.mark.parametrize("mu", range(1, 9))
+def test_lut_is_M_mu_times_x(oracle, mu):
+    rng = np.random.default_rng(100 + mu)
+    x = rng.standard_normal(mu)
+    table = oracle.lut_enum(x)
+    np.testing.assert_allclose(table, _m_mu(mu) @ x, rtol=0, atol=1e-14)
+    # brute force over itertools.product as well (sign of element j <-> bit j)
+    for k, signs in enumerate(itertools.product([-1.0, 1.0], repeat=mu)):
+        signs = signs[::-1]  # product varies the last position fastest = bit 0
+        assert abs(table[k] - float(np.dot(signs, x))) < 1e-14
+
+
+@pytest.mark.parametrize("mu", range(1, 9))
+def test_lut_closed_forms_and_invariants(oracle, mu):
+    rng = np.random.default_rng(200 + mu)
+    x = rng.standard_normal(mu)
+    for table in (oracle.lut_enum(x), oracle.lut_dp(x)[0]):
+        full = (1 << mu) - 1
+        assert abs(table[0] + x.sum()) < 1e-14
+        assert abs(table[full] - x.sum()) < 1e-14
+        for j in range(mu):
+            assert abs(table[1 << j] - (-x.sum() + 2 * x[j])) < 1e-14
+        for k in range(1 << mu):
+            for j in range(mu):
+                assert abs(table[k | (1 << j)] - table[k & ~(1 << j)] - 2 * x[j]) < 1e-13
+    # LUT[~k] = -LUT[k], bit for bit
+    e = oracle.lut_enum(x)
+    d = oracle.lut_dp(x)[0]
+    idx = np.arange(1 << mu)
+    assert np.array_equal(e[full - idx], -e)
+    assert np.array_equal(d[full - idx], -d)
+
+
+def test_lut_dp_equals_enumeration_and_counts_eq6_ops(oracle):
+    for mu_s, ops_s in read_golden("paper_eq6_build_ops.txt"):
+        mu = int(mu_s)
+        x = np.random.default_rng(300 + mu).standard_normal(mu)
+        table, ops = oracle.lut_dp(x)
+        assert ops == int(ops_s) == (1 << mu) + mu - 1
+        np.testing.assert_allclose(table, oracle.lut_enum(x), rtol=0, atol=1e-13)
+
+
+def test_lut_exact_on_integers(oracle):
+    x = np.array([3, -5, 7, 2, -8, 1, 4, -6], dtype=np.float64)
+    e = oracle.lut_enum(x)
+    d = oracle.lut_dp(x)[0]
+    assert np.array_equal(e, d)
+    assert np.array_equal(e, _m_mu(8) @ x)
+
+
+def test_build_lut_layout_and_tail_padding(oracle):
+    rng = np.random.default_rng(17)
+    n, b, mu = 22, 3, 4  # 5 full chunks + a 2-element tail
+    X = rng.standard_normal((b, n)).astype(np.float32)
+    Q = oracle.build_lut(X, mu)
+    assert Q.shape == (6, 16, b)
+    for a in range(b):
+        for c in range(6):
+            xs = np.zeros(mu)
+            seg = X[a, c * mu : min(n, (c + 1) * mu)].astype(np.float64)
+            xs[: len(seg)] = seg
+            np.testing.assert_allclose(Q[c, :, a], _m_mu(mu) @ xs, rtol=0, atol=1e-14)
+
+
+# --------------------------------------------------------------------------- the multiply
+
+def _dense_numpy(B, alpha, X):
+    # Eq. 2 through a library matmul: W = sum_i alpha_i[:, None] * B_i ; Y = X W^T
+    W = (alpha.astype(np.float64)[:, :, None] * B.astype(np.float64)).sum(axis=0)
+    return X.astype(np.float64) @ W.T
+
+
+SHAPES = [
+    # m, n, q, b
+    (1, 1, 1, 1),
+    (8, 24, 3, 3),
+    (5, 17, 2, 2),
+    (16, 64, 1, 1),
+    (7, 100, 3, 4),
+    (33, 130, 2, 5),
+]
+
+
+@pytest.mark.parametrize("m,n,q,b", SHAPES)
+def test_gemm_dense_matches_numpy_matmul(oracle, m, n, q, b):
+    rng = np.random.default_rng(m * 1000 + n)
+    B = (rng.integers(0, 2, size=(q, m, n)) * 2 - 1).astype(np.int8)
+    alpha = rng.uniform(0.05, 1.0, size=(q, m)).astype(np.float32)
+    X = rng.standard_normal((b, n)).astype(np.float32)
+    Y = oracle.gemm_dense(B, alpha, X)
+    ref = _dense_numpy(B, alpha, X)
+    np.testing.assert_allclose(Y, ref, rtol=1e-12, atol=1e-12)
+    rows = np.array(sorted(set(rng.integers(0, m, size=4).tolist())), dtype=np.int64)
+    np.testing.assert_array_equal(oracle.gemm_dense(B, alpha, X, rows=rows), Y[:, rows])
+
+
+@pytest.mark.parametrize("m,n,q,b", SHAPES)
+@pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_gemm_lut_matches_dense_definition(oracle, m, n, q, b, mu):
+    rng = np.random.default_rng(m * 977 + n * 13 + mu)
+    B = (rng.integers(0, 2, size=(q, m, n)) * 2 - 1).astype(np.int8)
+    alpha = rng.uniform(0.05, 1.0, size=(q, m)).astype(np.float32)
+    X = rng.standard_normal((b, n)).astype(np.float32)
+    keys = oracle.pack_keys(B, mu)
+    Y = oracle.gemm_lut(keys, alpha, X, mu)
+    scale = np.abs(X.astype(np.float64)).sum(axis=1, keepdims=True) * np.abs(alpha).sum(axis=0).max()
+    assert np.all(np.abs(Y - oracle.gemm_dense(B, alpha, X)) <= 1e-13 * scale)
+    assert np.all(np.abs(Y - _dense_numpy(B, alpha, X)) <= 1e-13 * scale)
+
+
+def test_gemm_lut_through_bitmap_keys(oracle):
+    # keys read back from the packed byte stream drive the same result
+    rng = np.random.default_rng(91)
+    q, m, n, b = 2, 9, 150, 2
+    B = (rng.integers(0, 2, size=(q, m, n)) * 2 - 1).astype(np.int8)
+    alpha = rng.uniform(0.1, 1.0, size=(q, m)).astype(np.float32)
+    X = rng.standard_normal((b, n)).astype(np.float32)
+    bitmap = oracle.pack_bitmap(B)
+    for mu in (4, 6, 8):
+        Y = oracle.gemm_lut(oracle.keys_from_bitmap(bitmap, n, mu), alpha, X, mu)
+        np.testing.assert_allclose(Y, _dense_numpy(B, alpha, X), rtol=1e-12, atol=1e-12)
+
+
+def test_special_case_all_plus_one(oracle):
+    rng = np.random.default_rng(3)
+    q, m, n, b = 3, 6, 40, 2
+    B = np.ones((q, m, n), dtype=np.int8)
+    alpha = rng.uniform(0.05, 1.0, size=(q, m)).astype(np.float32)
+    X = rng.standard_normal((b, n)).astype(np.float32)
+    expect = X.astype(np.float64).sum(axis=1)[:, None] * alpha.astype(np.float64).sum(axis=0)[None, :]
+    for Y in (oracle.gemm_dense(B, alpha, X), oracle.gemm_lut(oracle.pack_keys(B, 8), alpha, X, 8)):
+        np.testing.assert_allclose(Y, expect, rtol=1e-12, atol=1e-12)
+
+
+def test_special_case_unit_vector_reads_a_column_of_W(oracle):
+    rng = np.random.default_rng(4)
+    q, m, n = 2, 5, 19
+    B = (rng.integers(0, 2, size=(q, m, n)) * 2 - 1).astype(np.int8)
+    alpha = rng.uniform(0.05, 1.0, size=(q, m)).astype(np.float32)
+    for j in (0, 7, 18):
+        X = np.zeros((1, n), dtype=np.float32)
+        X[0, j] = 1.0
+        expect = (alpha.astype(np.float64) * B[:, :, j]).sum(axis=0)
+        for mu in (3, 8):
+            Y = oracle.gemm_lut(oracle.pack_keys(B, mu), alpha, X, mu)
+            np.testing.assert_allclose(Y[0], expect, rtol=0, atol=1e-15)
+        np.testing.assert_allclose(oracle.gemm_dense(B, alpha, X)[0], expect, rtol=0, atol=1e-15)
+
+
+def test_special_case_opposite_planes_cancel(oracle):
+    rng = np.random.default_rng(6)
+    m, n, b = 4, 48, 3
+    B1 = (rng.integers(0, 2, size=(m, n)) * 2 - 1).astype(np.int8)
+    B = np.stack([B1, -B1])
+    a = rng.uniform(0.05, 1.0, size=m).astype(np.float32)
+    alpha = np.stack([a, a])
+    X = rng.standard_normal((b, n)).astype(np.float32)
+    assert np.all(oracle.gemm_lut(oracle.pack_keys(B, 8), alpha, X, 8) == 0.0)
+    assert np.all(np.abs(oracle.gemm_dense(B, alpha, X)) < 1e-13)
+
+
+def test_special_case_single_plane_unit_alpha_is_a_sign_matvec(oracle):
+    rng = np.random.default_rng(8)
+    m, n = 12, 96
+    B = (rng.integers(0, 2, size=(1, m, n)) * 2 - 1).astype(np.int8)
+    alpha = np.ones((1, m), dtype=np.float32)
+    X = rng.standard_normal((1, n)).astype(np.float32)
+    expect = B[0].astype(np.float64) @ X[0].astype(np.float64)
+    np.testing.assert_allclose(oracle.gemm_lut(oracle.pack_keys(B, 8), alpha, X, 8)[0], expect, rtol=1e-13)
+
+
+def test_exact_inputs_make_lut_and_dense_paths_identical(oracle):
+    from paper_2005_09904_amd.workloads import Workload, make_exact_inputs
+
+    w = Workload("tiny_exact", 40, 250, 3, 4, 8, "uniform", seed=77)
+    B, alpha, X = make_exact_inputs(w)
+    dense = oracle.gemm_dense(B, alpha, X)
+    for mu in (4, 6, 8):
+        assert np.array_equal(oracle.gemm_lut(oracle.pack_keys(B, mu), alpha, X, mu), dense)
+    assert np.array_equal(dense, _dense_numpy(B, alpha, X))
+    assert np.array_equal(dense.astype(np.float32).astype(np.float64), dense)  # fits fp32 exactly
+
+
+def test_oracle_lut_path_agrees_with_dense_on_config1(oracle):
+    from paper_2005_09904_amd.workloads import CONFIGS, make_inputs
+
+    w = CONFIGS["cfg1_fc512_b1"]
+    B, alpha, X = make_inputs(w)
+    Yl = oracle.gemm_lut(oracle.pack_keys(B, w.mu), alpha, X, w.mu)
+    Yd = oracle.gemm_dense(B, alpha, X)
+    scale = np.abs(X.astype(np.float64)).sum() * np.abs(alpha).sum(axis=0).max()
+    assert np.max(np.abs(Yl - Yd)) <= 1e-13 * scale
+    assert np.max(np.abs(Yd - _dense_numpy(B, alpha, X))) <= 1e-13 * scale
