@@ -1,0 +1,168 @@
+/*
+ * biq.h - C ABI of libbiq: the BiQGEMM lookup-table matrix multiply
+ * (arxiv 2005.09904) as hand-written HIP kernels for AMD gfx950 (MI355X).
+ *
+ *     Y = sum_{i=1..q} alpha_i o (B_i . X)            (paper Eq. 2)
+ *
+ * with B_i in {-1,+1}^(m x n) (binary-coding quantised weights, Sec. II-B),
+ * X real n x batch, alpha_i in R^m.  The product is never formed from unpacked
+ * weights: each row's signs are packed into mu-bit keys (Sec. III-B), every
+ * mu-element chunk of every input vector gets a table of all 2^mu signed
+ * partial sums q = M_mu . x (Sec. III-B, Algorithm 1), and the keys index
+ * those tables (Algorithm 2).
+ *
+ * Notation (the paper's): m output size, n input size, batch = b, q = number of
+ * bit-planes (beta_w), mu = LUT-unit, C = ceil(n / mu) chunks per row.
+ *
+ * General rules
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or keeps device memory (workspace is passed in).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it; calls return without synchronising.
+ *   - Output buffers are overwritten, never accumulated into.  Buffers must
+ *     not overlap.
+ *   - 1 <= mu <= 8, q >= 1, m, n, batch >= 1; m*q and n below 2^31.  Any
+ *     m, n, batch is accepted: there is no "multiple of the tile" requirement.
+ *   - Errors are returned as a negative biq_status; nothing aborts or throws
+ *     across this boundary.  On an error no kernel has been launched unless
+ *     the status is BIQ_EHIP.
+ *   - Inputs are assumed finite; behaviour on NaN/Inf is unspecified.
+ *
+ * Data layouts
+ *   B      int8   [q][m][n]            +1 / -1 (bit = (B > 0); other values are
+ *                                      not checked on the device)
+ *   K      uint8  [q][m][stride]       packed signs: bit (j mod 8) of byte
+ *                                      (j / 8) of a row is 1 iff B[.., j] = +1
+ *                                      (element j <-> bit j, LSB first, as in
+ *                                      Algorithms 1 and 3); stride =
+ *                                      biq_key_row_stride(n) = ceil(n/128)*16
+ *                                      bytes, padding bits are 0.  The key of
+ *                                      chunk c for LUT-unit mu is the bit field
+ *                                      [mu*c, mu*c + mu) of the row, so one
+ *                                      packed matrix serves every mu; for
+ *                                      mu = 8 byte c IS key c.  Planes are
+ *                                      concatenated vertically (Sec. III-B).
+ *   alpha  float  [q][m]               one scale per output row per plane
+ *   X      float  [batch][n]           each input vector contiguous
+ *   LUT    float  [C][2^mu][batch]     entries of one key adjacent across the
+ *                                      batch (the arrangement of Fig. 8)
+ *   Y      float  [batch][m]
+ *   K must be 16-byte aligned; float buffers 4-byte aligned.
+ */
+#ifndef BIQ_H_
+#define BIQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BIQ_OK = 0,
+    BIQ_EINVAL = -1,       /* null pointer, size out of range, misaligned buffer      */
+    BIQ_EUNSUPPORTED = -2, /* valid request this build cannot serve                   */
+    BIQ_EWORKSPACE = -3,   /* workspace smaller than biq_workspace_bytes()            */
+    BIQ_EHIP = -4          /* the HIP runtime reported an error (launch, attribute)   */
+} biq_status;
+
+/* Static, NUL-terminated description of a status; never freed. */
+const char* biq_status_str(biq_status status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int biq_version(void);
+
+/* ---- sizes (pure host arithmetic, no device access; 0 on invalid arguments) ---- */
+
+/* Bytes between packed rows: ceil(n/128)*16. */
+size_t biq_key_row_stride(int n);
+/* Bytes of the packed matrix K: q*m*stride.  With n a multiple of 128 this is
+ * q*m*n/8, the weight footprint of Table II. */
+size_t biq_packed_bytes(int m, int n, int q);
+/* C = ceil(n/mu). */
+size_t biq_num_chunks(int n, int mu);
+/* Bytes of the full table set: C * 2^mu * batch * 4 (Eq. 6 counts its entries). */
+size_t biq_lut_bytes(int n, int batch, int mu);
+/* Workspace biq_gemm / biq_query need for this shape (may be 0). */
+size_t biq_workspace_bytes(int m, int n, int q, int batch, int mu);
+
+/*
+ * How a call is mapped on the GPU.  Algorithm 2 leaves tile width/height free
+ * (Sec. III-B); biq_plan_get reports the choice the library makes, biq_gemm_ex
+ * accepts a caller-supplied one (for tuning sweeps).
+ */
+typedef struct {
+    int kernel;          /* kernel family id (see biq_kernel_name)                        */
+    int threads;         /* threads per workgroup                                         */
+    int chunks_per_tile; /* chunks whose tables one workgroup holds in LDS at a time      */
+    int batch_tile;      /* input vectors served by one workgroup                         */
+    int chunk_splits;    /* workgroups sharing one row block along n (partials if > 1)    */
+    int tiles_per_split; /* LUT tiles each of those workgroups walks through              */
+    int rows_per_wg;     /* output rows per workgroup                                     */
+    int row_blocks;      /* ceil(m / rows_per_wg)                                         */
+    int batch_tiles;     /* ceil(batch / batch_tile)                                      */
+    int lds_bytes;       /* dynamic LDS per workgroup                                     */
+    int reserved[6];
+} biq_plan;
+
+biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan);
+/* Workspace a given (valid) plan needs. */
+size_t biq_plan_workspace_bytes(const biq_plan* plan, int m, int batch);
+const char* biq_kernel_name(int kernel);
+
+/* ---- operations ---- */
+
+/*
+ * Key packing (Sec. III-B: mu consecutive binary weights of a row become the
+ * integer key; K "can be loaded in advance").  B device int8 [q][m][n] -> K device
+ * uint8 [q][m][stride].  The byte format does not depend on mu (see above); mu is
+ * validated only.  Bit = (B > 0).
+ */
+biq_status biq_pack(const int8_t* B, uint8_t* K, int m, int n, int q, int mu, void* stream);
+
+/*
+ * The table indices exactly as the query kernels extract them from K:
+ * keys device uint8 [q][m][C], keys[i][r][c] = bit field [mu*c, mu*c+mu) of
+ * packed row (i, r).  For checking indices bit for bit against a reference.
+ */
+biq_status biq_unpack_keys(const uint8_t* K, uint8_t* keys, int m, int n, int q, int mu, void* stream);
+
+/*
+ * Table construction (Sec. III-B, q_alpha^beta = M_mu . x_alpha^beta; Algorithm 1):
+ * LUT[c][k][a] = sum_j s_j(k) * X[a][mu*c + j], s_j(k) = +1 if bit j of k is set
+ * else -1, elements past column n count as 0.  fp32.  LUT[c][~k][a] = -LUT[c][k][a]
+ * holds bit for bit.  X device [batch][n] -> LUT device [C][2^mu][batch].
+ */
+biq_status biq_build_lut(const float* X, float* LUT, int n, int batch, int mu, void* stream);
+
+/*
+ * Query (Algorithm 2 lines 4-6 + Eq. 2): Y[a][r] = sum_i alpha[i][r] *
+ * sum_c LUT[c][key(i,r,c)][a], with the tables read from device memory.
+ * workspace: device, >= biq_workspace_bytes(...) bytes, 16-byte aligned (may be
+ * NULL when that size is 0); contents undefined afterwards.
+ */
+biq_status biq_query(const uint8_t* K, const float* alpha, const float* LUT, float* Y,
+                     int m, int n, int q, int batch, int mu,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The fused multiply (Algorithm 2 as a whole + Eq. 2): tables are built on the
+ * fly in LDS from X and never written to device memory (Sec. III-B: "not taken
+ * from DRAM"), keys are streamed once, partial sums are combined in a fixed
+ * order (deterministic: same inputs, same bits).
+ */
+biq_status biq_gemm(const uint8_t* K, const float* alpha, const float* X, float* Y,
+                    int m, int n, int q, int batch, int mu,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* biq_gemm with a caller-supplied plan; BIQ_EINVAL if the plan is inconsistent
+ * with the shape or exceeds device limits. */
+biq_status biq_gemm_ex(const uint8_t* K, const float* alpha, const float* X, float* Y,
+                       int m, int n, int q, int batch, int mu, const biq_plan* plan,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BIQ_H_ */

@@ -1,0 +1,354 @@
+// C ABI of libbiq (see include/biq.h): argument checks, launch planning, launches.
+#include "biq.h"
+
+#include <hip/hip_runtime.h>
+
+#include "biq_kernels.h"
+
+namespace {
+
+using namespace biq;
+
+// gfx950 (MI355X) limits the planner is written for.
+constexpr int kLdsPerCu = 160 * 1024;
+constexpr int kLdsTableBudget = 128 * 1024;  // tables of one tile (leaves room for 1 WG/CU extras)
+constexpr int kNumCu = 256;
+constexpr int kNumXcd = 8;
+
+enum KernelId { KERNEL_GENERIC = 0, KERNEL_COUNT };
+
+inline bool shape_ok(int m, int n, int q, int batch, int mu) {
+    if (m < 1 || n < 1 || q < 1 || batch < 1) return false;
+    if (mu < 1 || mu > 8) return false;
+    if ((long long)m * q >= (1ll << 31)) return false;
+    return true;
+}
+
+inline int unit_keys(int mu) {
+    switch (mu) {
+        case 8: return KeyUnit<8>::UK; case 7: return KeyUnit<7>::UK; case 6: return KeyUnit<6>::UK;
+        case 5: return KeyUnit<5>::UK; case 4: return KeyUnit<4>::UK; case 3: return KeyUnit<3>::UK;
+        case 2: return KeyUnit<2>::UK; default: return KeyUnit<1>::UK;
+    }
+}
+
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
+
+inline int plan_lds_bytes(const biq_plan& pl, int mu) {
+    long long b = (long long)pl.chunks_per_tile * (1 << mu) * pl.batch_tile * 4;
+    if (pl.tiles_per_split > 1) b += (long long)pl.rows_per_wg * pl.batch_tile * 4;
+    return b > (1ll << 30) ? (1 << 30) : (int)b;
+}
+
+// Completes the derived fields and checks a plan against the shape and device limits.
+bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
+    (void)q;
+    const int UK = unit_keys(mu);
+    const int C = ceil_div(n, mu);
+    if (pl.kernel != KERNEL_GENERIC) return false;
+    if (pl.threads < 64 || pl.threads > 1024 || pl.threads % 64) return false;
+    if (pl.batch_tile != 1 && pl.batch_tile != 2 && pl.batch_tile != 4 && pl.batch_tile != 8) return false;
+    if (pl.chunks_per_tile < UK || pl.chunks_per_tile % UK) return false;
+    const int G = pl.chunks_per_tile / UK;
+    if (G > 64 || (G & (G - 1))) return false;
+    if (pl.rows_per_wg < 1 || pl.tiles_per_split < 1) return false;
+    const int tiles = ceil_div(C, pl.chunks_per_tile);
+    if (pl.tiles_per_split > tiles) pl.tiles_per_split = tiles;
+    pl.chunk_splits = ceil_div(tiles, pl.tiles_per_split);
+    pl.row_blocks = ceil_div(m, pl.rows_per_wg);
+    pl.batch_tiles = ceil_div(batch, pl.batch_tile);
+    pl.lds_bytes = plan_lds_bytes(pl, mu);
+    if (pl.lds_bytes > kLdsPerCu) return false;
+    const long long tasks = (long long)pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
+    if (tasks > (1ll << 30)) return false;
+    return true;
+}
+
+// Default mapping.  Algorithm 2 leaves the tile sizes open; the choices here are:
+//  - batch tile: as many input vectors as one lookup can serve with a single wide LDS read
+//  - tile width: the largest power-of-two number of key units whose tables fit the LDS budget
+//  - chunk splits: bounded so that the partial sums written stay below about twice the
+//    bytes the method has to move anyway
+//  - rows per workgroup: enough workgroups to fill the 256 CUs several times over
+void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu) {
+    const int UK = unit_keys(mu);
+    const int C = ceil_div(n, mu);
+    const int E = 1 << mu;
+    pl = biq_plan{};
+    pl.kernel = KERNEL_GENERIC;
+    pl.batch_tile = batch >= 5 ? 8 : batch >= 3 ? 4 : batch;
+    // widest tile: G units, G a power of two, tables within the budget, no wider than the row
+    int G = 1;
+    while (G < 64 && (long long)(2 * G) * UK * E * pl.batch_tile * 4 <= kLdsTableBudget &&
+           G * UK < C)
+        G *= 2;
+    pl.chunks_per_tile = G * UK;
+    const int tiles = ceil_div(C, pl.chunks_per_tile);
+    pl.threads = 256;
+    const int groups = pl.threads / G;
+    const int batch_tiles = ceil_div(batch, pl.batch_tile);
+    // chunk splits
+    const long long algo_bytes = (long long)q * m * ((n + 7) / 8) + 4ll * q * m + 4ll * n * batch +
+                                 4ll * m * batch;
+    long long max_splits = (2 * algo_bytes) / (4ll * m * batch);
+    if (max_splits < 1) max_splits = 1;
+    int splits = tiles < max_splits ? tiles : (int)max_splits;
+    pl.tiles_per_split = ceil_div(tiles, splits);
+    splits = ceil_div(tiles, pl.tiles_per_split);
+    // rows per workgroup: aim at >= 8 workgroups per CU while each keeps >= 1 row iteration
+    const long long row_iters = ceil_div(m, groups);
+    const long long want_wgs = 8ll * kNumCu;
+    long long k = (row_iters * splits * batch_tiles) / want_wgs;
+    if (k < 1) k = 1;
+    if (k > 64) k = 64;
+    pl.rows_per_wg = (int)(k * groups);
+    plan_finish(pl, m, n, q, batch, mu);
+}
+
+size_t plan_workspace(const biq_plan& pl, int m, int batch) {
+    return pl.chunk_splits > 1 ? (size_t)pl.chunk_splits * batch * m * sizeof(float) : 0;
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+template <int MU, int BT, bool FUSED>
+hipError_t launch_query_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    auto kern = query_kernel<MU, BT, FUSED>;
+    if (lds > 48 * 1024) {
+        // opt in to large dynamic LDS once per instantiation (attribute is per function)
+        static int granted = 0;
+        if (lds > granted) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+            if (e != hipSuccess) return e;
+            granted = kLdsPerCu;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
+    return hipGetLastError();
+}
+
+template <int MU, bool FUSED>
+hipError_t launch_query_bt(int bt, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    switch (bt) {
+        case 1: return launch_query_inst<MU, 1, FUSED>(qp, grid, threads, lds, s);
+        case 2: return launch_query_inst<MU, 2, FUSED>(qp, grid, threads, lds, s);
+        case 4: return launch_query_inst<MU, 4, FUSED>(qp, grid, threads, lds, s);
+        default: return launch_query_inst<MU, 8, FUSED>(qp, grid, threads, lds, s);
+    }
+}
+
+template <bool FUSED>
+hipError_t launch_query_mu(int mu, int bt, const QueryParams& qp, int grid, int threads, int lds,
+                           hipStream_t s) {
+    switch (mu) {
+        case 1: return launch_query_bt<1, FUSED>(bt, qp, grid, threads, lds, s);
+        case 2: return launch_query_bt<2, FUSED>(bt, qp, grid, threads, lds, s);
+        case 3: return launch_query_bt<3, FUSED>(bt, qp, grid, threads, lds, s);
+        case 4: return launch_query_bt<4, FUSED>(bt, qp, grid, threads, lds, s);
+        case 5: return launch_query_bt<5, FUSED>(bt, qp, grid, threads, lds, s);
+        case 6: return launch_query_bt<6, FUSED>(bt, qp, grid, threads, lds, s);
+        case 7: return launch_query_bt<7, FUSED>(bt, qp, grid, threads, lds, s);
+        default: return launch_query_bt<8, FUSED>(bt, qp, grid, threads, lds, s);
+    }
+}
+
+biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const float* X,
+                     const float* LUT, float* Y, int m, int n, int q, int batch, int mu,
+                     const biq_plan* user_plan, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+    if (!shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
+    if (!K || !alpha || !Y || (fused ? !X : !LUT)) return BIQ_EINVAL;
+    if (!aligned(K, 16) || !aligned(alpha, 4) || !aligned(Y, 4) || !aligned(fused ? X : LUT, 4))
+        return BIQ_EINVAL;
+    biq_plan pl;
+    if (user_plan) {
+        pl = *user_plan;
+        if (!plan_finish(pl, m, n, q, batch, mu)) return BIQ_EINVAL;
+    } else {
+        plan_default(pl, m, n, q, batch, mu);
+    }
+    const size_t need = plan_workspace(pl, m, batch);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return BIQ_EWORKSPACE;
+        if (!aligned(workspace, 16)) return BIQ_EINVAL;
+    }
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    QueryParams qp{};
+    qp.K = reinterpret_cast<const uint32_t*>(K);
+    qp.alpha = alpha;
+    qp.X = X;
+    qp.LUT = LUT;
+    qp.out = pl.chunk_splits > 1 ? reinterpret_cast<float*>(workspace) : Y;
+    qp.m = m; qp.n = n; qp.q = q; qp.batch = batch;
+    qp.stride_dw = (int)(biq_key_row_stride(n) / 4);
+    qp.C = ceil_div(n, mu);
+    qp.CT = pl.chunks_per_tile;
+    qp.G = pl.chunks_per_tile / unit_keys(mu);
+    qp.log2G = ilog2(qp.G);
+    qp.tiles = ceil_div(qp.C, qp.CT);
+    qp.tps = pl.tiles_per_split;
+    qp.splits = pl.chunk_splits;
+    qp.rows_per_wg = pl.rows_per_wg;
+    qp.row_blocks = pl.row_blocks;
+    qp.batch_tiles = pl.batch_tiles;
+    qp.ntasks = pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
+    qp.tasks_per_xcd = ceil_div(qp.ntasks, kNumXcd);
+    const int grid = qp.tasks_per_xcd * kNumXcd;
+
+    hipError_t e = fused ? launch_query_mu<true>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s)
+                         : launch_query_mu<false>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s);
+    if (e != hipSuccess) return BIQ_EHIP;
+    if (pl.chunk_splits > 1) {
+        const long long count = (long long)batch * m;
+        hipLaunchKernelGGL(reduce_splits_kernel, dim3(ceil_div(count, 256)), dim3(256), 0, s,
+                           reinterpret_cast<const float*>(workspace), Y, count, pl.chunk_splits);
+        if (hipGetLastError() != hipSuccess) return BIQ_EHIP;
+    }
+    return BIQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* biq_status_str(biq_status status) {
+    switch (status) {
+        case BIQ_OK: return "ok";
+        case BIQ_EINVAL: return "invalid argument";
+        case BIQ_EUNSUPPORTED: return "unsupported request";
+        case BIQ_EWORKSPACE: return "workspace too small";
+        case BIQ_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int biq_version(void) { return 100; }
+
+size_t biq_key_row_stride(int n) { return n < 1 ? 0 : (size_t)((n + 127) / 128) * 16; }
+
+size_t biq_packed_bytes(int m, int n, int q) {
+    if (m < 1 || n < 1 || q < 1) return 0;
+    return (size_t)q * m * biq_key_row_stride(n);
+}
+
+size_t biq_num_chunks(int n, int mu) {
+    if (n < 1 || mu < 1 || mu > 8) return 0;
+    return (size_t)((n + mu - 1) / mu);
+}
+
+size_t biq_lut_bytes(int n, int batch, int mu) {
+    if (n < 1 || batch < 1 || mu < 1 || mu > 8) return 0;
+    return biq_num_chunks(n, mu) * ((size_t)1 << mu) * batch * sizeof(float);
+}
+
+biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan) {
+    if (!plan || !shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
+    plan_default(*plan, m, n, q, batch, mu);
+    return BIQ_OK;
+}
+
+size_t biq_plan_workspace_bytes(const biq_plan* plan, int m, int batch) {
+    if (!plan || m < 1 || batch < 1) return 0;
+    return plan_workspace(*plan, m, batch);
+}
+
+size_t biq_workspace_bytes(int m, int n, int q, int batch, int mu) {
+    if (!shape_ok(m, n, q, batch, mu)) return 0;
+    biq_plan pl;
+    plan_default(pl, m, n, q, batch, mu);
+    return plan_workspace(pl, m, batch);
+}
+
+const char* biq_kernel_name(int kernel) {
+    switch (kernel) {
+        case KERNEL_GENERIC: return "query_generic";
+    }
+    return "unknown";
+}
+
+biq_status biq_pack(const int8_t* B, uint8_t* K, int m, int n, int q, int mu, void* stream) {
+    if (!shape_ok(m, n, q, 1, mu) || !B || !K) return BIQ_EINVAL;
+    if (!aligned(K, 16)) return BIQ_EINVAL;
+    const long long key_rows = (long long)q * m;
+    const int stride_dw = (int)(biq_key_row_stride(n) / 4);
+    const long long total = key_rows * stride_dw;
+    if (total > (1ll << 38)) return BIQ_EUNSUPPORTED;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    if (n % 16 == 0 && aligned(B, 16))
+        hipLaunchKernelGGL(pack_kernel<true>, dim3(grid), dim3(256), 0, s, B,
+                           reinterpret_cast<uint32_t*>(K), key_rows, n, stride_dw);
+    else
+        hipLaunchKernelGGL(pack_kernel<false>, dim3(grid), dim3(256), 0, s, B,
+                           reinterpret_cast<uint32_t*>(K), key_rows, n, stride_dw);
+    return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
+}
+
+biq_status biq_unpack_keys(const uint8_t* K, uint8_t* keys, int m, int n, int q, int mu, void* stream) {
+    if (!shape_ok(m, n, q, 1, mu) || !K || !keys) return BIQ_EINVAL;
+    if (!aligned(K, 16)) return BIQ_EINVAL;
+    const long long key_rows = (long long)q * m;
+    const int stride_dw = (int)(biq_key_row_stride(n) / 4);
+    const int C = ceil_div(n, mu);
+    const int units = ceil_div(C, unit_keys(mu));
+    const long long total = key_rows * units;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    const uint32_t* Kd = reinterpret_cast<const uint32_t*>(K);
+#define BIQ_UNPACK_CASE(MU)                                                                       \
+    case MU:                                                                                      \
+        hipLaunchKernelGGL(unpack_keys_kernel<MU>, dim3(grid), dim3(256), 0, s, Kd, keys, key_rows, \
+                           C, stride_dw);                                                         \
+        break;
+    switch (mu) {
+        BIQ_UNPACK_CASE(1) BIQ_UNPACK_CASE(2) BIQ_UNPACK_CASE(3) BIQ_UNPACK_CASE(4)
+        BIQ_UNPACK_CASE(5) BIQ_UNPACK_CASE(6) BIQ_UNPACK_CASE(7) BIQ_UNPACK_CASE(8)
+    }
+#undef BIQ_UNPACK_CASE
+    return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
+}
+
+biq_status biq_build_lut(const float* X, float* LUT, int n, int batch, int mu, void* stream) {
+    if (!shape_ok(1, n, 1, batch, mu) || !X || !LUT) return BIQ_EINVAL;
+    if (!aligned(X, 4) || !aligned(LUT, 4)) return BIQ_EINVAL;
+    const int C = ceil_div(n, mu);
+    const int HG = mu > 4 ? (1 << (mu - 4)) : 1;
+    const long long total = (long long)C * HG * batch;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const unsigned grid = (unsigned)((total + 255) / 256);
+#define BIQ_LUT_CASE(MU)                                                                          \
+    case MU:                                                                                      \
+        hipLaunchKernelGGL(build_lut_kernel<MU>, dim3(grid), dim3(256), 0, s, X, LUT, n, batch, C); \
+        break;
+    switch (mu) {
+        BIQ_LUT_CASE(1) BIQ_LUT_CASE(2) BIQ_LUT_CASE(3) BIQ_LUT_CASE(4)
+        BIQ_LUT_CASE(5) BIQ_LUT_CASE(6) BIQ_LUT_CASE(7) BIQ_LUT_CASE(8)
+    }
+#undef BIQ_LUT_CASE
+    return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
+}
+
+biq_status biq_query(const uint8_t* K, const float* alpha, const float* LUT, float* Y, int m, int n,
+                     int q, int batch, int mu, void* workspace, size_t workspace_bytes, void* stream) {
+    return run_query(false, K, alpha, nullptr, LUT, Y, m, n, q, batch, mu, nullptr, workspace,
+                     workspace_bytes, stream);
+}
+
+biq_status biq_gemm(const uint8_t* K, const float* alpha, const float* X, float* Y, int m, int n,
+                    int q, int batch, int mu, void* workspace, size_t workspace_bytes, void* stream) {
+    return run_query(true, K, alpha, X, nullptr, Y, m, n, q, batch, mu, nullptr, workspace,
+                     workspace_bytes, stream);
+}
+
+biq_status biq_gemm_ex(const uint8_t* K, const float* alpha, const float* X, float* Y, int m, int n,
+                       int q, int batch, int mu, const biq_plan* plan, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+    if (!plan) return BIQ_EINVAL;
+    return run_query(true, K, alpha, X, nullptr, Y, m, n, q, batch, mu, plan, workspace,
+                     workspace_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,114 @@
+// Shared device-side definitions of libbiq (gfx950 only).
+//
+// Key stream: a packed row is a little-endian bit string; the key of chunk c for
+// LUT-unit MU is bits [MU*c, MU*c + MU) (paper Sec. III-B; element j <-> bit j as in
+// Algorithms 1 and 3).  A lane always handles a "unit": UD consecutive dwords holding
+// UK whole keys, so that no key straddles two lanes.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace biq {
+
+constexpr int kWave = 64;
+
+template <int MU> struct KeyUnit;
+// 16-byte units where MU divides 32 ...
+template <> struct KeyUnit<8> { static constexpr int UD = 4, UK = 16; };
+template <> struct KeyUnit<4> { static constexpr int UD = 4, UK = 32; };
+template <> struct KeyUnit<2> { static constexpr int UD = 4, UK = 64; };
+template <> struct KeyUnit<1> { static constexpr int UD = 4, UK = 128; };
+// ... and the shortest run of whole dwords that holds whole keys otherwise
+template <> struct KeyUnit<6> { static constexpr int UD = 3, UK = 16; };
+template <> struct KeyUnit<3> { static constexpr int UD = 3, UK = 32; };
+template <> struct KeyUnit<5> { static constexpr int UD = 5, UK = 32; };
+template <> struct KeyUnit<7> { static constexpr int UD = 7, UK = 32; };
+
+// Key t (compile-time position) of a unit held in w[0..UD).
+template <int MU, int T, int UD>
+__device__ __forceinline__ uint32_t unit_key(const uint32_t (&w)[UD]) {
+    constexpr int bit = T * MU;
+    constexpr int d = bit >> 5;
+    constexpr int s = bit & 31;
+    constexpr uint32_t mask = (1u << MU) - 1u;
+    if constexpr (s + MU <= 32) {
+        return __builtin_amdgcn_ubfe(w[d], s, MU);
+    } else {
+        // key straddles dwords d and d+1
+        return __builtin_amdgcn_alignbit(w[d + 1], w[d], s) & mask;
+    }
+}
+
+// Loads the UD dwords of a unit starting at dword index dw0 of a packed row;
+// dwords at or past the row stride read as 0 (their chunks do not exist).
+template <int UD>
+__device__ __forceinline__ void load_unit(const uint32_t* __restrict__ row, int dw0, int stride_dw,
+                                          uint32_t (&w)[UD]) {
+    if constexpr (UD == 4) {
+        // stride is a multiple of 4 dwords and dw0 a multiple of 4: all or nothing
+        if (dw0 < stride_dw) {
+            const uint4 v = *reinterpret_cast<const uint4*>(row + dw0);
+            w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+        } else {
+            w[0] = w[1] = w[2] = w[3] = 0u;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < UD; ++i) w[i] = (dw0 + i < stride_dw) ? row[dw0 + i] : 0u;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Table entries.  For one chunk x[0..8) (elements past MU or past column n are 0) the
+// entry of key k = 16*h + l is  lo(l) + hi(h)  with
+//   lo(l) = (s0 x0 + s1 x1) + (s2 x2 + s3 x3),  hi(h) = (s4 x4 + s5 x5) + (s6 x6 + s7 x7),
+// s_j = +1 if bit j of k is set else -1 (paper: q = M_mu . x).  Every partial is formed
+// from a pair and its exact negation, so entry(~k) = -entry(k) holds bit for bit, the
+// property Algorithm 1 obtains by copying negated entries.
+// ---------------------------------------------------------------------------------
+struct PairSums {
+    float a[4];  // a[s] = (s&1 ? x0 : -x0) + (s&2 ? x1 : -x1)
+};
+
+__device__ __forceinline__ PairSums pair_sums(float x0, float x1) {
+    PairSums p;
+    const float s = x0 + x1, d = x0 - x1;
+    p.a[0] = -s; p.a[1] = d; p.a[2] = -d; p.a[3] = s;
+    return p;
+}
+
+__device__ __forceinline__ float pair_pick(const PairSums& p, uint32_t s) {
+    // branch-free select of p.a[s], s in 0..3
+    const float lo = (s & 1u) ? p.a[1] : p.a[0];
+    const float hi = (s & 1u) ? p.a[3] : p.a[2];
+    return (s & 2u) ? hi : lo;
+}
+
+// hi(h) for h in 0..15
+__device__ __forceinline__ float table_hi(const float (&x)[8], uint32_t h) {
+    const PairSums c = pair_sums(x[4], x[5]);
+    const PairSums d = pair_sums(x[6], x[7]);
+    return pair_pick(c, h & 3u) + pair_pick(d, h >> 2);
+}
+
+// lo(l) for all l in 0..15
+__device__ __forceinline__ void table_lo(const float (&x)[8], float (&lo)[16]) {
+    const PairSums a = pair_sums(x[0], x[1]);
+    const PairSums b = pair_sums(x[2], x[3]);
+#pragma unroll
+    for (int l = 0; l < 16; ++l) lo[l] = a.a[l & 3] + b.a[l >> 2];
+}
+
+// x[j] = X[col][MU*c + j] for j < MU and inside the row, else 0
+template <int MU>
+__device__ __forceinline__ void load_chunk_x(const float* __restrict__ X, int n, int batch, int col,
+                                             int c, float (&x)[8]) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int e = MU * c + j;
+        x[j] = (j < MU && col < batch && e < n) ? X[(size_t)col * n + e] : 0.0f;
+    }
+}
+
+}  // namespace biq

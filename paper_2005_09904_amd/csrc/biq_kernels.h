@@ -1,0 +1,291 @@
+// Kernels of libbiq (gfx950): key packing, table construction, LUT query.
+#pragma once
+
+#include "biq_common.h"
+
+namespace biq {
+
+// =====================================================================================
+// biq_pack: B int8 [q*m][n] (+1/-1) -> packed sign bit stream [q*m][stride] (Sec. III-B).
+// One thread per output dword (32 weights).  bit = (B > 0).
+// =====================================================================================
+__device__ __forceinline__ uint32_t sign_bits4(uint32_t w) {
+    // w holds four int8; returns a 4-bit mask, bit i = (byte i > 0)
+    const uint32_t nonzero = ((w & 0x7f7f7f7fu) + 0x7f7f7f7fu) | w;  // bit 7 of each byte
+    const uint32_t pos = (nonzero & ~w & 0x80808080u) >> 7;          // bit 0 of each byte
+    return (pos * 0x01020408u) >> 24;                                // gather to bits 0..3
+}
+
+template <bool ALIGNED16>
+__global__ __launch_bounds__(256) void pack_kernel(const int8_t* __restrict__ B,
+                                                   uint32_t* __restrict__ K, long long key_rows,
+                                                   int n, int stride_dw) {
+    const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = key_rows * stride_dw;
+    if (gid >= total) return;
+    const long long kr = gid / stride_dw;
+    const int dw = (int)(gid - kr * stride_dw);
+    const int col0 = dw * 32;
+    const int8_t* row = B + kr * (long long)n;
+    uint32_t bits = 0;
+    if (ALIGNED16 && col0 + 32 <= n) {
+        // n % 16 == 0 and B 16-byte aligned: two 128-bit loads
+        const uint4 v0 = *reinterpret_cast<const uint4*>(row + col0);
+        const uint4 v1 = *reinterpret_cast<const uint4*>(row + col0 + 16);
+        bits = sign_bits4(v0.x) | (sign_bits4(v0.y) << 4) | (sign_bits4(v0.z) << 8) |
+               (sign_bits4(v0.w) << 12) | (sign_bits4(v1.x) << 16) | (sign_bits4(v1.y) << 20) |
+               (sign_bits4(v1.z) << 24) | (sign_bits4(v1.w) << 28);
+    } else {
+        for (int j = 0; j < 32; ++j) {
+            const int col = col0 + j;
+            if (col < n && row[col] > 0) bits |= 1u << j;
+        }
+    }
+    K[gid] = bits;
+}
+
+// =====================================================================================
+// biq_unpack_keys: the table indices as the query kernels extract them.
+// One thread per (key row, unit); keys uint8 [q*m][C].
+// =====================================================================================
+template <int MU, int T>
+__device__ __forceinline__ void store_unit_keys(const uint32_t (&w)[KeyUnit<MU>::UD], uint8_t* dst,
+                                                int c0, int C) {
+    if constexpr (T < KeyUnit<MU>::UK) {
+        if (c0 + T < C) dst[c0 + T] = (uint8_t)unit_key<MU, T>(w);
+        store_unit_keys<MU, T + 1>(w, dst, c0, C);
+    }
+}
+
+template <int MU>
+__global__ __launch_bounds__(256) void unpack_keys_kernel(const uint32_t* __restrict__ K,
+                                                          uint8_t* __restrict__ keys,
+                                                          long long key_rows, int C, int stride_dw) {
+    constexpr int UD = KeyUnit<MU>::UD, UK = KeyUnit<MU>::UK;
+    const int units = (C + UK - 1) / UK;
+    const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= key_rows * units) return;
+    const long long kr = gid / units;
+    const int u = (int)(gid - kr * units);
+    uint32_t w[UD];
+    load_unit<UD>(K + kr * stride_dw, u * UD, stride_dw, w);
+    store_unit_keys<MU, 0>(w, keys + kr * C, u * UK, C);
+}
+
+// =====================================================================================
+// biq_build_lut: X [batch][n] -> LUT [C][2^MU][batch] in device memory (Sec. III-B).
+// One thread per (chunk, input vector, group of 16 keys).
+// =====================================================================================
+template <int MU>
+__global__ __launch_bounds__(256) void build_lut_kernel(const float* __restrict__ X,
+                                                        float* __restrict__ LUT, int n, int batch,
+                                                        int C) {
+    constexpr int E = 1 << MU;
+    constexpr int HG = (MU > 4) ? (1 << (MU - 4)) : 1;  // groups of 16 keys per table
+    constexpr int LN = (MU > 4) ? 16 : E;               // keys per group
+    const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)C * HG * batch;
+    if (gid >= total) return;
+    const int a = (int)(gid % batch);
+    const long long rest = gid / batch;
+    const int h = (int)(rest % HG);
+    const int c = (int)(rest / HG);
+    float x[8], lo[16];
+    load_chunk_x<MU>(X, n, batch, a, c, x);
+    table_lo(x, lo);
+    const float hi = table_hi(x, (uint32_t)h);
+    float* dst = LUT + ((size_t)c * E + (size_t)h * 16) * batch + a;
+#pragma unroll
+    for (int l = 0; l < LN; ++l) dst[(size_t)l * batch] = lo[l] + hi;
+}
+
+// =====================================================================================
+// Query / fused multiply (Algorithm 2 + Eq. 2), generic over MU and the batch tile BT.
+//
+// A workgroup owns rows [r0, r0 + rows_per_wg) (all q planes), input vectors
+// [b0, b0 + BT) and the LUT tiles [sp*tps, (sp+1)*tps).  For each tile it fills LDS with
+// the tables of CT chunks (built from X when FUSED, copied from device memory otherwise),
+// then streams its key rows: a group of G = CT/UK lanes covers one row's segment, each
+// lane looks its UK keys up, the plane sums are scaled by alpha and added, and the G lanes
+// are reduced.  LDS table layout: [chunk in tile][key][BT].
+// =====================================================================================
+struct QueryParams {
+    const uint32_t* K;
+    const float* alpha;
+    const float* X;    // FUSED: [batch][n]
+    const float* LUT;  // !FUSED: [C][2^MU][batch]
+    float* out;        // Y [batch][m] if splits == 1, else partial sums [splits][batch][m]
+    int m, n, q, batch;
+    int stride_dw, C;
+    int CT, G, log2G;
+    int tiles, tps, splits;
+    int rows_per_wg, row_blocks, batch_tiles;
+    int ntasks, tasks_per_xcd;
+};
+
+template <int MU, int BT, int T>
+__device__ __forceinline__ void lookup_unit(const uint32_t (&w)[KeyUnit<MU>::UD],
+                                            const float* __restrict__ tab, float (&acc)[BT]) {
+    // tab points at the table of this lane's first chunk
+    if constexpr (T < KeyUnit<MU>::UK) {
+        constexpr int E = 1 << MU;
+        const uint32_t key = unit_key<MU, T>(w);
+        const float* p = tab + ((size_t)T * E + key) * BT;
+        if constexpr (BT == 1) {
+            acc[0] += p[0];
+        } else if constexpr (BT == 2) {
+            const float2 v = *reinterpret_cast<const float2*>(p);
+            acc[0] += v.x; acc[1] += v.y;
+        } else {
+#pragma unroll
+            for (int c4 = 0; c4 < BT / 4; ++c4) {
+                const float4 v = *reinterpret_cast<const float4*>(p + 4 * c4);
+                acc[4 * c4 + 0] += v.x; acc[4 * c4 + 1] += v.y;
+                acc[4 * c4 + 2] += v.z; acc[4 * c4 + 3] += v.w;
+            }
+        }
+        lookup_unit<MU, BT, T + 1>(w, tab, acc);
+    }
+}
+
+template <int MU, int BT, bool FUSED>
+__global__ __launch_bounds__(1024) void query_kernel(const QueryParams p) {
+    constexpr int E = 1 << MU;
+    constexpr int UD = KeyUnit<MU>::UD, UK = KeyUnit<MU>::UK;
+    extern __shared__ __align__(16) float lds[];
+
+    // XCD-aware task order: consecutive workgroup ids go to different XCDs, so give each
+    // XCD a contiguous range of tasks; tasks that differ only in the batch tile read the
+    // same keys and stay on one XCD's L2.
+    const int wg = blockIdx.x;
+    const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
+    if (task >= p.ntasks) return;
+    const int bt = task % p.batch_tiles;
+    const int rest = task / p.batch_tiles;
+    const int sp = rest % p.splits;
+    const int rb = rest / p.splits;
+
+    const int b0 = bt * BT;
+    const int r0 = rb * p.rows_per_wg;
+    const int r1 = min(p.m, r0 + p.rows_per_wg);
+    const int tile0 = sp * p.tps;
+    const int tile1 = min(p.tiles, tile0 + p.tps);
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int G = p.G;
+    const int L = tid & (G - 1);       // lane inside the row group
+    const int grp = tid >> p.log2G;    // row group inside the workgroup
+    const int ngrp = nthreads >> p.log2G;
+
+    float* tables = lds;                                  // [CT][E][BT]
+    float* yacc = lds + (size_t)p.CT * E * BT;            // [rows_per_wg][BT], only if tps > 1
+    const bool multi = (tile1 - tile0) > 1;
+
+    if (multi) {
+        for (int i = tid; i < p.rows_per_wg * BT; i += nthreads) yacc[i] = 0.0f;
+    }
+
+    for (int tile = tile0; tile < tile1; ++tile) {
+        const int c0 = tile * p.CT;
+        __syncthreads();  // previous tile's readers are done (also orders the yacc init)
+        if constexpr (FUSED) {
+            constexpr int HG = (MU > 4) ? (1 << (MU - 4)) : 1;
+            constexpr int LN = (MU > 4) ? 16 : E;
+            const int jobs = p.CT * BT * HG;
+            for (int job = tid; job < jobs; job += nthreads) {
+                const int col = job % BT;
+                const int r2 = job / BT;
+                const int h = r2 % HG;
+                const int ct = r2 / HG;
+                float x[8], lo[16];
+                load_chunk_x<MU>(p.X, p.n, p.batch, b0 + col, c0 + ct, x);
+                table_lo(x, lo);
+                const float hi = table_hi(x, (uint32_t)h);
+                float* dst = tables + ((size_t)ct * E + h * 16) * BT + col;
+                if constexpr (BT == 1 && LN >= 4) {
+#pragma unroll
+                    for (int l4 = 0; l4 < LN / 4; ++l4)
+                        *reinterpret_cast<float4*>(dst + 4 * l4) =
+                            make_float4(lo[4 * l4] + hi, lo[4 * l4 + 1] + hi, lo[4 * l4 + 2] + hi,
+                                        lo[4 * l4 + 3] + hi);
+                } else {
+#pragma unroll
+                    for (int l = 0; l < LN; ++l) dst[l * BT] = lo[l] + hi;
+                }
+            }
+        } else {
+            const int entries = p.CT * E * BT;
+            for (int e = tid; e < entries; e += nthreads) {
+                const int col = e % BT;
+                const int ck = e / BT;  // ct*E + key
+                const int c = c0 + ck / E;
+                float v = 0.0f;
+                if (c < p.C && b0 + col < p.batch)
+                    v = p.LUT[((size_t)c0 * E + ck) * p.batch + b0 + col];
+                tables[e] = v;
+            }
+        }
+        __syncthreads();
+
+        const int dw0 = (c0 / UK) * UD + L * UD;  // this lane's unit inside a packed row
+        const float* tab = tables + (size_t)L * UK * E * BT;
+        for (int r = r0 + grp; r < r1; r += ngrp) {
+            float y[BT];
+#pragma unroll
+            for (int c = 0; c < BT; ++c) y[c] = 0.0f;
+            for (int i = 0; i < p.q; ++i) {
+                const size_t kr = (size_t)i * p.m + r;
+                uint32_t w[UD];
+                load_unit<UD>(p.K + kr * p.stride_dw, dw0, p.stride_dw, w);
+                float acc[BT];
+#pragma unroll
+                for (int c = 0; c < BT; ++c) acc[c] = 0.0f;
+                lookup_unit<MU, BT, 0>(w, tab, acc);
+                const float al = p.alpha[kr];
+#pragma unroll
+                for (int c = 0; c < BT; ++c) y[c] = fmaf(al, acc[c], y[c]);
+            }
+            // reduce over the G lanes of the row group (G is a power of two <= 64)
+            for (int off = G >> 1; off > 0; off >>= 1) {
+#pragma unroll
+                for (int c = 0; c < BT; ++c) y[c] += __shfl_xor(y[c], off, kWave);
+            }
+            if (L == 0) {
+                if (multi) {
+                    float* ya = yacc + (size_t)(r - r0) * BT;
+#pragma unroll
+                    for (int c = 0; c < BT; ++c) ya[c] += y[c];
+                } else {
+#pragma unroll
+                    for (int c = 0; c < BT; ++c)
+                        if (b0 + c < p.batch)
+                            p.out[((size_t)sp * p.batch + b0 + c) * p.m + r] = y[c];
+                }
+            }
+        }
+    }
+
+    if (multi) {
+        __syncthreads();
+        const int rows = r1 - r0;
+        for (int i = tid; i < rows * BT; i += nthreads) {
+            const int c = i / rows, rr = i - c * rows;  // consecutive threads -> consecutive rows
+            if (b0 + c < p.batch)
+                p.out[((size_t)sp * p.batch + b0 + c) * p.m + r0 + rr] = yacc[(size_t)rr * BT + c];
+        }
+    }
+}
+
+// Sum of the chunk-split partials in a fixed order: Y[i] = sum_s partial[s][i].
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ partial,
+                                                            float* __restrict__ Y, long long count,
+                                                            int splits) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    float acc = partial[i];
+    for (int s = 1; s < splits; ++s) acc += partial[(size_t)s * count + i];
+    Y[i] = acc;
+}
+
+}  // namespace biq

@@ -1,0 +1,139 @@
+"""Host-side checks that need no GPU: the library loads, exports what include/biq.h declares,
+its size arithmetic and planner are consistent, and argument errors are reported as codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def biq():
+    import paper_2005_09904_amd as biq
+    from paper_2005_09904_amd import build
+
+    if build.is_stale():
+        build.build_library()
+    biq.load_library()
+    return biq
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "biq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(biq_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol(biq):
+    lib = biq.load_library()
+    declared = _declared_functions()
+    assert len(declared) >= 14
+    for name in declared:
+        assert hasattr(lib, name), "libbiq.so does not export %s" % name
+    from paper_2005_09904_amd.binding import EXPORTS
+    assert sorted(EXPORTS) == declared
+
+
+def test_plan_struct_matches_header(biq):
+    text = open(os.path.join(ROOT, "include", "biq.h")).read()
+    body = re.search(r"typedef struct \{(.*?)\} biq_plan;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"int\s+([a-z_]+)(?:\[(\d+)\])?\s*;", body)
+    mirror = [(n, getattr(t, "_length_", None)) for n, t in biq.BiqPlan._fields_]
+    assert [(n, int(l) if l else None) for n, l in fields] == mirror
+
+
+def test_size_arithmetic(biq):
+    assert biq.biq_key_row_stride(1) == 16
+    assert biq.biq_key_row_stride(128) == 16
+    assert biq.biq_key_row_stride(129) == 32
+    assert biq.biq_key_row_stride(4096) == 512
+    # Table II: 512x512 with 4/3/2 planes -> q*m*n/8 bytes
+    for q, nbytes in [(4, 131072), (3, 98304), (2, 65536)]:
+        assert biq.biq_packed_bytes(512, 512, q) == nbytes
+    assert biq.biq_num_chunks(4096, 6) == 683
+    assert biq.biq_num_chunks(4096, 8) == 512
+    assert biq.biq_lut_bytes(4096, 32, 8) == 16 * 1024 * 1024
+    assert biq.biq_lut_bytes(512, 1, 8) == 64 * 1024
+    # invalid arguments give 0, not garbage
+    assert biq.biq_key_row_stride(0) == 0
+    assert biq.biq_packed_bytes(0, 5, 1) == 0
+    assert biq.biq_num_chunks(10, 9) == 0
+    assert biq.biq_lut_bytes(10, 1, 0) == 0
+
+
+def test_status_strings(biq):
+    for code in (0, -1, -2, -3, -4):
+        assert biq.status_str(code)
+    assert biq.status_str(0) == "ok"
+    assert "unknown" in biq.status_str(-99)
+
+
+@pytest.mark.parametrize("mu", range(1, 9))
+def test_default_plans_are_consistent(biq, mu):
+    for (m, n, q, b) in [(1, 1, 1, 1), (512, 512, 1, 1), (2048, 2048, 2, 1), (4096, 1024, 3, 8),
+                         (4096, 4096, 3, 32), (16384, 4096, 2, 128), (4096, 16384, 2, 128),
+                         (1 << 20, 2048, 2, 1), (77, 100000, 1, 3)]:
+        p = biq.biq_plan_get(m, n, q, b, mu)
+        C = biq.biq_num_chunks(n, mu)
+        tiles = -(-C // p.chunks_per_tile)
+        assert p.threads % 64 == 0 and 64 <= p.threads <= 1024
+        assert p.batch_tile in (1, 2, 4, 8)
+        assert p.chunk_splits * p.tiles_per_split >= tiles
+        assert (p.chunk_splits - 1) * p.tiles_per_split < tiles
+        assert p.row_blocks * p.rows_per_wg >= m > (p.row_blocks - 1) * p.rows_per_wg
+        assert p.batch_tiles * p.batch_tile >= b
+        assert 0 < p.lds_bytes <= 160 * 1024
+        ws = biq.biq_workspace_bytes(m, n, q, b, mu)
+        assert ws == biq.biq_plan_workspace_bytes(p, m, b)
+        assert ws == (p.chunk_splits * b * m * 4 if p.chunk_splits > 1 else 0)
+        assert biq.biq_kernel_name(p.kernel) != "unknown"
+
+
+def test_argument_errors_are_reported_before_any_launch(biq):
+    lib = biq.load_library()
+    fake = 0x1000  # never dereferenced: every call below fails its argument checks first
+    assert lib.biq_pack(None, fake, 4, 4, 1, 8, None) == biq.BIQ_EINVAL
+    assert lib.biq_pack(fake, fake, 0, 4, 1, 8, None) == biq.BIQ_EINVAL
+    assert lib.biq_pack(fake, fake, 4, 4, 1, 9, None) == biq.BIQ_EINVAL
+    assert lib.biq_pack(fake, fake + 8, 4, 4, 1, 8, None) == biq.BIQ_EINVAL  # K not 16-byte aligned
+    assert lib.biq_unpack_keys(None, fake, 4, 4, 1, 8, None) == biq.BIQ_EINVAL
+    assert lib.biq_build_lut(fake, None, 4, 1, 8, None) == biq.BIQ_EINVAL
+    assert lib.biq_build_lut(fake, fake, 4, 0, 8, None) == biq.BIQ_EINVAL
+    assert lib.biq_gemm(None, fake, fake, fake, 4, 4, 1, 1, 8, None, 0, None) == biq.BIQ_EINVAL
+    assert lib.biq_gemm(fake, fake, fake, fake, 4, 4, 1, 1, 0, None, 0, None) == biq.BIQ_EINVAL
+    assert lib.biq_gemm(fake, fake, fake, fake, 4, 4, 0, 1, 8, None, 0, None) == biq.BIQ_EINVAL
+    assert lib.biq_gemm(fake, fake + 2, fake, fake, 4, 4, 1, 1, 8, None, 0, None) == biq.BIQ_EINVAL
+    assert lib.biq_query(fake, fake, None, fake, 4, 4, 1, 1, 8, None, 0, None) == biq.BIQ_EINVAL
+    # a shape whose default plan splits the chunks needs a workspace
+    m, n, q, b, mu = 2048, 2048, 2, 1, 8
+    need = biq.biq_workspace_bytes(m, n, q, b, mu)
+    if need:
+        assert lib.biq_gemm(fake, fake, fake, fake, m, n, q, b, mu, None, 0, None) == biq.BIQ_EWORKSPACE
+        assert lib.biq_gemm(fake, fake, fake, fake, m, n, q, b, mu, fake, need - 1, None) == biq.BIQ_EWORKSPACE
+    bad = biq.BiqPlan()
+    bad.threads, bad.chunks_per_tile, bad.batch_tile, bad.tiles_per_split, bad.rows_per_wg = 100, 16, 1, 1, 1
+    assert lib.biq_gemm_ex(fake, fake, fake, fake, 4, 4, 1, 1, 8, ctypes.byref(bad), None, 0, None) == biq.BIQ_EINVAL
+    bad.threads, bad.chunks_per_tile = 256, 24  # not a power-of-two number of units
+    assert lib.biq_gemm_ex(fake, fake, fake, fake, 4, 4, 1, 1, 8, ctypes.byref(bad), None, 0, None) == biq.BIQ_EINVAL
+    bad.chunks_per_tile, bad.batch_tile = 256, 8  # tables would not fit LDS
+    assert lib.biq_gemm_ex(fake, fake, fake, fake, 4, 4096, 1, 8, 8, ctypes.byref(bad), None, 0, None) == biq.BIQ_EINVAL
+    assert lib.biq_gemm_ex(fake, fake, fake, fake, 4, 4, 1, 1, 8, None, None, 0, None) == biq.BIQ_EINVAL
+
+
+def test_missing_library_fails_loudly(biq, tmp_path):
+    with pytest.raises(FileNotFoundError):
+        biq.load_library(str(tmp_path / "libbiq_missing.so"))
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2005_09904_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "biq_oracle" not in text, f

@@ -1,0 +1,252 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Keys and table indices bit-exact; fp32 outputs within the stated tolerance;
+bit-exact on inputs whose partial sums are all exactly representable."""
+import sys
+
+import numpy as np
+import pytest
+
+from gpu_util import assert_within_tolerance, device_inputs, gpu_gemm, gpu_pack
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def biq():
+    import torch
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2005_09904_amd as biq
+
+    biq.load_library()  # raises if the HIP library is missing: there is no fallback
+    return biq
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _rand_inputs(m, n, q, b, seed):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((b, n), dtype=np.float32)
+    B = (rng.integers(0, 2, size=(q, m, n), dtype=np.int8) * 2 - 1).astype(np.int8)
+    alpha = rng.uniform(0.05, 1.0, size=(q, m)).astype(np.float32)
+    return B, alpha, X
+
+
+RAGGED_SHAPES = [
+    # m, n, q, batch
+    (1, 1, 1, 1),
+    (3, 7, 1, 1),
+    (37, 100, 2, 1),
+    (64, 128, 1, 2),
+    (130, 1000, 3, 3),
+    (257, 2056, 2, 1),
+    (33, 4100, 1, 5),
+    (500, 300, 2, 8),
+    (70, 513, 3, 9),
+    (45, 1300, 2, 33),
+]
+
+
+@pytest.mark.parametrize("m,n,q,b", RAGGED_SHAPES)
+def test_pack_bit_exact(biq, oracle, m, n, q, b):
+    _say("pack m=%d n=%d q=%d" % (m, n, q))
+    B, _, _ = _rand_inputs(m, n, q, 1, 1000 + m + n)
+    import torch
+
+    K = gpu_pack(biq, torch.from_numpy(B).cuda())
+    torch.cuda.synchronize()
+    ref = oracle.pack_bitmap(B)
+    assert np.array_equal(K.cpu().numpy().reshape(ref.shape), ref)
+
+
+@pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_table_indices_bit_exact(biq, oracle, mu):
+    import torch
+
+    for (m, n, q) in [(5, 77, 2), (16, 1024, 1), (9, 4099, 1)]:
+        _say("unpack_keys mu=%d m=%d n=%d q=%d" % (mu, m, n, q))
+        B, _, _ = _rand_inputs(m, n, q, 1, 2000 + mu + n)
+        K = gpu_pack(biq, torch.from_numpy(B).cuda(), mu)
+        C = biq.biq_num_chunks(n, mu)
+        keys = torch.full((q, m, C), 0xEE, dtype=torch.uint8, device="cuda")
+        biq.biq_unpack_keys(K, keys, m, n, q, mu)
+        torch.cuda.synchronize()
+        assert np.array_equal(keys.cpu().numpy().astype(np.uint16), oracle.pack_keys(B, mu))
+
+
+@pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_build_lut_parity_and_antisymmetry(biq, oracle, mu):
+    import torch
+
+    for (n, b) in [(1, 1), (50, 3), (1024, 1), (333, 8)]:
+        _say("build_lut mu=%d n=%d b=%d" % (mu, n, b))
+        X = np.random.default_rng(3000 + mu + n).standard_normal((b, n), dtype=np.float32)
+        C = biq.biq_num_chunks(n, mu)
+        E = 1 << mu
+        assert biq.biq_lut_bytes(n, b, mu) == C * E * b * 4
+        LUT = torch.full((C, E, b), float("nan"), dtype=torch.float32, device="cuda")
+        biq.biq_build_lut(torch.from_numpy(X).cuda(), LUT, n, b, mu)
+        torch.cuda.synchronize()
+        got = LUT.cpu().numpy()
+        ref = oracle.build_lut(X, mu)
+        # fp32 pairwise tree of at most 8 terms: <= 3 roundings of partial sums
+        Xp = np.zeros((b, C * mu), dtype=np.float64)
+        Xp[:, :n] = np.abs(X)
+        l1 = Xp.reshape(b, C, mu).sum(axis=2).T  # [C][b]
+        assert np.all(np.abs(got - ref) <= 4 * 2.0 ** -24 * l1[:, None, :] + 1e-45)
+        # LUT[~k] = -LUT[k] exactly (Algorithm 1 builds the upper half by negation)
+        assert np.array_equal(got[:, ::-1, :], -got)
+
+
+CONFIG_NAMES = ["cfg1_fc512_b1", "cfg2_gemv2048_q2_b1", "cfg3_lstm4096x1024_q3_b8"]
+
+
+@pytest.mark.parametrize("name", CONFIG_NAMES)
+def test_gemm_parity_full_configs(biq, oracle, name):
+    from paper_2005_09904_amd.workloads import CONFIGS, make_inputs
+
+    w = CONFIGS[name]
+    _say("gemm %s" % name)
+    B, alpha, X = make_inputs(w)
+    Bd, ad, Xd = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, Bd, w.mu)
+    assert np.array_equal(K.cpu().numpy().reshape(w.q, w.m, -1), oracle.pack_bitmap(B))
+    Y = gpu_gemm(biq, K, ad, Xd, w.m, w.n, w.q, w.mu).cpu().numpy()
+    ref = oracle.gemm_dense(B, alpha, X)
+    assert_within_tolerance(Y, ref, alpha, X, name)
+    # the method's own oracle (Algorithm 2) gives the same reference
+    ref_lut = oracle.gemm_lut(oracle.pack_keys(B, w.mu), alpha, X, w.mu)
+    assert_within_tolerance(Y, ref_lut, alpha, X, name + " vs lut oracle")
+
+
+LARGE = [("cfg4_sq4096_q3_b32", [8]), ("cfg5_ffn_up_q2_b128", [4, 6, 8]), ("cfg5_ffn_down_q2_b128", [8])]
+
+
+@pytest.mark.parametrize("name,mus", LARGE)
+def test_gemm_parity_large_configs_sampled_rows(biq, oracle, name, mus):
+    """Full-size launches; the oracle computes a sample of output rows one by one."""
+    import torch
+    from paper_2005_09904_amd.workloads import CONFIGS, make_inputs
+
+    w = CONFIGS[name]
+    B, alpha, X = make_inputs(w)
+    Bd, ad, Xd = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, Bd, w.mu)
+    del Bd
+    rows = np.unique(np.concatenate([
+        np.array([0, 1, w.m - 1, w.m // 2]),
+        np.random.default_rng(w.seed).integers(0, w.m, size=96)])).astype(np.int64)
+    ref = oracle.gemm_dense(B, alpha, X, rows=rows)
+    bitmap_rows = oracle.pack_bitmap(B[:, rows, :])
+    Kh = K.cpu().numpy().reshape(w.q, w.m, -1)
+    assert np.array_equal(Kh[:, rows, :], bitmap_rows)
+    for mu in mus:
+        _say("gemm %s mu=%d (sampled rows)" % (name, mu))
+        Y = gpu_gemm(biq, K, ad, Xd, w.m, w.n, w.q, mu).cpu().numpy()
+        assert np.all(np.isfinite(Y))
+        assert_within_tolerance(Y[:, rows], ref, alpha[:, rows], X, "%s mu=%d" % (name, mu))
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("m,n,q,b", RAGGED_SHAPES)
+@pytest.mark.parametrize("mu", [8, 4, 6, 1, 2, 3, 5, 7])
+def test_gemm_parity_ragged_shapes(biq, oracle, m, n, q, b, mu):
+    _say("gemm ragged m=%d n=%d q=%d b=%d mu=%d" % (m, n, q, b, mu))
+    B, alpha, X = _rand_inputs(m, n, q, b, 4000 + m + n + mu)
+    Bd, ad, Xd = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, Bd, mu)
+    Y = gpu_gemm(biq, K, ad, Xd, m, n, q, mu).cpu().numpy()
+    assert_within_tolerance(Y, oracle.gemm_dense(B, alpha, X), alpha, X, "ragged")
+
+
+@pytest.mark.parametrize("mu", [8, 4, 6, 3])
+def test_gemm_bit_exact_on_exact_inputs(biq, oracle, mu):
+    """Small-integer x and power-of-two alpha: every fp32 partial sum is exact, so any table
+    width, tiling and reduction order must reproduce the oracle bit for bit."""
+    from paper_2005_09904_amd.workloads import Workload, make_exact_inputs
+
+    for (m, n, q, b) in [(300, 2048, 2, 1), (129, 1000, 3, 4), (64, 4096, 1, 9)]:
+        _say("gemm exact m=%d n=%d q=%d b=%d mu=%d" % (m, n, q, b, mu))
+        w = Workload("exact", m, n, q, b, mu, "uniform", seed=500 + m)
+        B, alpha, X = make_exact_inputs(w)
+        Bd, ad, Xd = device_inputs(B, alpha, X)
+        K = gpu_pack(biq, Bd, mu)
+        Y = gpu_gemm(biq, K, ad, Xd, m, n, q, mu).cpu().numpy()
+        ref = oracle.gemm_dense(B, alpha, X)
+        assert np.array_equal(Y.astype(np.float64), ref)
+
+
+def test_query_with_tables_from_memory_matches_fused(biq, oracle):
+    import torch
+
+    for (m, n, q, b, mu) in [(200, 1500, 2, 1, 8), (100, 700, 3, 6, 8), (90, 1000, 2, 3, 4), (50, 600, 1, 2, 6)]:
+        _say("query m=%d n=%d q=%d b=%d mu=%d" % (m, n, q, b, mu))
+        B, alpha, X = _rand_inputs(m, n, q, b, 6000 + m + mu)
+        Bd, ad, Xd = device_inputs(B, alpha, X)
+        K = gpu_pack(biq, Bd, mu)
+        C = biq.biq_num_chunks(n, mu)
+        LUT = torch.empty((C, 1 << mu, b), dtype=torch.float32, device="cuda")
+        biq.biq_build_lut(Xd, LUT, n, b, mu)
+        Y = torch.full((b, m), float("nan"), dtype=torch.float32, device="cuda")
+        ws_bytes = biq.biq_workspace_bytes(m, n, q, b, mu)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+        biq.biq_query(K, ad, LUT, Y, m, n, q, b, mu, workspace=ws)
+        torch.cuda.synchronize()
+        Yf = gpu_gemm(biq, K, ad, Xd, m, n, q, mu)
+        assert torch.equal(Y, Yf)  # same tables, same order of sums
+        assert_within_tolerance(Y.cpu().numpy(), oracle.gemm_dense(B, alpha, X), alpha, X, "query")
+
+
+def test_explicit_plans_give_the_same_result(biq, oracle):
+    """Tile width, chunk splits, rows per workgroup and threads do not change the result
+    beyond rounding (Algorithm 2's tiling is free)."""
+    m, n, q, b, mu = 700, 3000, 2, 3, 8
+    B, alpha, X = _rand_inputs(m, n, q, b, 7000)
+    Bd, ad, Xd = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, Bd, mu)
+    ref = oracle.gemm_dense(B, alpha, X)
+    base = biq.biq_plan_get(m, n, q, b, mu)
+    for threads, ct, bt, tps, rows in [(64, 16, 1, 1, 5), (256, 32, 4, 3, 64), (512, 64, 2, 100, 700),
+                                       (1024, 128, 1, 2, 33), (128, 16, 8, 7, 1)]:
+        _say("plan threads=%d ct=%d bt=%d tps=%d rows=%d" % (threads, ct, bt, tps, rows))
+        plan = biq.BiqPlan()
+        plan.kernel = base.kernel
+        plan.threads, plan.chunks_per_tile, plan.batch_tile = threads, ct, bt
+        plan.tiles_per_split, plan.rows_per_wg = tps, rows
+        Y = gpu_gemm(biq, K, ad, Xd, m, n, q, mu, plan=plan).cpu().numpy()
+        assert_within_tolerance(Y, ref, alpha, X, "plan")
+
+
+def test_gemm_is_deterministic(biq):
+    import torch
+
+    m, n, q, b, mu = 1024, 4096, 2, 1, 8
+    B, alpha, X = _rand_inputs(m, n, q, b, 8000)
+    Bd, ad, Xd = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, Bd, mu)
+    Y0 = gpu_gemm(biq, K, ad, Xd, m, n, q, mu)
+    for _ in range(3):
+        assert torch.equal(gpu_gemm(biq, K, ad, Xd, m, n, q, mu), Y0)
+
+
+def test_error_paths_on_device_buffers(biq):
+    import torch
+
+    m, n, q, b, mu = 64, 4096, 1, 4, 8
+    K = torch.zeros(biq.biq_packed_bytes(m, n, q), dtype=torch.uint8, device="cuda")
+    alpha = torch.ones((q, m), device="cuda")
+    X = torch.ones((b, n), device="cuda")
+    Y = torch.zeros((b, m), device="cuda")
+    plan = biq.BiqPlan()
+    plan.threads, plan.chunks_per_tile, plan.batch_tile, plan.tiles_per_split, plan.rows_per_wg = 256, 16, 4, 1, 64
+    need = biq.biq_plan_workspace_bytes(biq.biq_plan_get(m, n, q, b, mu), m, b)
+    lib = biq.load_library()
+    import ctypes
+    assert lib.biq_gemm_ex(K.data_ptr(), alpha.data_ptr(), X.data_ptr(), Y.data_ptr(), m, n, q, b, mu,
+                           ctypes.byref(plan), None, 0, None) == biq.BIQ_EWORKSPACE
+    assert lib.biq_gemm(K.data_ptr() + 4, alpha.data_ptr(), X.data_ptr(), Y.data_ptr(), m, n, q, b, mu,
+                        None, 0, None) == biq.BIQ_EINVAL
+    assert need >= 0
