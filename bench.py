@@ -1,0 +1,291 @@
+#!/usr/bin/env python3
+"""Benchmark of the BiQGEMM lookup-table multiply on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one biq_gemm call (tables built in LDS, keys streamed, partials reduced, alpha
+applied) on one batch of synthetic input already resident in HBM.  The headline workload is
+the batch-1 GEMV configuration (m = n = 2048, q = 2, mu = 8); consecutive steps use different
+packed weight matrices (more than 512 MiB in rotation) so that keys come from HBM, not from a
+cache.  The roofline object is measured on the same kernel with the same n, q, mu and batch
+but m scaled until the keys are 512 MiB per call: at the literal size a call moves 1 MiB and
+is bounded by launch latency, not by any memory system.  One JSON line is printed at the end.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(msg: str) -> None:
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+class Problem:
+    """Device buffers of one workload; `copies` packed weight matrices used in rotation."""
+
+    def __init__(self, biq, torch, w, copies: int, real_first: bool = True):
+        self.w = w
+        dev = torch.device("cuda:0")
+        self.key_bytes_padded = biq.biq_packed_bytes(w.m, w.n, w.q)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed)
+        # iid uniform bytes are iid uniform +-1 signs, 8 per byte
+        self.K = torch.randint(0, 256, (copies, self.key_bytes_padded), dtype=torch.uint8, device=dev,
+                               generator=gen)
+        if real_first:
+            from paper_2005_09904_amd.workloads import make_inputs
+
+            B, alpha, X = make_inputs(w)
+            self.host = (B, alpha, X)
+            Bd = torch.from_numpy(B).to(dev)
+            biq.biq_pack(Bd, self.K[0], w.m, w.n, w.q, w.mu)
+            del Bd
+            self.alpha = torch.from_numpy(alpha).to(dev)
+            self.X = torch.from_numpy(X).to(dev)
+        else:
+            self.host = None
+            self.alpha = torch.rand((w.q, w.m), device=dev, generator=gen) * 0.95 + 0.05
+            self.X = torch.randn((w.batch, w.n), device=dev, generator=gen)
+        self.Y = torch.zeros((w.batch, w.m), dtype=torch.float32, device=dev)
+        ws_bytes = biq.biq_workspace_bytes(w.m, w.n, w.q, w.batch, w.mu)
+        self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+        self.copies = copies
+        self.biq = biq
+        self.calls = 0
+
+    def step(self):
+        w = self.w
+        k = self.K[self.calls % self.copies]
+        self.calls += 1
+        self.biq.biq_gemm(k, self.alpha, self.X, self.Y, w.m, w.n, w.q, w.batch, w.mu, workspace=self.ws)
+
+
+def time_steps(torch, prob: Problem, steps: int, warmup: int):
+    """Returns (wall seconds, HIP-event seconds) for exactly `steps` calls after `warmup` calls.
+    The events are recorded on the stream the kernels are launched on (torch's current one)."""
+    for _ in range(warmup):
+        prob.step()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        prob.step()
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return t1 - t0, ev0.elapsed_time(ev1) * 1e-3
+
+
+def summarize(w, seconds_per_call: float):
+    return {
+        "workload": w.name,
+        "m": w.m, "n": w.n, "q": w.q, "batch": w.batch, "mu": w.mu,
+        "us_per_call": seconds_per_call * 1e6,
+        "algorithmic_bytes": w.algorithmic_bytes,
+        "achieved_GBps": w.algorithmic_bytes / seconds_per_call / 1e9,
+        "hbm_frac": w.algorithmic_bytes / seconds_per_call / 1e9 / HBM_PEAK_GBPS,
+        "weight_GBps": w.key_bytes / seconds_per_call / 1e9,
+        "effective_GOPS": w.dense_equiv_ops / seconds_per_call / 1e9,
+        "lookups_per_s": w.lookups / seconds_per_call,
+    }
+
+
+def cpu_baseline(w, host_inputs, budget_s: float = 10.0):
+    """The oracle's LUT path (Algorithm 2, single thread, fp64) timed on this host."""
+    import numpy as np
+    import oracle
+
+    B, alpha, X = host_inputs
+    keys = oracle.pack_keys(B, w.mu)
+    t0 = time.perf_counter()
+    oracle.gemm_lut(keys, alpha, X, w.mu)
+    first = time.perf_counter() - t0
+    reps = int(max(3, min(200, budget_s / max(first, 1e-6))))
+    times = []
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        oracle.gemm_lut(keys, alpha, X, w.mu)
+        times.append(time.perf_counter() - t0)
+    med = float(np.median(times))
+    cpu_model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {
+        "value": w.algorithmic_bytes / med / 1e9,
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": "whole %s workload, oracle gemm_lut (Algorithm 2, fp64), median of %d calls" % (w.name, reps),
+        "us_per_call": med * 1e6,
+        "host_cpu": cpu_model,
+        "host_cores_total": os.cpu_count(),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--only", choices=["all", "headline", "roofline"], default="all",
+                    help="restrict the run to one timed region (used for profiling)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2005_09904_amd as biq
+    from paper_2005_09904_amd.workloads import CONFIGS
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    biq.load_library()  # raises if libbiq.so is missing: there is no fallback
+    torch.cuda.set_device(0)
+
+    head = CONFIGS["cfg2_gemv2048_q2_b1"]
+    out = {}
+    extra = []
+
+    # ---- headline: literal GEMV b=1 configuration, keys cold (rotation > 512 MiB) -------------
+    head_sum = None
+    prob = None
+    if args.only in ("all", "headline"):
+        copies = (512 * 1024 * 1024) // head.key_bytes + 1
+        prob = Problem(biq, torch, head, copies)
+        wall, ev = time_steps(torch, prob, args.steps, args.warmup)
+        head_sum = summarize(head, wall / args.steps)
+        head_sum["event_us_per_call"] = ev / args.steps * 1e6
+        log("headline %s: %.2f us/call wall, %.2f us/call events" %
+            (head.name, head_sum["us_per_call"], head_sum["event_us_per_call"]))
+        # same buffers every call: keys served from cache
+        warm = Problem(biq, torch, head, 1)
+        wwall, _ = time_steps(torch, warm, args.steps, args.warmup)
+        head_sum["warm_us_per_call"] = wwall / args.steps * 1e6
+        del warm
+
+    # ---- roofline: same kernel, m scaled until keys are 512 MiB per call ----------------------
+    roof = None
+    if args.only in ("all", "roofline"):
+        big = head.scaled_m(head.m * 512, "cfg2_shape_m1048576_hbm_regime")
+        pb = Problem(biq, torch, big, 2, real_first=False)
+        rsteps = max(20, min(200, args.steps // 10))
+        rwall, rev = time_steps(torch, pb, rsteps, 5)
+        launch_s = rev / rsteps
+        plan = biq.biq_plan_get(big.m, big.n, big.q, big.batch, big.mu)
+        roof = {
+            "bound": "hbm",
+            "achieved": big.algorithmic_bytes / launch_s / 1e9,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": big.algorithmic_bytes / launch_s / 1e9 / HBM_PEAK_GBPS,
+            "traffic": None,
+            "kernel": biq.biq_kernel_name(plan.kernel),
+            "workload": big.name,
+            "algorithmic_bytes_per_launch": big.algorithmic_bytes,
+            "launch_us": launch_s * 1e6,
+            "launches_timed": rsteps,
+        }
+        log("roofline %s: %.1f us/launch, %.0f GB/s (%.1f%% of HBM peak)" %
+            (big.name, roof["launch_us"], roof["achieved"], 100 * roof["frac"]))
+        del pb
+        torch.cuda.empty_cache()
+        if head_sum is not None:
+            roof["literal_headline"] = {
+                "workload": head.name,
+                "achieved": head_sum["achieved_GBps"],
+                "frac": head_sum["hbm_frac"],
+                "launch_us": head_sum["event_us_per_call"],
+                "note": "1 MiB of keys per call: bounded by launch latency, not by HBM",
+            }
+
+    # ---- the other configurations (context rows) ------------------------------------------------
+    if args.only == "all":
+        for name in ["cfg1_fc512_b1", "cfg3_lstm4096x1024_q3_b8", "cfg4_sq4096_q3_b32",
+                     "cfg5_ffn_up_q2_b128", "cfg5_ffn_down_q2_b128"]:
+            w = CONFIGS[name]
+            copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
+            p = Problem(biq, torch, w, copies, real_first=False)
+            steps = 200 if w.lookups < 1e9 else 20
+            wall, _ = time_steps(torch, p, steps, 5)
+            s = summarize(w, wall / steps)
+            s["key_copies_in_rotation"] = copies
+            extra.append(s)
+            log("%s: %.2f us/call, %.1f GB/s, %.0f GOPS" % (name, s["us_per_call"], s["achieved_GBps"],
+                                                          s["effective_GOPS"]))
+            del p
+            torch.cuda.empty_cache()
+        # the batch-1 family: m scaled by powers of two, to show the launch-latency knee
+        fam = []
+        for k in range(0, 10):
+            w = head.scaled_m(head.m << k)
+            copies = max(2, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
+            p = Problem(biq, torch, w, copies, real_first=False)
+            steps = 200 if k < 6 else 30
+            wall, _ = time_steps(torch, p, steps, 5)
+            s = summarize(w, wall / steps)
+            fam.append({"m": w.m, "key_bytes": w.key_bytes, "us_per_call": s["us_per_call"],
+                        "achieved_GBps": s["achieved_GBps"], "hbm_frac": s["hbm_frac"]})
+            del p
+            torch.cuda.empty_cache()
+        out["gemv_b1_family"] = fam
+
+    cpu = None
+    if not args.no_cpu_baseline and prob is not None and prob.host is not None:
+        cpu = cpu_baseline(head, prob.host)
+        log("cpu oracle: %.0f us/call on 1 core (%s)" % (cpu["us_per_call"], cpu["host_cpu"]))
+
+    value = head_sum["achieved_GBps"] if head_sum else (roof["achieved"] if roof else None)
+    ms_per_step = head_sum["us_per_call"] / 1e3 if head_sum else (roof["launch_us"] / 1e3 if roof else None)
+    line = {
+        "metric": "biq_gemm achieved HBM GB/s (algorithmic bytes / time), GEMV b=1",
+        "value": value,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": head.name,
+            "m": head.m, "n": head.n, "q": head.q, "batch": head.batch, "mu": head.mu,
+            "keys": "cold: %d packed matrices in rotation" % (prob.copies if prob else 0),
+        },
+        "headline": head_sum,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "workloads": extra,
+    }
+    line.update(out)
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -107,7 +107,11 @@ typedef struct {
 } biq_plan;
 
 biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan);
-/* Workspace a given (valid) plan needs. */
+/* Validates a caller-filled plan (kernel, threads, chunks_per_tile, batch_tile,
+ * tiles_per_split, rows_per_wg) against the shape and the device limits and fills in the
+ * derived fields (chunk_splits, row_blocks, batch_tiles, lds_bytes). */
+biq_status biq_plan_check(int m, int n, int q, int batch, int mu, biq_plan* plan);
+/* Workspace a checked plan needs. */
 size_t biq_plan_workspace_bytes(const biq_plan* plan, int m, int batch);
 const char* biq_kernel_name(int kernel);
 

@@ -250,6 +250,11 @@ biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan) 
     return BIQ_OK;
 }
 
+biq_status biq_plan_check(int m, int n, int q, int batch, int mu, biq_plan* plan) {
+    if (!plan || !shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
+    return plan_finish(*plan, m, n, q, batch, mu) ? BIQ_OK : BIQ_EINVAL;
+}
+
 size_t biq_plan_workspace_bytes(const biq_plan* plan, int m, int batch) {
     if (!plan || m < 1 || batch < 1) return 0;
     return plan_workspace(*plan, m, batch);

@@ -27,7 +27,7 @@ def gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, mu, plan=None):
     if plan is None:
         ws_bytes = biq.biq_workspace_bytes(m, n, q, batch, mu)
     else:
-        ws_bytes = biq.biq_plan_workspace_bytes(plan, m, batch)
+        ws_bytes = biq.biq_plan_workspace_bytes(biq.biq_plan_check(m, n, q, batch, mu, plan), m, batch)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=X_dev.device) if ws_bytes else None
     if plan is None:
         biq.biq_gemm(K, alpha_dev, X_dev, Y, m, n, q, batch, mu, workspace=ws)
