@@ -13,6 +13,7 @@ SOURCES = [os.path.join(CSRC, "biq_api.hip")]
 HEADERS = [
     os.path.join(CSRC, "biq_common.h"),
     os.path.join(CSRC, "biq_kernels.h"),
+    os.path.join(CSRC, "biq_gemv8.h"),
     os.path.join(ROOT, "include", "biq.h"),
 ]
 

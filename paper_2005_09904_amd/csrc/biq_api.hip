@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include "biq_kernels.h"
+#include "biq_gemv8.h"
 
 namespace {
 
@@ -15,7 +16,7 @@ constexpr int kLdsTableBudget = 128 * 1024;  // tables of one tile (leaves room 
 constexpr int kNumCu = 256;
 constexpr int kNumXcd = 8;
 
-enum KernelId { KERNEL_GENERIC = 0, KERNEL_COUNT };
+enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_COUNT };
 
 inline bool shape_ok(int m, int n, int q, int batch, int mu) {
     if (m < 1 || n < 1 || q < 1 || batch < 1) return false;
@@ -36,6 +37,7 @@ inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
 
 inline int plan_lds_bytes(const biq_plan& pl, int mu) {
+    if (pl.kernel == KERNEL_GEMV8) return kGemvTileBytes;
     long long b = (long long)pl.chunks_per_tile * (1 << mu) * pl.batch_tile * 4;
     if (pl.tiles_per_split > 1) b += (long long)pl.rows_per_wg * pl.batch_tile * 4;
     return b > (1ll << 30) ? (1 << 30) : (int)b;
@@ -43,11 +45,16 @@ inline int plan_lds_bytes(const biq_plan& pl, int mu) {
 
 // Completes the derived fields and checks a plan against the shape and device limits.
 bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
-    (void)q;
     const int UK = unit_keys(mu);
     const int C = ceil_div(n, mu);
-    if (pl.kernel != KERNEL_GENERIC) return false;
+    if (pl.kernel != KERNEL_GENERIC && pl.kernel != KERNEL_GEMV8) return false;
     if (pl.threads < 64 || pl.threads > 1024 || pl.threads % 64) return false;
+    if (pl.kernel == KERNEL_GEMV8) {
+        // mu = 8, one input vector, at most 4 planes; one 128-chunk tile per workgroup
+        if (mu != 8 || batch != 1 || q > 4) return false;
+        if (pl.chunks_per_tile != kGemvTileChunks || pl.batch_tile != 1 || pl.tiles_per_split != 1)
+            return false;
+    }
     if (pl.batch_tile != 1 && pl.batch_tile != 2 && pl.batch_tile != 4 && pl.batch_tile != 8) return false;
     if (pl.chunks_per_tile < UK || pl.chunks_per_tile % UK) return false;
     const int G = pl.chunks_per_tile / UK;
@@ -76,6 +83,22 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     const int C = ceil_div(n, mu);
     const int E = 1 << mu;
     pl = biq_plan{};
+    if (mu == 8 && batch == 1 && q <= 4) {
+        // GEMV: LUT-stationary workgroups of 1024 threads, one 128-chunk tile each; about four
+        // workgroups per CU over the whole grid when there are rows enough
+        pl.kernel = KERNEL_GEMV8;
+        pl.threads = 1024;
+        pl.chunks_per_tile = kGemvTileChunks;
+        pl.batch_tile = 1;
+        pl.tiles_per_split = 1;
+        const int tiles = ceil_div(C, kGemvTileChunks);
+        const int rows_per_iter = pl.threads / 8;
+        long long k = ((long long)m * tiles) / ((long long)rows_per_iter * 4 * kNumCu);
+        if (k < 1) k = 1;
+        pl.rows_per_wg = (int)(k * rows_per_iter);
+        plan_finish(pl, m, n, q, batch, mu);
+        return;
+    }
     pl.kernel = KERNEL_GENERIC;
     pl.batch_tile = batch >= 5 ? 8 : batch >= 3 ? 4 : batch;
     // widest tile: G units, G a power of two, tables within the budget, no wider than the row
@@ -154,6 +177,30 @@ hipError_t launch_query_mu(int mu, int bt, const QueryParams& qp, int grid, int 
     }
 }
 
+template <int Q, bool FUSED>
+hipError_t launch_gemv8_inst(const QueryParams& qp, int grid, int threads, hipStream_t s) {
+    auto kern = gemv8_kernel<Q, FUSED>;
+    static bool granted = false;
+    if (!granted) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+        if (e != hipSuccess) return e;
+        granted = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), kGemvTileBytes, s, qp);
+    return hipGetLastError();
+}
+
+template <bool FUSED>
+hipError_t launch_gemv8(int q, const QueryParams& qp, int grid, int threads, hipStream_t s) {
+    switch (q) {
+        case 1: return launch_gemv8_inst<1, FUSED>(qp, grid, threads, s);
+        case 2: return launch_gemv8_inst<2, FUSED>(qp, grid, threads, s);
+        case 3: return launch_gemv8_inst<3, FUSED>(qp, grid, threads, s);
+        default: return launch_gemv8_inst<4, FUSED>(qp, grid, threads, s);
+    }
+}
+
 biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const float* X,
                      const float* LUT, float* Y, int m, int n, int q, int batch, int mu,
                      const biq_plan* user_plan, void* workspace, size_t workspace_bytes,
@@ -198,8 +245,12 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     qp.tasks_per_xcd = ceil_div(qp.ntasks, kNumXcd);
     const int grid = qp.tasks_per_xcd * kNumXcd;
 
-    hipError_t e = fused ? launch_query_mu<true>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s)
-                         : launch_query_mu<false>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s);
+    hipError_t e;
+    if (pl.kernel == KERNEL_GEMV8)
+        e = fused ? launch_gemv8<true>(q, qp, grid, pl.threads, s) : launch_gemv8<false>(q, qp, grid, pl.threads, s);
+    else
+        e = fused ? launch_query_mu<true>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s)
+                  : launch_query_mu<false>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s);
     if (e != hipSuccess) return BIQ_EHIP;
     if (pl.chunk_splits > 1) {
         const long long count = (long long)batch * m;
@@ -270,6 +321,7 @@ size_t biq_workspace_bytes(int m, int n, int q, int batch, int mu) {
 const char* biq_kernel_name(int kernel) {
     switch (kernel) {
         case KERNEL_GENERIC: return "query_generic";
+        case KERNEL_GEMV8: return "gemv8";
     }
     return "unknown";
 }

@@ -1,0 +1,199 @@
+// LUT query for mu = 8, batch = 1 (GEMV): the HBM-bound case.
+//
+// A workgroup keeps the tables of one tile of 128 chunks (128 KiB) in LDS and streams its
+// rows' 128-byte key segments with 128-bit loads: 8 lanes per row segment, 8 rows per wave
+// load.  Per key byte the inner loop is one v_perm_b32 (forms the LDS address), one
+// ds_read_b32 and one v_add_f32.
+//
+// LDS layout.  Chunk c of the tile is written c = 16*L + 4*td + e (L = lane inside the row
+// group, td = dword of the lane's 16 bytes, e = byte of that dword).  Entry `key` of its
+// table lives at byte address
+//       (td >> 1) * 65536  +  key * 256  +  (td & 1) * 128  +  (L + 8*e) * 4
+// so that (a) the key sits in byte 1 of the address and v_perm_b32 can drop it there
+// straight from the key dword, and (b) the LDS bank is L + 8*e, independent of the key.
+// LDS serves a wave in two halves of 32 lanes = 4 rows x 8 L.  At step te the lane of row
+// rho visits byte e = (te + rho) & 3 of its dword, so the 32 lanes of a half hit the 32
+// banks exactly once whatever the keys are: gathers are conflict-free by construction
+// (the arrangement idea of Fig. 8, applied to chunks instead of batch entries).
+#pragma once
+
+#include "biq_common.h"
+#include "biq_kernels.h"
+
+namespace biq {
+
+constexpr int kGemvTileChunks = 128;
+constexpr int kGemvTileBytes = kGemvTileChunks * 256 * 4;  // 131072
+
+__device__ __forceinline__ uint32_t gemv8_slot_offset(int L, int td, int e) {
+    return (uint32_t)((td >> 1) * 65536 + (td & 1) * 128 + (L + 8 * e) * 4);
+}
+
+template <int DPP_CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), DPP_CTRL, 0xf, 0xf, true);
+    return v + __int_as_float(moved);
+}
+
+// Sum over each aligned group of 8 lanes; every lane of the group gets the total.
+__device__ __forceinline__ float reduce8(float v) {
+    v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);  // row_half_mirror
+    return v;
+}
+
+// Reads LDS at an absolute byte address.  The kernels below own all of LDS (no static
+// __shared__ variable), so their dynamic LDS starts at address 0 and a table offset is an
+// LDS address; this keeps the per-key address arithmetic to the single v_perm_b32.
+typedef __attribute__((address_space(3))) const float lds_cfloat;
+__device__ __forceinline__ float lds_read_abs(uint32_t byte_addr) {
+    return *reinterpret_cast<lds_cfloat*>(static_cast<uintptr_t>(byte_addr));
+}
+// LDS address of a pointer into __shared__ memory.
+__device__ __forceinline__ uint32_t lds_address_of(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+
+template <int Q, bool FUSED>
+__global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
+    extern __shared__ __align__(16) float lds[];
+    char* const lds_bytes = reinterpret_cast<char*>(lds);
+
+    const int wg = blockIdx.x;
+    const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
+    if (task >= p.ntasks) return;
+    const int sp = task % p.splits;  // tile index: one tile per workgroup
+    const int rb = task / p.splits;
+    const int r0 = rb * p.rows_per_wg;
+    const int r1 = min(p.m, r0 + p.rows_per_wg);
+    const int c0 = sp * kGemvTileChunks;
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    // The lookups address LDS absolutely (see lds_read_abs): fixed at compile time by this
+    // kernel having no static LDS.  Should that ever change, leave Y untouched rather than
+    // read wrong tables.
+    if (lds_address_of(lds) != 0u) return;
+
+    // ---- tables of chunks [c0, c0 + 128) into LDS ------------------------------------------
+    if constexpr (FUSED) {
+        const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+        for (int job = tid; job < 1024; job += nthreads) {
+            const int Lp = job & 3, e = (job >> 2) & 3, td = (job >> 4) & 3, h = job >> 6;
+            float xa[8], xb[8], loa[16], lob[16];
+            const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
+            const int cb = ca + 16;
+            if (vec_ok && 8 * cb + 8 <= p.n) {
+                const float4* xv = reinterpret_cast<const float4*>(p.X);
+                const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], b0 = xv[2 * cb], b1 = xv[2 * cb + 1];
+                xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
+                xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
+                xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w;
+                xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
+            } else {
+                load_chunk_x<8>(p.X, p.n, 1, 0, ca, xa);
+                load_chunk_x<8>(p.X, p.n, 1, 0, cb, xb);
+            }
+            table_lo(xa, loa);
+            table_lo(xb, lob);
+            const float hia = table_hi(xa, (uint32_t)h);
+            const float hib = table_hi(xb, (uint32_t)h);
+            char* dst = lds_bytes + gemv8_slot_offset(2 * Lp, td, e) + (h * 16) * 256;
+#pragma unroll
+            for (int l = 0; l < 16; ++l)
+                *reinterpret_cast<float2*>(dst + l * 256) = make_float2(loa[l] + hia, lob[l] + hib);
+        }
+    } else {
+        for (int i = tid; i < kGemvTileChunks * 256; i += nthreads) {
+            const int key = i & 255, c = i >> 8;
+            const int L = c >> 4, td = (c >> 2) & 3, e = c & 3;
+            float v = 0.0f;
+            if (c0 + c < p.C) v = p.LUT[(size_t)(c0 + c) * 256 + key];
+            *reinterpret_cast<float*>(lds_bytes + gemv8_slot_offset(L, td, e) + key * 256) = v;
+        }
+    }
+    __syncthreads();
+
+    // ---- stream the rows -----------------------------------------------------------------------
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int nwaves = nthreads >> 6;
+    const int L = lane & 7;
+    const int rsub = lane >> 3;  // row inside the wave's group of 8
+    const int rho = rsub & 3;    // rotation: rows of one 32-lane half get distinct values
+
+    // v_perm_b32 operands: S0 = key dword (bytes 4..7 of the pair), S1 = base (bytes 0..3).
+    // result byte 0 <- base byte 0, byte 1 <- key byte (te + rho) & 3, byte 2 <- base byte 2.
+    uint32_t sel[4], base_lo[4], base_hi[4];
+#pragma unroll
+    for (int te = 0; te < 4; ++te) {
+        const int e = (te + rho) & 3;
+        sel[te] = 0x0c020000u | ((uint32_t)(4 + e) << 8);
+        base_lo[te] = (uint32_t)((L + 8 * e) * 4);
+        base_hi[te] = base_lo[te] | 0x10000u;
+    }
+
+    const int dw = sp * 32 + L * 4;  // dword offset of this lane's 16 bytes inside a packed row
+    const bool have_keys = dw < p.stride_dw;
+    const int rows_per_iter = nwaves * 8;
+    const int n_iter = (r1 - r0 + rows_per_iter - 1) / rows_per_iter;
+
+    auto load_keys = [&](int it, uint4 (&k)[Q], float (&al)[Q]) {
+        const int r = r0 + (it * nwaves + wave) * 8 + rsub;
+        const bool ok = have_keys && r < r1 && it < n_iter;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) {
+            k[i] = make_uint4(0u, 0u, 0u, 0u);
+            al[i] = 0.0f;
+            if (ok) {
+                const size_t kr = (size_t)i * p.m + r;
+                k[i] = *reinterpret_cast<const uint4*>(p.K + kr * p.stride_dw + dw);
+                al[i] = p.alpha[kr];
+            }
+        }
+    };
+
+    auto lookup16 = [&](const uint4& k) -> float {
+        const uint32_t w[4] = {k.x, k.y, k.z, k.w};
+        float a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+        for (int td = 0; td < 4; ++td) {
+#pragma unroll
+            for (int te = 0; te < 4; ++te) {
+                const uint32_t b = (td & 2) ? base_hi[te] : base_lo[te];
+                const uint32_t addr = __builtin_amdgcn_perm(w[td], b, sel[te]);
+                const float v = lds_read_abs(addr + (td & 1) * 128);
+                if (te & 1) a1 += v; else a0 += v;
+            }
+        }
+        return a0 + a1;
+    };
+
+    auto finish_row = [&](int it, const uint4 (&k)[Q], const float (&al)[Q]) {
+        float y = 0.0f;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) y = fmaf(al[i], lookup16(k[i]), y);
+        y = reduce8(y);
+        const int r = r0 + (it * nwaves + wave) * 8 + rsub;
+        if (L == 0 && r < r1) p.out[(size_t)sp * p.m + r] = y;
+    };
+
+    // two row groups in flight per wave: while one is looked up the next two are loading
+    uint4 ka[Q], kb[Q];
+    float ala[Q], alb[Q];
+    load_keys(0, ka, ala);
+    load_keys(1, kb, alb);
+    for (int it = 0; it < n_iter; it += 2) {
+        uint4 kc[Q], kd[Q];
+        float alc[Q], ald[Q];
+        load_keys(it + 2, kc, alc);
+        load_keys(it + 3, kd, ald);
+        finish_row(it, ka, ala);
+        if (it + 1 < n_iter) finish_row(it + 1, kb, alb);
+#pragma unroll
+        for (int i = 0; i < Q; ++i) { ka[i] = kc[i]; kb[i] = kd[i]; ala[i] = alc[i]; alb[i] = ald[i]; }
+    }
+}
+
+}  // namespace biq
