@@ -37,7 +37,8 @@ inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
 
 inline int plan_lds_bytes(const biq_plan& pl, int mu) {
-    if (pl.kernel == KERNEL_GEMV8) return kGemvTileBytes;
+    if (pl.kernel == KERNEL_GEMV8)
+        return kGemvTileBytes + (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + 63) / 64) * 64 * 4 : 0);
     long long b = (long long)pl.chunks_per_tile * (1 << mu) * pl.batch_tile * 4;
     if (pl.tiles_per_split > 1) b += (long long)pl.rows_per_wg * pl.batch_tile * 4;
     return b > (1ll << 30) ? (1 << 30) : (int)b;
@@ -52,8 +53,9 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     if (pl.kernel == KERNEL_GEMV8) {
         // mu = 8, one input vector, at most 4 planes; one 128-chunk tile per workgroup
         if (mu != 8 || batch != 1 || q > 4) return false;
-        if (pl.chunks_per_tile != kGemvTileChunks || pl.batch_tile != 1 || pl.tiles_per_split != 1)
-            return false;
+        if (pl.chunks_per_tile != kGemvTileChunks || pl.batch_tile != 1) return false;
+        // 32-bit byte offsets inside a workgroup's row block
+        if ((long long)pl.rows_per_wg * (long long)biq_key_row_stride(n) >= (1ll << 31)) return false;
     }
     if (pl.batch_tile != 1 && pl.batch_tile != 2 && pl.batch_tile != 4 && pl.batch_tile != 8) return false;
     if (pl.chunks_per_tile < UK || pl.chunks_per_tile % UK) return false;
@@ -84,18 +86,25 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     const int E = 1 << mu;
     pl = biq_plan{};
     if (mu == 8 && batch == 1 && q <= 4) {
-        // GEMV: LUT-stationary workgroups of 1024 threads, one 128-chunk tile each; about four
-        // workgroups per CU over the whole grid when there are rows enough
+        // GEMV: workgroups of 1024 threads, 128-chunk tiles, one workgroup per CU when the
+        // rows allow it (every further round of workgroups pays the table build again).  With
+        // >= 1024 rows per CU a workgroup walks all tiles of its rows (no partial sums);
+        // otherwise the tiles are split over workgroups as well and the partials are summed by
+        // a second small kernel.
         pl.kernel = KERNEL_GEMV8;
         pl.threads = 1024;
         pl.chunks_per_tile = kGemvTileChunks;
         pl.batch_tile = 1;
-        pl.tiles_per_split = 1;
         const int tiles = ceil_div(C, kGemvTileChunks);
-        const int rows_per_iter = pl.threads / 8;
-        long long k = ((long long)m * tiles) / ((long long)rows_per_iter * 4 * kNumCu);
-        if (k < 1) k = 1;
-        pl.rows_per_wg = (int)(k * rows_per_iter);
+        if (ceil_div(m, 1024) >= kNumCu) {
+            pl.tiles_per_split = tiles;
+            int rows = ceil_div(ceil_div(m, kNumCu), 64) * 64;
+            pl.rows_per_wg = rows > 8192 ? 8192 : rows;
+        } else {
+            pl.tiles_per_split = 1;
+            int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 64) * 64;
+            pl.rows_per_wg = rows > 8192 ? 8192 : rows;
+        }
         plan_finish(pl, m, n, q, batch, mu);
         return;
     }
@@ -178,7 +187,7 @@ hipError_t launch_query_mu(int mu, int bt, const QueryParams& qp, int grid, int 
 }
 
 template <int Q, bool FUSED>
-hipError_t launch_gemv8_inst(const QueryParams& qp, int grid, int threads, hipStream_t s) {
+hipError_t launch_gemv8_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     auto kern = gemv8_kernel<Q, FUSED>;
     static bool granted = false;
     if (!granted) {
@@ -187,17 +196,17 @@ hipError_t launch_gemv8_inst(const QueryParams& qp, int grid, int threads, hipSt
         if (e != hipSuccess) return e;
         granted = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), kGemvTileBytes, s, qp);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
     return hipGetLastError();
 }
 
 template <bool FUSED>
-hipError_t launch_gemv8(int q, const QueryParams& qp, int grid, int threads, hipStream_t s) {
+hipError_t launch_gemv8(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     switch (q) {
-        case 1: return launch_gemv8_inst<1, FUSED>(qp, grid, threads, s);
-        case 2: return launch_gemv8_inst<2, FUSED>(qp, grid, threads, s);
-        case 3: return launch_gemv8_inst<3, FUSED>(qp, grid, threads, s);
-        default: return launch_gemv8_inst<4, FUSED>(qp, grid, threads, s);
+        case 1: return launch_gemv8_inst<1, FUSED>(qp, grid, threads, lds, s);
+        case 2: return launch_gemv8_inst<2, FUSED>(qp, grid, threads, lds, s);
+        case 3: return launch_gemv8_inst<3, FUSED>(qp, grid, threads, lds, s);
+        default: return launch_gemv8_inst<4, FUSED>(qp, grid, threads, lds, s);
     }
 }
 
@@ -247,7 +256,8 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
 
     hipError_t e;
     if (pl.kernel == KERNEL_GEMV8)
-        e = fused ? launch_gemv8<true>(q, qp, grid, pl.threads, s) : launch_gemv8<false>(q, qp, grid, pl.threads, s);
+        e = fused ? launch_gemv8<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
+                  : launch_gemv8<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
     else
         e = fused ? launch_query_mu<true>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s)
                   : launch_query_mu<false>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s);

@@ -55,19 +55,23 @@ __device__ __forceinline__ uint32_t lds_address_of(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 template <int Q, bool FUSED>
 __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
     extern __shared__ __align__(16) float lds[];
     char* const lds_bytes = reinterpret_cast<char*>(lds);
+    float* const yacc = lds + kGemvTileBytes / 4;  // [rows_per_wg], used when a workgroup walks > 1 tile
 
     const int wg = blockIdx.x;
     const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
     if (task >= p.ntasks) return;
-    const int sp = task % p.splits;  // tile index: one tile per workgroup
+    const int sp = task % p.splits;
     const int rb = task / p.splits;
     const int r0 = rb * p.rows_per_wg;
     const int r1 = min(p.m, r0 + p.rows_per_wg);
-    const int c0 = sp * kGemvTileChunks;
+    const int tile0 = sp * p.tps;
+    const int tile1 = min(p.tiles, tile0 + p.tps);
 
     const int tid = threadIdx.x;
     const int nthreads = blockDim.x;
@@ -76,52 +80,12 @@ __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
     // read wrong tables.
     if (lds_address_of(lds) != 0u) return;
 
-    // ---- tables of chunks [c0, c0 + 128) into LDS ------------------------------------------
-    if constexpr (FUSED) {
-        const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
-        for (int job = tid; job < 1024; job += nthreads) {
-            const int Lp = job & 3, e = (job >> 2) & 3, td = (job >> 4) & 3, h = job >> 6;
-            float xa[8], xb[8], loa[16], lob[16];
-            const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
-            const int cb = ca + 16;
-            if (vec_ok && 8 * cb + 8 <= p.n) {
-                const float4* xv = reinterpret_cast<const float4*>(p.X);
-                const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], b0 = xv[2 * cb], b1 = xv[2 * cb + 1];
-                xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
-                xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
-                xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w;
-                xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
-            } else {
-                load_chunk_x<8>(p.X, p.n, 1, 0, ca, xa);
-                load_chunk_x<8>(p.X, p.n, 1, 0, cb, xb);
-            }
-            table_lo(xa, loa);
-            table_lo(xb, lob);
-            const float hia = table_hi(xa, (uint32_t)h);
-            const float hib = table_hi(xb, (uint32_t)h);
-            char* dst = lds_bytes + gemv8_slot_offset(2 * Lp, td, e) + (h * 16) * 256;
-#pragma unroll
-            for (int l = 0; l < 16; ++l)
-                *reinterpret_cast<float2*>(dst + l * 256) = make_float2(loa[l] + hia, lob[l] + hib);
-        }
-    } else {
-        for (int i = tid; i < kGemvTileChunks * 256; i += nthreads) {
-            const int key = i & 255, c = i >> 8;
-            const int L = c >> 4, td = (c >> 2) & 3, e = c & 3;
-            float v = 0.0f;
-            if (c0 + c < p.C) v = p.LUT[(size_t)(c0 + c) * 256 + key];
-            *reinterpret_cast<float*>(lds_bytes + gemv8_slot_offset(L, td, e) + key * 256) = v;
-        }
-    }
-    __syncthreads();
-
-    // ---- stream the rows -----------------------------------------------------------------------
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int nwaves = nthreads >> 6;
     const int L = lane & 7;
-    const int rsub = lane >> 3;  // row inside the wave's group of 8
-    const int rho = rsub & 3;    // rotation: rows of one 32-lane half get distinct values
+    const int rsub = lane >> 3;  // row group inside the wave
+    const int rho = rsub & 3;    // rotation: the 4 row groups of a 32-lane half get distinct values
 
     // v_perm_b32 operands: S0 = key dword (bytes 4..7 of the pair), S1 = base (bytes 0..3).
     // result byte 0 <- base byte 0, byte 1 <- key byte (te + rho) & 3, byte 2 <- base byte 2.
@@ -134,29 +98,9 @@ __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
         base_hi[te] = base_lo[te] | 0x10000u;
     }
 
-    const int dw = sp * 32 + L * 4;  // dword offset of this lane's 16 bytes inside a packed row
-    const bool have_keys = dw < p.stride_dw;
-    const int rows_per_iter = nwaves * 8;
-    const int n_iter = (r1 - r0 + rows_per_iter - 1) / rows_per_iter;
-
-    auto load_keys = [&](int it, uint4 (&k)[Q], float (&al)[Q]) {
-        const int r = r0 + (it * nwaves + wave) * 8 + rsub;
-        const bool ok = have_keys && r < r1 && it < n_iter;
-#pragma unroll
-        for (int i = 0; i < Q; ++i) {
-            k[i] = make_uint4(0u, 0u, 0u, 0u);
-            al[i] = 0.0f;
-            if (ok) {
-                const size_t kr = (size_t)i * p.m + r;
-                k[i] = *reinterpret_cast<const uint4*>(p.K + kr * p.stride_dw + dw);
-                al[i] = p.alpha[kr];
-            }
-        }
-    };
-
-    auto lookup16 = [&](const uint4& k) -> float {
+    auto lookup16 = [&](const u32x4& k) -> float {
         const uint32_t w[4] = {k.x, k.y, k.z, k.w};
-        float a0 = 0.0f, a1 = 0.0f;
+        float a0, a1;
 #pragma unroll
         for (int td = 0; td < 4; ++td) {
 #pragma unroll
@@ -164,35 +108,115 @@ __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
                 const uint32_t b = (td & 2) ? base_hi[te] : base_lo[te];
                 const uint32_t addr = __builtin_amdgcn_perm(w[td], b, sel[te]);
                 const float v = lds_read_abs(addr + (td & 1) * 128);
-                if (te & 1) a1 += v; else a0 += v;
+                if (td == 0 && te < 2) { if (te) a1 = v; else a0 = v; }
+                else if (te & 1) a1 += v;
+                else a0 += v;
             }
         }
         return a0 + a1;
     };
 
-    auto finish_row = [&](int it, const uint4 (&k)[Q], const float (&al)[Q]) {
-        float y = 0.0f;
-#pragma unroll
-        for (int i = 0; i < Q; ++i) y = fmaf(al[i], lookup16(k[i]), y);
-        y = reduce8(y);
-        const int r = r0 + (it * nwaves + wave) * 8 + rsub;
-        if (L == 0 && r < r1) p.out[(size_t)sp * p.m + r] = y;
-    };
+    // Rows are handled in blocks of 64: in step t (0..7) row group g of the wave reads row
+    // 8*g + t of the block, and the lane with L == t keeps the row's sum, so that after the 8
+    // steps lane j holds row j of the block: alpha and Y are then accessed coalesced.
+    const int nblk = (r1 - r0 + 63) >> 6;
+    const uint32_t stride_bytes = (uint32_t)p.stride_dw * 4u;
 
-    // two row groups in flight per wave: while one is looked up the next two are loading
-    uint4 ka[Q], kb[Q];
-    float ala[Q], alb[Q];
-    load_keys(0, ka, ala);
-    load_keys(1, kb, alb);
-    for (int it = 0; it < n_iter; it += 2) {
-        uint4 kc[Q], kd[Q];
-        float alc[Q], ald[Q];
-        load_keys(it + 2, kc, alc);
-        load_keys(it + 3, kd, ald);
-        finish_row(it, ka, ala);
-        if (it + 1 < n_iter) finish_row(it + 1, kb, alb);
+    for (int tile = tile0; tile < tile1; ++tile) {
+        const int c0 = tile * kGemvTileChunks;
+        if (tile != tile0) __syncthreads();  // every wave is done with the previous tables
+
+        // ---- tables of chunks [c0, c0 + 128) into LDS --------------------------------------
+        if constexpr (FUSED) {
+            const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+            for (int job = tid; job < 1024; job += nthreads) {
+                const int Lp = job & 3, e = (job >> 2) & 3, td = (job >> 4) & 3, h = job >> 6;
+                float xa[8], xb[8], loa[16], lob[16];
+                const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
+                const int cb = ca + 16;
+                if (vec_ok && 8 * cb + 8 <= p.n) {
+                    const float4* xv = reinterpret_cast<const float4*>(p.X);
+                    const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], b0 = xv[2 * cb], b1 = xv[2 * cb + 1];
+                    xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
+                    xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
+                    xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w;
+                    xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
+                } else {
+                    load_chunk_x<8>(p.X, p.n, 1, 0, ca, xa);
+                    load_chunk_x<8>(p.X, p.n, 1, 0, cb, xb);
+                }
+                table_lo(xa, loa);
+                table_lo(xb, lob);
+                const float hia = table_hi(xa, (uint32_t)h);
+                const float hib = table_hi(xb, (uint32_t)h);
+                char* dst = lds_bytes + gemv8_slot_offset(2 * Lp, td, e) + (h * 16) * 256;
 #pragma unroll
-        for (int i = 0; i < Q; ++i) { ka[i] = kc[i]; kb[i] = kd[i]; ala[i] = alc[i]; alb[i] = ald[i]; }
+                for (int l = 0; l < 16; ++l)
+                    *reinterpret_cast<float2*>(dst + l * 256) = make_float2(loa[l] + hia, lob[l] + hib);
+            }
+        } else {
+            for (int i = tid; i < kGemvTileChunks * 256; i += nthreads) {
+                const int key = i & 255, c = i >> 8;
+                const int cL = c >> 4, td = (c >> 2) & 3, e = c & 3;
+                float v = 0.0f;
+                if (c0 + c < p.C) v = p.LUT[(size_t)(c0 + c) * 256 + key];
+                *reinterpret_cast<float*>(lds_bytes + gemv8_slot_offset(cL, td, e) + key * 256) = v;
+            }
+        }
+        __syncthreads();
+
+        // ---- stream the rows ---------------------------------------------------------------------
+        const bool have_keys = (uint32_t)(tile * 128 + L * 16) < stride_bytes;
+        const char* kbase[Q];
+#pragma unroll
+        for (int i = 0; i < Q; ++i)
+            kbase[i] = reinterpret_cast<const char*>(p.K) +
+                       ((size_t)i * p.m + r0) * stride_bytes + (size_t)tile * 128;
+
+        auto load_iter = [&](int bk, int t, u32x4 (&k)[Q]) {
+            const uint32_t row = (uint32_t)(64 * bk + 8 * rsub + t);  // relative to r0
+            const bool ok = have_keys && bk < nblk && (int)row < r1 - r0;
+            const uint32_t voff = row * stride_bytes + (uint32_t)(16 * L);
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                k[i] = (u32x4){0u, 0u, 0u, 0u};
+                if (ok) k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kbase[i] + voff));
+            }
+        };
+
+        // ring of PD steps in flight per wave (PD * Q KiB); fewer for many planes to stay
+        // inside 128 VGPRs
+        constexpr int PD = (Q <= 2) ? 4 : (Q == 3 ? 2 : 1);
+        u32x4 buf[PD][Q];
+        int bk = wave;
+#pragma unroll
+        for (int s = 0; s < PD; ++s) load_iter(bk, s, buf[s]);
+        for (; bk < nblk; bk += nwaves) {
+            const int row_l = 64 * bk + lane;  // the row this lane finishes, relative to r0
+            const bool row_ok = row_l < r1 - r0;
+            float al[Q], keep[Q];
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                al[i] = row_ok ? p.alpha[(size_t)i * p.m + r0 + row_l] : 0.0f;
+                keep[i] = 0.0f;
+            }
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+#pragma unroll
+                for (int i = 0; i < Q; ++i) {
+                    const float s = reduce8(lookup16(buf[t % PD][i]));
+                    keep[i] = (L == t) ? s : keep[i];
+                }
+                if (t + PD < 8) load_iter(bk, t + PD, buf[t % PD]);
+                else load_iter(bk + nwaves, t + PD - 8, buf[t % PD]);
+            }
+            float y = 0.0f;
+#pragma unroll
+            for (int i = 0; i < Q; ++i) y = fmaf(al[i], keep[i], y);
+            if (tile != tile0) y += yacc[row_l];
+            if (tile + 1 < tile1) yacc[row_l] = y;
+            else if (row_ok) p.out[(size_t)sp * p.m + r0 + row_l] = y;
+        }
     }
 }
 
