@@ -145,8 +145,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--only", choices=["all", "headline", "roofline"], default="all",
-                    help="restrict the run to one timed region (used for profiling)")
+    ap.add_argument("--only", choices=["all", "headline", "roofline", "copy"], default="all",
+                    help="restrict the run to one timed region (used for profiling); 'copy' runs a "
+                         "plain 512 MiB device copy, the calibration kernel for HBM byte counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -164,6 +165,16 @@ def main() -> int:
         return 2
     biq.load_library()  # raises if libbiq.so is missing: there is no fallback
     torch.cuda.set_device(0)
+
+    if args.only == "copy":
+        # calibration for rocprofv3 FETCH_SIZE / WRITE_SIZE: reads and writes exactly 512 MiB
+        src = torch.randint(0, 256, (512 * 1024 * 1024,), dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": src.numel(), "copies": 10}))
+        return 0
 
     head = CONFIGS["cfg2_gemv2048_q2_b1"]
     out = {}
