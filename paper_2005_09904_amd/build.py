@@ -14,6 +14,7 @@ HEADERS = [
     os.path.join(CSRC, "biq_common.h"),
     os.path.join(CSRC, "biq_kernels.h"),
     os.path.join(CSRC, "biq_gemv8.h"),
+    os.path.join(CSRC, "biq_gemm8x2.h"),
     os.path.join(ROOT, "include", "biq.h"),
 ]
 

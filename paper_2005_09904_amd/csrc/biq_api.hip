@@ -5,6 +5,7 @@
 
 #include "biq_kernels.h"
 #include "biq_gemv8.h"
+#include "biq_gemm8x2.h"
 
 namespace {
 
@@ -16,7 +17,7 @@ constexpr int kLdsTableBudget = 128 * 1024;  // tables of one tile (leaves room 
 constexpr int kNumCu = 256;
 constexpr int kNumXcd = 8;
 
-enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_COUNT };
+enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL_COUNT };
 
 inline bool shape_ok(int m, int n, int q, int batch, int mu) {
     if (m < 1 || n < 1 || q < 1 || batch < 1) return false;
@@ -39,6 +40,8 @@ inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; 
 inline int plan_lds_bytes(const biq_plan& pl, int mu) {
     if (pl.kernel == KERNEL_GEMV8)
         return kGemvTileBytes + (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + 63) / 64) * 64 * 4 : 0);
+    if (pl.kernel == KERNEL_GEMM8X2)
+        return kGemmTileBytes + (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + 63) / 64) * 64 * 8 : 0);
     long long b = (long long)pl.chunks_per_tile * (1 << mu) * pl.batch_tile * 4;
     if (pl.tiles_per_split > 1) b += (long long)pl.rows_per_wg * pl.batch_tile * 4;
     return b > (1ll << 30) ? (1 << 30) : (int)b;
@@ -48,13 +51,19 @@ inline int plan_lds_bytes(const biq_plan& pl, int mu) {
 bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     const int UK = unit_keys(mu);
     const int C = ceil_div(n, mu);
-    if (pl.kernel != KERNEL_GENERIC && pl.kernel != KERNEL_GEMV8) return false;
+    if (pl.kernel < 0 || pl.kernel >= KERNEL_COUNT) return false;
     if (pl.threads < 64 || pl.threads > 1024 || pl.threads % 64) return false;
     if (pl.kernel == KERNEL_GEMV8) {
         // mu = 8, one input vector, at most 4 planes; one 128-chunk tile per workgroup
         if (mu != 8 || batch != 1 || q > 4) return false;
         if (pl.chunks_per_tile != kGemvTileChunks || pl.batch_tile != 1) return false;
         // 32-bit byte offsets inside a workgroup's row block
+        if ((long long)pl.rows_per_wg * (long long)biq_key_row_stride(n) >= (1ll << 31)) return false;
+    }
+    if (pl.kernel == KERNEL_GEMM8X2) {
+        // mu = 8, at most 4 planes; 64-chunk tiles of two input vectors
+        if (mu != 8 || q > 4) return false;
+        if (pl.chunks_per_tile != kGemmTileChunks || pl.batch_tile != kGemmBT) return false;
         if ((long long)pl.rows_per_wg * (long long)biq_key_row_stride(n) >= (1ll << 31)) return false;
     }
     if (pl.batch_tile != 1 && pl.batch_tile != 2 && pl.batch_tile != 4 && pl.batch_tile != 8) return false;
@@ -105,6 +114,35 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu) {
             int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 64) * 64;
             pl.rows_per_wg = rows > 8192 ? 8192 : rows;
         }
+        plan_finish(pl, m, n, q, batch, mu);
+        return;
+    }
+    if (mu == 8 && batch >= 2 && q <= 4) {
+        // Batched: workgroups of 1024 threads over (row block, chunk split, pair of input
+        // vectors).  Rows per workgroup as many as the LDS row accumulators hold (4096), so that
+        // a table build is amortised over many lookups; tiles are split over workgroups only as
+        // far as needed to give every CU a workgroup; if that is still not enough, rows shrink.
+        pl.kernel = KERNEL_GEMM8X2;
+        pl.threads = 1024;
+        pl.chunks_per_tile = kGemmTileChunks;
+        pl.batch_tile = kGemmBT;
+        const int tiles = ceil_div(C, kGemmTileChunks);
+        const int T = ceil_div(batch, kGemmBT);
+        int rows = ceil_div(m, 64) * 64;
+        if (rows > 4096) rows = 4096;
+        const long long RT = (long long)ceil_div(m, rows) * T;
+        int S = 1;
+        if (RT < kNumCu) {
+            S = ceil_div(kNumCu, RT);
+            if (S > tiles) S = tiles;
+        }
+        pl.tiles_per_split = ceil_div(tiles, S);
+        S = ceil_div(tiles, pl.tiles_per_split);
+        if (RT * S < kNumCu) {
+            int r2 = ceil_div(ceil_div((long long)m * T * S, kNumCu), 64) * 64;
+            if (r2 < rows) rows = r2;
+        }
+        pl.rows_per_wg = rows;
         plan_finish(pl, m, n, q, batch, mu);
         return;
     }
@@ -210,6 +248,30 @@ hipError_t launch_gemv8(int q, const QueryParams& qp, int grid, int threads, int
     }
 }
 
+template <int Q, bool FUSED>
+hipError_t launch_gemm8x2_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    auto kern = gemm8x2_kernel<Q, FUSED>;
+    static bool granted = false;
+    if (!granted) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+        if (e != hipSuccess) return e;
+        granted = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
+    return hipGetLastError();
+}
+
+template <bool FUSED>
+hipError_t launch_gemm8x2(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    switch (q) {
+        case 1: return launch_gemm8x2_inst<1, FUSED>(qp, grid, threads, lds, s);
+        case 2: return launch_gemm8x2_inst<2, FUSED>(qp, grid, threads, lds, s);
+        case 3: return launch_gemm8x2_inst<3, FUSED>(qp, grid, threads, lds, s);
+        default: return launch_gemm8x2_inst<4, FUSED>(qp, grid, threads, lds, s);
+    }
+}
+
 biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const float* X,
                      const float* LUT, float* Y, int m, int n, int q, int batch, int mu,
                      const biq_plan* user_plan, void* workspace, size_t workspace_bytes,
@@ -258,6 +320,9 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     if (pl.kernel == KERNEL_GEMV8)
         e = fused ? launch_gemv8<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
                   : launch_gemv8<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
+    else if (pl.kernel == KERNEL_GEMM8X2)
+        e = fused ? launch_gemm8x2<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
+                  : launch_gemm8x2<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
     else
         e = fused ? launch_query_mu<true>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s)
                   : launch_query_mu<false>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s);
@@ -332,6 +397,7 @@ const char* biq_kernel_name(int kernel) {
     switch (kernel) {
         case KERNEL_GENERIC: return "query_generic";
         case KERNEL_GEMV8: return "gemv8";
+        case KERNEL_GEMM8X2: return "gemm8x2";
     }
     return "unknown";
 }

@@ -1,0 +1,227 @@
+// LUT query for mu = 8, batch >= 2: two input vectors per workgroup pass.
+//
+// Same structure as the GEMV kernel (biq_gemv8.h): a 128 KiB LDS tile of tables, 128-bit key
+// loads, one v_perm_b32 per key byte to form the LDS address, gathers that are free of bank
+// conflicts for any key values.  Here a tile is 64 chunks x 2 input vectors, so 4 lanes cover
+// a row's 64-byte key segment and a wave load covers 16 rows; one address serves both vectors
+// (the two entries are 128 bytes apart: Fig. 8's "entries of one key side by side", spread
+// over two bank sweeps instead of adjacent words so that each sweep stays conflict-free).
+//
+// LDS layout.  Chunk c = 16*L + 4*td + e of the tile (L = lane in the row group, td = dword
+// of the lane's 16 key bytes, e = byte in the dword), vector v (0/1), entry `key`:
+//       (td >> 1) * 65536 + key * 256 + v * 128 + (L + 4*e + 16*(td & 1)) * 4
+// An LDS half-wave is 8 rows x 4 L.  Row r of the half visits, at static step (td, te), byte
+// e = (te + r) & 3 of dword td ^ (r >> 2): the dwords of rows 4..7 are swapped pairwise after
+// the load.  (L, e, td & 1) then takes 32 different values over the half: 32 different banks.
+#pragma once
+
+#include "biq_gemv8.h"
+
+namespace biq {
+
+constexpr int kGemmTileChunks = 64;
+constexpr int kGemmTileBytes = kGemmTileChunks * 256 * 2 * 4;  // 131072
+constexpr int kGemmBT = 2;
+
+__device__ __forceinline__ uint32_t gemm8x2_slot_offset(int L, int td, int e, int v) {
+    return (uint32_t)((td >> 1) * 65536 + v * 128 + (L + 4 * e + 16 * (td & 1)) * 4);
+}
+
+// Sum over each aligned group of 4 lanes; every lane of the group gets the total.
+__device__ __forceinline__ float reduce4(float v) {
+    v = dpp_add<0xB1>(v);  // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);  // quad_perm [2,3,0,1]
+    return v;
+}
+
+template <int Q, bool FUSED>
+__global__ __launch_bounds__(1024) void gemm8x2_kernel(const QueryParams p) {
+    extern __shared__ __align__(16) float lds[];
+    char* const lds_bytes = reinterpret_cast<char*>(lds);
+    float* const yacc = lds + kGemmTileBytes / 4;  // [rows_per_wg][2], when a workgroup walks > 1 tile
+
+    const int wg = blockIdx.x;
+    const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
+    if (task >= p.ntasks) return;
+    const int bt = task % p.batch_tiles;
+    const int rest = task / p.batch_tiles;
+    const int sp = rest % p.splits;
+    const int rb = rest / p.splits;
+    const int b0 = bt * kGemmBT;
+    const int r0 = rb * p.rows_per_wg;
+    const int r1 = min(p.m, r0 + p.rows_per_wg);
+    const int tile0 = sp * p.tps;
+    const int tile1 = min(p.tiles, tile0 + p.tps);
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    // lookups address LDS absolutely (see lds_read_abs in biq_gemv8.h)
+    if (lds_address_of(lds) != 0u) return;
+
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int nwaves = nthreads >> 6;
+    const int L = lane & 3;
+    const int rsub = lane >> 2;       // row group inside the wave, 0..15
+    const int rho = rsub & 3;         // byte rotation
+    const bool swap = (rsub & 4) != 0;  // rows 4..7 of a half-wave work on pairwise swapped dwords
+
+    // v_perm_b32: S0 = key dword, S1 = base; byte 0 <- base byte 0, byte 1 <- key byte
+    // (te + rho) & 3, byte 2 <- base byte 2, byte 3 <- 0.
+    uint32_t sel[4], base[2][2][4];  // base[td >> 1][td & 1][te]
+#pragma unroll
+    for (int te = 0; te < 4; ++te) {
+        const int e = (te + rho) & 3;
+        sel[te] = 0x0c020000u | ((uint32_t)(4 + e) << 8);
+#pragma unroll
+        for (int t1 = 0; t1 < 2; ++t1) {
+            const int td_low = t1 ^ (swap ? 1 : 0);  // dword parity this lane really holds at step t1
+            const uint32_t b = (uint32_t)((L + 4 * e + 16 * td_low) * 4);
+            base[0][t1][te] = b;
+            base[1][t1][te] = b | 0x10000u;
+        }
+    }
+
+    auto lookup16 = [&](const u32x4& k, float& s0, float& s1) {
+        // rows 4..7 of each half-wave: swap dwords 0<->1 and 2<->3
+        const uint32_t w[4] = {swap ? k.y : k.x, swap ? k.x : k.y, swap ? k.w : k.z, swap ? k.z : k.w};
+        float a0, a1, c0, c1;
+#pragma unroll
+        for (int td = 0; td < 4; ++td) {
+#pragma unroll
+            for (int te = 0; te < 4; ++te) {
+                const uint32_t addr = __builtin_amdgcn_perm(w[td], base[td >> 1][td & 1][te], sel[te]);
+                const float v0 = lds_read_abs(addr);
+                const float v1 = lds_read_abs(addr + 128);
+                if (td == 0 && te < 2) {
+                    if (te) { a1 = v0; c1 = v1; } else { a0 = v0; c0 = v1; }
+                } else if (te & 1) { a1 += v0; c1 += v1; }
+                else { a0 += v0; c0 += v1; }
+            }
+        }
+        s0 = a0 + a1;
+        s1 = c0 + c1;
+    };
+
+    // Rows in blocks of 64 per wave: in step t (0..3) row group g reads row 4*g + t and the
+    // lane with L == t keeps the row's sums, so after 4 steps lane j holds row j of the block.
+    const int nblk = (r1 - r0 + 63) >> 6;
+    const uint32_t stride_bytes = (uint32_t)p.stride_dw * 4u;
+
+    for (int tile = tile0; tile < tile1; ++tile) {
+        const int c0 = tile * kGemmTileChunks;
+        if (tile != tile0) __syncthreads();
+
+        // ---- tables of chunks [c0, c0 + 64) x vectors b0, b0 + 1 into LDS ------------------
+        if constexpr (FUSED) {
+            const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+            for (int job = tid; job < 1024; job += nthreads) {
+                const int Lp = job & 1, e = (job >> 1) & 3, td = (job >> 3) & 3, v = (job >> 5) & 1,
+                          h = job >> 6;
+                float xa[8], xb[8], loa[16], lob[16];
+                const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
+                const int cb = ca + 16;
+                const int col = b0 + v;
+                if (vec_ok && col < p.batch && 8 * cb + 8 <= p.n) {
+                    const float4* xv = reinterpret_cast<const float4*>(p.X + (size_t)col * p.n);
+                    const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], q0 = xv[2 * cb], q1 = xv[2 * cb + 1];
+                    xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
+                    xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
+                    xb[0] = q0.x; xb[1] = q0.y; xb[2] = q0.z; xb[3] = q0.w;
+                    xb[4] = q1.x; xb[5] = q1.y; xb[6] = q1.z; xb[7] = q1.w;
+                } else {
+                    load_chunk_x<8>(p.X, p.n, p.batch, col, ca, xa);
+                    load_chunk_x<8>(p.X, p.n, p.batch, col, cb, xb);
+                }
+                table_lo(xa, loa);
+                table_lo(xb, lob);
+                const float hia = table_hi(xa, (uint32_t)h);
+                const float hib = table_hi(xb, (uint32_t)h);
+                char* dst = lds_bytes + gemm8x2_slot_offset(2 * Lp, td, e, v) + (h * 16) * 256;
+#pragma unroll
+                for (int l = 0; l < 16; ++l)
+                    *reinterpret_cast<float2*>(dst + l * 256) = make_float2(loa[l] + hia, lob[l] + hib);
+            }
+        } else {
+            for (int i = tid; i < kGemmTileChunks * 256 * 2; i += nthreads) {
+                const int v = i & 1, key = (i >> 1) & 255, c = i >> 9;
+                const int cL = c >> 4, td = (c >> 2) & 3, e = c & 3;
+                float val = 0.0f;
+                if (c0 + c < p.C && b0 + v < p.batch)
+                    val = p.LUT[((size_t)(c0 + c) * 256 + key) * p.batch + b0 + v];
+                *reinterpret_cast<float*>(lds_bytes + gemm8x2_slot_offset(cL, td, e, v) + key * 256) = val;
+            }
+        }
+        __syncthreads();
+
+        // ---- stream the rows ---------------------------------------------------------------------
+        const bool have_keys = (uint32_t)(tile * 64 + L * 16) < stride_bytes;
+        const char* kbase[Q];
+#pragma unroll
+        for (int i = 0; i < Q; ++i)
+            kbase[i] = reinterpret_cast<const char*>(p.K) +
+                       ((size_t)i * p.m + r0) * stride_bytes + (size_t)tile * 64;
+
+        auto load_iter = [&](int bk, int t, u32x4 (&k)[Q]) {
+            const uint32_t row = (uint32_t)(64 * bk + 4 * rsub + t);  // relative to r0
+            const bool ok = have_keys && bk < nblk && (int)row < r1 - r0;
+            const uint32_t voff = row * stride_bytes + (uint32_t)(16 * L);
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                k[i] = (u32x4){0u, 0u, 0u, 0u};
+                if (ok) k[i] = *reinterpret_cast<const u32x4*>(kbase[i] + voff);
+            }
+        };
+
+        constexpr int PD = (Q == 1) ? 4 : (Q == 2 ? 2 : 1);  // steps in flight per wave (VGPR budget 128)
+        u32x4 buf[PD][Q];
+        int bk = wave;
+#pragma unroll
+        for (int s = 0; s < PD; ++s) load_iter(bk, s, buf[s]);
+        for (; bk < nblk; bk += nwaves) {
+            const int row_l = 64 * bk + lane;  // the row this lane finishes, relative to r0
+            const bool row_ok = row_l < r1 - r0;
+            float al[Q], keep0[Q], keep1[Q];
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                al[i] = row_ok ? p.alpha[(size_t)i * p.m + r0 + row_l] : 0.0f;
+                keep0[i] = 0.0f;
+                keep1[i] = 0.0f;
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+#pragma unroll
+                for (int i = 0; i < Q; ++i) {
+                    float s0, s1;
+                    lookup16(buf[t % PD][i], s0, s1);
+                    s0 = reduce4(s0);
+                    s1 = reduce4(s1);
+                    keep0[i] = (L == t) ? s0 : keep0[i];
+                    keep1[i] = (L == t) ? s1 : keep1[i];
+                }
+                if (t + PD < 4) load_iter(bk, t + PD, buf[t % PD]);
+                else load_iter(bk + nwaves, t + PD - 4, buf[t % PD]);
+            }
+            float y0 = 0.0f, y1 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                y0 = fmaf(al[i], keep0[i], y0);
+                y1 = fmaf(al[i], keep1[i], y1);
+            }
+            if (tile != tile0) {
+                const float2 prev = *reinterpret_cast<const float2*>(yacc + 2 * row_l);
+                y0 += prev.x;
+                y1 += prev.y;
+            }
+            if (tile + 1 < tile1) {
+                *reinterpret_cast<float2*>(yacc + 2 * row_l) = make_float2(y0, y1);
+            } else if (row_ok) {
+                float* out = p.out + ((size_t)sp * p.batch + b0) * p.m + r0 + row_l;
+                out[0] = y0;
+                if (b0 + 1 < p.batch) out[p.m] = y1;
+            }
+        }
+    }
+}
+
+}  // namespace biq

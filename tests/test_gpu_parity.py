@@ -200,6 +200,13 @@ def test_query_with_tables_from_memory_matches_fused(biq, oracle):
         assert_within_tolerance(Y.cpu().numpy(), oracle.gemm_dense(B, alpha, X), alpha, X, "query")
 
 
+def _plan(biq, kernel, threads, ct, bt, tps, rows):
+    plan = biq.BiqPlan()
+    plan.kernel, plan.threads, plan.chunks_per_tile, plan.batch_tile = kernel, threads, ct, bt
+    plan.tiles_per_split, plan.rows_per_wg = tps, rows
+    return plan
+
+
 def test_explicit_plans_give_the_same_result(biq, oracle):
     """Tile width, chunk splits, rows per workgroup and threads do not change the result
     beyond rounding (Algorithm 2's tiling is free)."""
@@ -208,16 +215,36 @@ def test_explicit_plans_give_the_same_result(biq, oracle):
     Bd, ad, Xd = device_inputs(B, alpha, X)
     K = gpu_pack(biq, Bd, mu)
     ref = oracle.gemm_dense(B, alpha, X)
-    base = biq.biq_plan_get(m, n, q, b, mu)
-    for threads, ct, bt, tps, rows in [(64, 16, 1, 1, 5), (256, 32, 4, 3, 64), (512, 64, 2, 100, 700),
-                                       (1024, 128, 1, 2, 33), (128, 16, 8, 7, 1)]:
-        _say("plan threads=%d ct=%d bt=%d tps=%d rows=%d" % (threads, ct, bt, tps, rows))
-        plan = biq.BiqPlan()
-        plan.kernel = base.kernel
-        plan.threads, plan.chunks_per_tile, plan.batch_tile = threads, ct, bt
-        plan.tiles_per_split, plan.rows_per_wg = tps, rows
-        Y = gpu_gemm(biq, K, ad, Xd, m, n, q, mu, plan=plan).cpu().numpy()
+    plans = [(0, 64, 16, 1, 1, 5), (0, 256, 32, 4, 3, 64), (0, 512, 64, 2, 100, 700),
+             (0, 1024, 128, 1, 2, 33), (0, 128, 16, 8, 7, 1),
+             # batched mu=8 kernel: 64-chunk tiles of 2 vectors
+             (2, 1024, 64, 2, 1, 64), (2, 512, 64, 2, 2, 128), (2, 256, 64, 2, 6, 704), (2, 64, 64, 2, 3, 100)]
+    for kernel, threads, ct, bt, tps, rows in plans:
+        _say("plan kernel=%d threads=%d ct=%d bt=%d tps=%d rows=%d" % (kernel, threads, ct, bt, tps, rows))
+        Y = gpu_gemm(biq, K, ad, Xd, m, n, q, mu, plan=_plan(biq, kernel, threads, ct, bt, tps, rows)).cpu().numpy()
         assert_within_tolerance(Y, ref, alpha, X, "plan")
+    # GEMV kernel plans (batch 1)
+    B, alpha, X = _rand_inputs(m, n, 3, 1, 7001)
+    Bd, ad, Xd = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, Bd, mu)
+    ref = oracle.gemm_dense(B, alpha, X)
+    for kernel, threads, ct, bt, tps, rows in [(1, 1024, 128, 1, 1, 64), (1, 512, 128, 1, 3, 700),
+                                               (1, 64, 128, 1, 2, 130), (0, 256, 64, 1, 1, 50)]:
+        _say("plan kernel=%d threads=%d ct=%d bt=%d tps=%d rows=%d" % (kernel, threads, ct, bt, tps, rows))
+        Y = gpu_gemm(biq, K, ad, Xd, m, n, 3, mu, plan=_plan(biq, kernel, threads, ct, bt, tps, rows)).cpu().numpy()
+        assert_within_tolerance(Y, ref, alpha, X, "plan")
+
+
+@pytest.mark.parametrize("q", [1, 2, 3, 4, 5])
+def test_plane_counts(biq, oracle, q):
+    """q = 1..4 run the specialised mu = 8 kernels, q = 5 the generic one."""
+    for (m, n, b) in [(333, 1100, 1), (200, 900, 2), (150, 2100, 5)]:
+        _say("planes q=%d m=%d n=%d b=%d" % (q, m, n, b))
+        B, alpha, X = _rand_inputs(m, n, q, b, 9000 + q + b)
+        Bd, ad, Xd = device_inputs(B, alpha, X)
+        K = gpu_pack(biq, Bd, 8)
+        Y = gpu_gemm(biq, K, ad, Xd, m, n, q, 8).cpu().numpy()
+        assert_within_tolerance(Y, oracle.gemm_dense(B, alpha, X), alpha, X, "planes")
 
 
 def test_gemm_is_deterministic(biq):
@@ -240,8 +267,7 @@ def test_error_paths_on_device_buffers(biq):
     alpha = torch.ones((q, m), device="cuda")
     X = torch.ones((b, n), device="cuda")
     Y = torch.zeros((b, m), device="cuda")
-    plan = biq.BiqPlan()
-    plan.threads, plan.chunks_per_tile, plan.batch_tile, plan.tiles_per_split, plan.rows_per_wg = 256, 16, 4, 1, 64
+    plan = _plan(biq, 0, 256, 16, 4, 1, 64)
     need = biq.biq_plan_workspace_bytes(biq.biq_plan_get(m, n, q, b, mu), m, b)
     lib = biq.load_library()
     import ctypes
