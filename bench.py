@@ -62,12 +62,13 @@ class Problem:
         self.copies = copies
         self.biq = biq
         self.calls = 0
+        # one marshalled call per key matrix in the rotation: a step is then one C-ABI call
+        self.prepared = [biq.PreparedGemm(self.K[i], self.alpha, self.X, self.Y, w.m, w.n, w.q, w.batch,
+                                          w.mu, workspace=self.ws) for i in range(copies)]
 
     def step(self):
-        w = self.w
-        k = self.K[self.calls % self.copies]
+        self.prepared[self.calls % self.copies]()
         self.calls += 1
-        self.biq.biq_gemm(k, self.alpha, self.X, self.Y, w.m, w.n, w.q, w.batch, w.mu, workspace=self.ws)
 
 
 def time_steps(torch, prob: Problem, steps: int, warmup: int):

@@ -103,7 +103,11 @@ typedef struct {
     int row_blocks;      /* ceil(m / rows_per_wg)                                         */
     int batch_tiles;     /* ceil(batch / batch_tile)                                      */
     int lds_bytes;       /* dynamic LDS per workgroup                                     */
-    int reserved[6];
+    int row_mode;        /* mu = 8 kernels: 0 = a wave works through blocks of 64 rows
+                            (throughput), 1 = one step of rows per wave at a time, keys
+                            requested before the tables are built (latency; needs
+                            tiles_per_split = 1)                                           */
+    int reserved[5];
 } biq_plan;
 
 biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan);

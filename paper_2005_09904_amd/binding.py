@@ -28,7 +28,7 @@ class BiqPlan(ctypes.Structure):
         ("kernel", ctypes.c_int), ("threads", ctypes.c_int), ("chunks_per_tile", ctypes.c_int),
         ("batch_tile", ctypes.c_int), ("chunk_splits", ctypes.c_int), ("tiles_per_split", ctypes.c_int),
         ("rows_per_wg", ctypes.c_int), ("row_blocks", ctypes.c_int), ("batch_tiles", ctypes.c_int),
-        ("lds_bytes", ctypes.c_int), ("reserved", ctypes.c_int * 6),
+        ("lds_bytes", ctypes.c_int), ("row_mode", ctypes.c_int), ("reserved", ctypes.c_int * 5),
     ]
 
     def as_dict(self):
@@ -176,6 +176,29 @@ def biq_gemm(K, alpha, X, Y, m: int, n: int, q: int, batch: int, mu: int, worksp
              stream=None) -> None:
     _check(load_library().biq_gemm(_ptr(K), _ptr(alpha), _ptr(X), _ptr(Y), m, n, q, batch, mu,
                                    _ptr(workspace), _nbytes(workspace), _stream(stream)), "biq_gemm")
+
+
+class PreparedGemm:
+    """A biq_gemm call with its arguments marshalled once: calling the object only crosses the
+    C ABI (no tensor attribute lookups per call).  The tensors must stay alive and in place.
+    The stream is the one given here, or torch's current stream at preparation time."""
+
+    def __init__(self, K, alpha, X, Y, m, n, q, batch, mu, workspace=None, stream=None, plan=None):
+        lib = load_library()
+        self._keep = (K, alpha, X, Y, workspace, plan)
+        ws_ptr, ws_bytes, st = _ptr(workspace), _nbytes(workspace), _stream(stream)
+        if plan is None:
+            self._fn = lib.biq_gemm
+            self._args = (_ptr(K), _ptr(alpha), _ptr(X), _ptr(Y), m, n, q, batch, mu, ws_ptr, ws_bytes, st)
+        else:
+            self._fn = lib.biq_gemm_ex
+            self._args = (_ptr(K), _ptr(alpha), _ptr(X), _ptr(Y), m, n, q, batch, mu, ctypes.byref(plan),
+                          ws_ptr, ws_bytes, st)
+
+    def __call__(self) -> None:
+        status = self._fn(*self._args)
+        if status != BIQ_OK:
+            raise BiqError(status, "biq_gemm")
 
 
 def biq_gemm_ex(K, alpha, X, Y, m: int, n: int, q: int, batch: int, mu: int, plan: BiqPlan,

@@ -73,6 +73,8 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     if (pl.rows_per_wg < 1 || pl.tiles_per_split < 1) return false;
     const int tiles = ceil_div(C, pl.chunks_per_tile);
     if (pl.tiles_per_split > tiles) pl.tiles_per_split = tiles;
+    if (pl.row_mode != 0 && !(pl.row_mode == 1 && pl.kernel != KERNEL_GENERIC && pl.tiles_per_split == 1))
+        return false;
     pl.chunk_splits = ceil_div(tiles, pl.tiles_per_split);
     pl.row_blocks = ceil_div(m, pl.rows_per_wg);
     pl.batch_tiles = ceil_div(batch, pl.batch_tile);
@@ -109,6 +111,12 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu) {
             pl.tiles_per_split = tiles;
             int rows = ceil_div(ceil_div(m, kNumCu), 64) * 64;
             pl.rows_per_wg = rows > 8192 ? 8192 : rows;
+        } else if ((long long)m * tiles <= 4ll * 128 * kNumCu) {
+            // small: latency mode, 8 rows per wave step, at most 4 steps per wave
+            pl.tiles_per_split = 1;
+            pl.row_mode = 1;
+            int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 128) * 128;
+            pl.rows_per_wg = rows;
         } else {
             pl.tiles_per_split = 1;
             int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 64) * 64;
@@ -141,6 +149,11 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu) {
         if (RT * S < kNumCu) {
             int r2 = ceil_div(ceil_div((long long)m * T * S, kNumCu), 64) * 64;
             if (r2 < rows) rows = r2;
+        }
+        if (pl.tiles_per_split == 1 && rows <= 4 * 256) {
+            // few rows per workgroup: latency mode, 16 rows per wave step, at most 4 steps per wave
+            pl.row_mode = 1;
+            rows = ceil_div(rows, 256) * 256;
         }
         pl.rows_per_wg = rows;
         plan_finish(pl, m, n, q, batch, mu);
@@ -314,6 +327,7 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     qp.batch_tiles = pl.batch_tiles;
     qp.ntasks = pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
     qp.tasks_per_xcd = ceil_div(qp.ntasks, kNumXcd);
+    qp.row_mode = pl.row_mode;
     const int grid = qp.tasks_per_xcd * kNumXcd;
 
     hipError_t e;

@@ -61,8 +61,8 @@ __device__ __forceinline__ void load_unit(const uint32_t* __restrict__ row, int 
 
 // ---------------------------------------------------------------------------------
 // Table entries.  For one chunk x[0..8) (elements past MU or past column n are 0) the
-// entry of key k = 16*h + l is  lo(l) + hi(h)  with
-//   lo(l) = (s0 x0 + s1 x1) + (s2 x2 + s3 x3),  hi(h) = (s4 x4 + s5 x5) + (s6 x6 + s7 x7),
+// entry of key k = 16*h + l is  (s0 x0 + s1 x1) + ((s2 x2 + s3 x3) + hi(h))  with
+//   hi(h) = (s4 x4 + s5 x5) + (s6 x6 + s7 x7),
 // s_j = +1 if bit j of k is set else -1 (paper: q = M_mu . x).  Every partial is formed
 // from a pair and its exact negation, so entry(~k) = -entry(k) holds bit for bit, the
 // property Algorithm 1 obtains by copying negated entries.
@@ -92,12 +92,17 @@ __device__ __forceinline__ float table_hi(const float (&x)[8], uint32_t h) {
     return pair_pick(c, h & 3u) + pair_pick(d, h >> 2);
 }
 
-// lo(l) for all l in 0..15
-__device__ __forceinline__ void table_lo(const float (&x)[8], float (&lo)[16]) {
+// The 16 entries of keys 16*h + l, l = 0..15:  A[l & 3] + (B[l >> 2] + hi(h)).  Every kernel
+// that fills tables uses this one association, so fused and unfused paths agree bit for bit.
+__device__ __forceinline__ void table16(const float (&x)[8], uint32_t h, float (&out)[16]) {
     const PairSums a = pair_sums(x[0], x[1]);
     const PairSums b = pair_sums(x[2], x[3]);
+    const float hi = table_hi(x, h);
+    float bh[4];
 #pragma unroll
-    for (int l = 0; l < 16; ++l) lo[l] = a.a[l & 3] + b.a[l >> 2];
+    for (int j = 0; j < 4; ++j) bh[j] = b.a[j] + hi;
+#pragma unroll
+    for (int l = 0; l < 16; ++l) out[l] = a.a[l & 3] + bh[l >> 2];
 }
 
 // x[j] = X[col][MU*c + j] for j < MU and inside the row, else 0

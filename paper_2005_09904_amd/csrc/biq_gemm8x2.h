@@ -34,6 +34,50 @@ __device__ __forceinline__ float reduce4(float v) {
     return v;
 }
 
+// Tables of chunks [c0, c0 + 64) for input vectors b0, b0 + 1, built from X into the LDS
+// layout above.  One job = (vector, pair of chunks adjacent in L, 16 keys): 1024 jobs.
+__device__ __forceinline__ void gemm8x2_build_tile(const QueryParams& p, char* lds_bytes, int c0,
+                                                   int b0, int tid, int nthreads) {
+    const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+    for (int job = tid; job < 1024; job += nthreads) {
+        const int Lp = job & 1, e = (job >> 1) & 3, td = (job >> 3) & 3, v = (job >> 5) & 1, h = job >> 6;
+        float xa[8], xb[8], ea[16], eb[16];
+        const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
+        const int cb = ca + 16;
+        const int col = b0 + v;
+        if (vec_ok && col < p.batch && 8 * cb + 8 <= p.n) {
+            const float4* xv = reinterpret_cast<const float4*>(p.X + (size_t)col * p.n);
+            const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], q0 = xv[2 * cb], q1 = xv[2 * cb + 1];
+            xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
+            xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
+            xb[0] = q0.x; xb[1] = q0.y; xb[2] = q0.z; xb[3] = q0.w;
+            xb[4] = q1.x; xb[5] = q1.y; xb[6] = q1.z; xb[7] = q1.w;
+        } else {
+            load_chunk_x<8>(p.X, p.n, p.batch, col, ca, xa);
+            load_chunk_x<8>(p.X, p.n, p.batch, col, cb, xb);
+        }
+        table16(xa, (uint32_t)h, ea);
+        table16(xb, (uint32_t)h, eb);
+        char* dst = lds_bytes + gemm8x2_slot_offset(2 * Lp, td, e, v) + (h * 16) * 256;
+#pragma unroll
+        for (int l = 0; l < 16; ++l)
+            *reinterpret_cast<float2*>(dst + l * 256) = make_float2(ea[l], eb[l]);
+    }
+}
+
+// The same tile copied from tables in device memory (LUT [C][256][batch]).
+__device__ __forceinline__ void gemm8x2_copy_tile(const QueryParams& p, char* lds_bytes, int c0,
+                                                  int b0, int tid, int nthreads) {
+    for (int i = tid; i < kGemmTileChunks * 256 * 2; i += nthreads) {
+        const int v = i & 1, key = (i >> 1) & 255, c = i >> 9;
+        const int cL = c >> 4, td = (c >> 2) & 3, e = c & 3;
+        float val = 0.0f;
+        if (c0 + c < p.C && b0 + v < p.batch)
+            val = p.LUT[((size_t)(c0 + c) * 256 + key) * p.batch + b0 + v];
+        *reinterpret_cast<float*>(lds_bytes + gemm8x2_slot_offset(cL, td, e, v) + key * 256) = val;
+    }
+}
+
 template <int Q, bool FUSED>
 __global__ __launch_bounds__(1024) void gemm8x2_kernel(const QueryParams p) {
     extern __shared__ __align__(16) float lds[];
@@ -103,55 +147,71 @@ __global__ __launch_bounds__(1024) void gemm8x2_kernel(const QueryParams p) {
         s1 = c0 + c1;
     };
 
-    // Rows in blocks of 64 per wave: in step t (0..3) row group g reads row 4*g + t and the
-    // lane with L == t keeps the row's sums, so after 4 steps lane j holds row j of the block.
-    const int nblk = (r1 - r0 + 63) >> 6;
     const uint32_t stride_bytes = (uint32_t)p.stride_dw * 4u;
+    const int nrows = r1 - r0;
+
+    if (p.row_mode == 1) {
+        // ---- latency mode: one tile per workgroup, one step of 16 rows per wave at a time; the
+        // first step's keys are requested before the tables are built.
+        const int tile = tile0;
+        const bool have_keys = (uint32_t)(tile * 64 + L * 16) < stride_bytes;
+        const int nsteps = (nrows + 15) >> 4;
+        auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q]) {
+            const int row = 16 * s + rsub;
+            const bool ok = have_keys && s < nsteps && row < nrows;
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                k[i] = (u32x4){0u, 0u, 0u, 0u};
+                al[i] = 0.0f;
+                if (ok) {
+                    const size_t kr = (size_t)i * p.m + r0 + row;
+                    k[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.K) +
+                                                           kr * stride_bytes + tile * 64 + 16 * L);
+                    al[i] = p.alpha[kr];
+                }
+            }
+        };
+        u32x4 k[Q], kn[Q];
+        float al[Q], aln[Q];
+        load_step(wave, k, al);
+        if constexpr (FUSED) gemm8x2_build_tile(p, lds_bytes, tile * kGemmTileChunks, b0, tid, nthreads);
+        else gemm8x2_copy_tile(p, lds_bytes, tile * kGemmTileChunks, b0, tid, nthreads);
+        __syncthreads();
+        for (int s = wave; s < nsteps; s += nwaves) {
+            load_step(s + nwaves, kn, aln);
+            float y0 = 0.0f, y1 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                float s0, s1;
+                lookup16(k[i], s0, s1);
+                y0 = fmaf(al[i], s0, y0);
+                y1 = fmaf(al[i], s1, y1);
+            }
+            y0 = reduce4(y0);
+            y1 = reduce4(y1);
+            const int row = 16 * s + rsub;
+            if (L == 0 && row < nrows) {
+                float* out = p.out + ((size_t)sp * p.batch + b0) * p.m + r0 + row;
+                out[0] = y0;
+                if (b0 + 1 < p.batch) out[p.m] = y1;
+            }
+#pragma unroll
+            for (int i = 0; i < Q; ++i) { k[i] = kn[i]; al[i] = aln[i]; }
+        }
+        return;
+    }
+
+    // ---- throughput mode.  Rows in blocks of 64 per wave: in step t (0..3) row group g reads
+    // row 4*g + t and the lane with L == t keeps the row's sums, so after 4 steps lane j holds
+    // row j of the block.
+    const int nblk = (nrows + 63) >> 6;
 
     for (int tile = tile0; tile < tile1; ++tile) {
         const int c0 = tile * kGemmTileChunks;
         if (tile != tile0) __syncthreads();
 
-        // ---- tables of chunks [c0, c0 + 64) x vectors b0, b0 + 1 into LDS ------------------
-        if constexpr (FUSED) {
-            const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
-            for (int job = tid; job < 1024; job += nthreads) {
-                const int Lp = job & 1, e = (job >> 1) & 3, td = (job >> 3) & 3, v = (job >> 5) & 1,
-                          h = job >> 6;
-                float xa[8], xb[8], loa[16], lob[16];
-                const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
-                const int cb = ca + 16;
-                const int col = b0 + v;
-                if (vec_ok && col < p.batch && 8 * cb + 8 <= p.n) {
-                    const float4* xv = reinterpret_cast<const float4*>(p.X + (size_t)col * p.n);
-                    const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], q0 = xv[2 * cb], q1 = xv[2 * cb + 1];
-                    xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
-                    xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
-                    xb[0] = q0.x; xb[1] = q0.y; xb[2] = q0.z; xb[3] = q0.w;
-                    xb[4] = q1.x; xb[5] = q1.y; xb[6] = q1.z; xb[7] = q1.w;
-                } else {
-                    load_chunk_x<8>(p.X, p.n, p.batch, col, ca, xa);
-                    load_chunk_x<8>(p.X, p.n, p.batch, col, cb, xb);
-                }
-                table_lo(xa, loa);
-                table_lo(xb, lob);
-                const float hia = table_hi(xa, (uint32_t)h);
-                const float hib = table_hi(xb, (uint32_t)h);
-                char* dst = lds_bytes + gemm8x2_slot_offset(2 * Lp, td, e, v) + (h * 16) * 256;
-#pragma unroll
-                for (int l = 0; l < 16; ++l)
-                    *reinterpret_cast<float2*>(dst + l * 256) = make_float2(loa[l] + hia, lob[l] + hib);
-            }
-        } else {
-            for (int i = tid; i < kGemmTileChunks * 256 * 2; i += nthreads) {
-                const int v = i & 1, key = (i >> 1) & 255, c = i >> 9;
-                const int cL = c >> 4, td = (c >> 2) & 3, e = c & 3;
-                float val = 0.0f;
-                if (c0 + c < p.C && b0 + v < p.batch)
-                    val = p.LUT[((size_t)(c0 + c) * 256 + key) * p.batch + b0 + v];
-                *reinterpret_cast<float*>(lds_bytes + gemm8x2_slot_offset(cL, td, e, v) + key * 256) = val;
-            }
-        }
+        if constexpr (FUSED) gemm8x2_build_tile(p, lds_bytes, c0, b0, tid, nthreads);
+        else gemm8x2_copy_tile(p, lds_bytes, c0, b0, tid, nthreads);
         __syncthreads();
 
         // ---- stream the rows ---------------------------------------------------------------------

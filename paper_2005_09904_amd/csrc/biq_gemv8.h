@@ -57,6 +57,48 @@ __device__ __forceinline__ uint32_t lds_address_of(const void* p) {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Tables of chunks [c0, c0 + 128) for one input vector, built from X straight into the LDS
+// layout above.  One job = (pair of chunks adjacent in L, 16 keys): 1024 jobs per tile.
+__device__ __forceinline__ void gemv8_build_tile(const QueryParams& p, char* lds_bytes, int c0,
+                                                 int tid, int nthreads) {
+    const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+    for (int job = tid; job < 1024; job += nthreads) {
+        const int Lp = job & 3, e = (job >> 2) & 3, td = (job >> 4) & 3, h = job >> 6;
+        float xa[8], xb[8], ea[16], eb[16];
+        const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
+        const int cb = ca + 16;
+        if (vec_ok && 8 * cb + 8 <= p.n) {
+            const float4* xv = reinterpret_cast<const float4*>(p.X);
+            const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], b0 = xv[2 * cb], b1 = xv[2 * cb + 1];
+            xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
+            xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
+            xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w;
+            xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
+        } else {
+            load_chunk_x<8>(p.X, p.n, 1, 0, ca, xa);
+            load_chunk_x<8>(p.X, p.n, 1, 0, cb, xb);
+        }
+        table16(xa, (uint32_t)h, ea);
+        table16(xb, (uint32_t)h, eb);
+        char* dst = lds_bytes + gemv8_slot_offset(2 * Lp, td, e) + (h * 16) * 256;
+#pragma unroll
+        for (int l = 0; l < 16; ++l)
+            *reinterpret_cast<float2*>(dst + l * 256) = make_float2(ea[l], eb[l]);
+    }
+}
+
+// The same tile copied from tables in device memory (LUT [C][256][1]).
+__device__ __forceinline__ void gemv8_copy_tile(const QueryParams& p, char* lds_bytes, int c0,
+                                                int tid, int nthreads) {
+    for (int i = tid; i < kGemvTileChunks * 256; i += nthreads) {
+        const int key = i & 255, c = i >> 8;
+        const int cL = c >> 4, td = (c >> 2) & 3, e = c & 3;
+        float v = 0.0f;
+        if (c0 + c < p.C) v = p.LUT[(size_t)(c0 + c) * 256 + key];
+        *reinterpret_cast<float*>(lds_bytes + gemv8_slot_offset(cL, td, e) + key * 256) = v;
+    }
+}
+
 template <int Q, bool FUSED>
 __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
     extern __shared__ __align__(16) float lds[];
@@ -116,56 +158,60 @@ __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
         return a0 + a1;
     };
 
-    // Rows are handled in blocks of 64: in step t (0..7) row group g of the wave reads row
-    // 8*g + t of the block, and the lane with L == t keeps the row's sum, so that after the 8
-    // steps lane j holds row j of the block: alpha and Y are then accessed coalesced.
-    const int nblk = (r1 - r0 + 63) >> 6;
     const uint32_t stride_bytes = (uint32_t)p.stride_dw * 4u;
+    const int nrows = r1 - r0;
 
-    for (int tile = tile0; tile < tile1; ++tile) {
-        const int c0 = tile * kGemvTileChunks;
-        if (tile != tile0) __syncthreads();  // every wave is done with the previous tables
-
-        // ---- tables of chunks [c0, c0 + 128) into LDS --------------------------------------
-        if constexpr (FUSED) {
-            const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
-            for (int job = tid; job < 1024; job += nthreads) {
-                const int Lp = job & 3, e = (job >> 2) & 3, td = (job >> 4) & 3, h = job >> 6;
-                float xa[8], xb[8], loa[16], lob[16];
-                const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
-                const int cb = ca + 16;
-                if (vec_ok && 8 * cb + 8 <= p.n) {
-                    const float4* xv = reinterpret_cast<const float4*>(p.X);
-                    const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], b0 = xv[2 * cb], b1 = xv[2 * cb + 1];
-                    xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
-                    xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
-                    xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w;
-                    xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
-                } else {
-                    load_chunk_x<8>(p.X, p.n, 1, 0, ca, xa);
-                    load_chunk_x<8>(p.X, p.n, 1, 0, cb, xb);
-                }
-                table_lo(xa, loa);
-                table_lo(xb, lob);
-                const float hia = table_hi(xa, (uint32_t)h);
-                const float hib = table_hi(xb, (uint32_t)h);
-                char* dst = lds_bytes + gemv8_slot_offset(2 * Lp, td, e) + (h * 16) * 256;
+    if (p.row_mode == 1) {
+        // ---- latency mode: one tile per workgroup, one step of 8 rows per wave at a time.  The
+        // first step's keys are requested before the tables are built.
+        const int tile = tile0;
+        const bool have_keys = (uint32_t)(tile * 128 + L * 16) < stride_bytes;
+        const int nsteps = (nrows + 7) >> 3;
+        auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q]) {
+            const int row = 8 * s + rsub;
+            const bool ok = have_keys && s < nsteps && row < nrows;
 #pragma unroll
-                for (int l = 0; l < 16; ++l)
-                    *reinterpret_cast<float2*>(dst + l * 256) = make_float2(loa[l] + hia, lob[l] + hib);
+            for (int i = 0; i < Q; ++i) {
+                k[i] = (u32x4){0u, 0u, 0u, 0u};
+                al[i] = 0.0f;
+                if (ok) {
+                    const size_t kr = (size_t)i * p.m + r0 + row;
+                    k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(
+                        reinterpret_cast<const char*>(p.K) + kr * stride_bytes + tile * 128 + 16 * L));
+                    al[i] = p.alpha[kr];
+                }
             }
-        } else {
-            for (int i = tid; i < kGemvTileChunks * 256; i += nthreads) {
-                const int key = i & 255, c = i >> 8;
-                const int cL = c >> 4, td = (c >> 2) & 3, e = c & 3;
-                float v = 0.0f;
-                if (c0 + c < p.C) v = p.LUT[(size_t)(c0 + c) * 256 + key];
-                *reinterpret_cast<float*>(lds_bytes + gemv8_slot_offset(cL, td, e) + key * 256) = v;
-            }
+        };
+        u32x4 k[Q], kn[Q];
+        float al[Q], aln[Q];
+        load_step(wave, k, al);
+        if constexpr (FUSED) gemv8_build_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
+        else gemv8_copy_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
+        __syncthreads();
+        for (int s = wave; s < nsteps; s += nwaves) {
+            load_step(s + nwaves, kn, aln);
+            float y = 0.0f;
+#pragma unroll
+            for (int i = 0; i < Q; ++i) y = fmaf(al[i], lookup16(k[i]), y);
+            y = reduce8(y);
+            const int row = 8 * s + rsub;
+            if (L == 0 && row < nrows) p.out[(size_t)sp * p.m + r0 + row] = y;
+#pragma unroll
+            for (int i = 0; i < Q; ++i) { k[i] = kn[i]; al[i] = aln[i]; }
         }
+        return;
+    }
+
+    // ---- throughput mode.  Rows are handled in blocks of 64: in step t (0..7) row group g of
+    // the wave reads row 8*g + t of the block, and the lane with L == t keeps the row's sum, so
+    // that after the 8 steps lane j holds row j of the block: alpha and Y are accessed coalesced.
+    const int nblk = (nrows + 63) >> 6;
+    for (int tile = tile0; tile < tile1; ++tile) {
+        if (tile != tile0) __syncthreads();  // every wave is done with the previous tables
+        if constexpr (FUSED) gemv8_build_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
+        else gemv8_copy_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
         __syncthreads();
 
-        // ---- stream the rows ---------------------------------------------------------------------
         const bool have_keys = (uint32_t)(tile * 128 + L * 16) < stride_bytes;
         const char* kbase[Q];
 #pragma unroll
@@ -175,7 +221,7 @@ __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
 
         auto load_iter = [&](int bk, int t, u32x4 (&k)[Q]) {
             const uint32_t row = (uint32_t)(64 * bk + 8 * rsub + t);  // relative to r0
-            const bool ok = have_keys && bk < nblk && (int)row < r1 - r0;
+            const bool ok = have_keys && bk < nblk && (int)row < nrows;
             const uint32_t voff = row * stride_bytes + (uint32_t)(16 * L);
 #pragma unroll
             for (int i = 0; i < Q; ++i) {
@@ -193,7 +239,7 @@ __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
         for (int s = 0; s < PD; ++s) load_iter(bk, s, buf[s]);
         for (; bk < nblk; bk += nwaves) {
             const int row_l = 64 * bk + lane;  // the row this lane finishes, relative to r0
-            const bool row_ok = row_l < r1 - r0;
+            const bool row_ok = row_l < nrows;
             float al[Q], keep[Q];
 #pragma unroll
             for (int i = 0; i < Q; ++i) {

@@ -90,13 +90,12 @@ __global__ __launch_bounds__(256) void build_lut_kernel(const float* __restrict_
     const long long rest = gid / batch;
     const int h = (int)(rest % HG);
     const int c = (int)(rest / HG);
-    float x[8], lo[16];
+    float x[8], ent[16];
     load_chunk_x<MU>(X, n, batch, a, c, x);
-    table_lo(x, lo);
-    const float hi = table_hi(x, (uint32_t)h);
+    table16(x, (uint32_t)h, ent);
     float* dst = LUT + ((size_t)c * E + (size_t)h * 16) * batch + a;
 #pragma unroll
-    for (int l = 0; l < LN; ++l) dst[(size_t)l * batch] = lo[l] + hi;
+    for (int l = 0; l < LN; ++l) dst[(size_t)l * batch] = ent[l];
 }
 
 // =====================================================================================
@@ -121,6 +120,7 @@ struct QueryParams {
     int tiles, tps, splits;
     int rows_per_wg, row_blocks, batch_tiles;
     int ntasks, tasks_per_xcd;
+    int row_mode;  // mu = 8 kernels: 0 = 64-row blocks per wave, 1 = one row step per wave
 };
 
 template <int MU, int BT, int T>
@@ -198,20 +198,18 @@ __global__ __launch_bounds__(1024) void query_kernel(const QueryParams p) {
                 const int r2 = job / BT;
                 const int h = r2 % HG;
                 const int ct = r2 / HG;
-                float x[8], lo[16];
+                float x[8], ent[16];
                 load_chunk_x<MU>(p.X, p.n, p.batch, b0 + col, c0 + ct, x);
-                table_lo(x, lo);
-                const float hi = table_hi(x, (uint32_t)h);
+                table16(x, (uint32_t)h, ent);
                 float* dst = tables + ((size_t)ct * E + h * 16) * BT + col;
                 if constexpr (BT == 1 && LN >= 4) {
 #pragma unroll
                     for (int l4 = 0; l4 < LN / 4; ++l4)
                         *reinterpret_cast<float4*>(dst + 4 * l4) =
-                            make_float4(lo[4 * l4] + hi, lo[4 * l4 + 1] + hi, lo[4 * l4 + 2] + hi,
-                                        lo[4 * l4 + 3] + hi);
+                            make_float4(ent[4 * l4], ent[4 * l4 + 1], ent[4 * l4 + 2], ent[4 * l4 + 3]);
                 } else {
 #pragma unroll
-                    for (int l = 0; l < LN; ++l) dst[l * BT] = lo[l] + hi;
+                    for (int l = 0; l < LN; ++l) dst[l * BT] = ent[l];
                 }
             }
         } else {

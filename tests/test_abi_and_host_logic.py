@@ -117,6 +117,10 @@ def test_argument_errors_are_reported_before_any_launch(biq):
     bad = biq.BiqPlan()
     bad.threads, bad.chunks_per_tile, bad.batch_tile, bad.tiles_per_split, bad.rows_per_wg = 100, 16, 1, 1, 1
     assert lib.biq_gemm_ex(fake, fake, fake, fake, 4, 4, 1, 1, 8, ctypes.byref(bad), None, 0, None) == biq.BIQ_EINVAL
+    bad.row_mode = 1  # latency mode exists only in the mu = 8 kernels
+    bad.threads, bad.chunks_per_tile = 256, 16
+    assert lib.biq_gemm_ex(fake, fake, fake, fake, 4, 4, 1, 1, 8, ctypes.byref(bad), None, 0, None) == biq.BIQ_EINVAL
+    bad.row_mode = 0
     bad.threads, bad.chunks_per_tile = 256, 24  # not a power-of-two number of units
     assert lib.biq_gemm_ex(fake, fake, fake, fake, 4, 4, 1, 1, 8, ctypes.byref(bad), None, 0, None) == biq.BIQ_EINVAL
     bad.chunks_per_tile, bad.batch_tile = 256, 8  # tables would not fit LDS

@@ -200,10 +200,10 @@ def test_query_with_tables_from_memory_matches_fused(biq, oracle):
         assert_within_tolerance(Y.cpu().numpy(), oracle.gemm_dense(B, alpha, X), alpha, X, "query")
 
 
-def _plan(biq, kernel, threads, ct, bt, tps, rows):
+def _plan(biq, kernel, threads, ct, bt, tps, rows, row_mode=0):
     plan = biq.BiqPlan()
     plan.kernel, plan.threads, plan.chunks_per_tile, plan.batch_tile = kernel, threads, ct, bt
-    plan.tiles_per_split, plan.rows_per_wg = tps, rows
+    plan.tiles_per_split, plan.rows_per_wg, plan.row_mode = tps, rows, row_mode
     return plan
 
 
@@ -218,20 +218,23 @@ def test_explicit_plans_give_the_same_result(biq, oracle):
     plans = [(0, 64, 16, 1, 1, 5), (0, 256, 32, 4, 3, 64), (0, 512, 64, 2, 100, 700),
              (0, 1024, 128, 1, 2, 33), (0, 128, 16, 8, 7, 1),
              # batched mu=8 kernel: 64-chunk tiles of 2 vectors
-             (2, 1024, 64, 2, 1, 64), (2, 512, 64, 2, 2, 128), (2, 256, 64, 2, 6, 704), (2, 64, 64, 2, 3, 100)]
-    for kernel, threads, ct, bt, tps, rows in plans:
-        _say("plan kernel=%d threads=%d ct=%d bt=%d tps=%d rows=%d" % (kernel, threads, ct, bt, tps, rows))
-        Y = gpu_gemm(biq, K, ad, Xd, m, n, q, mu, plan=_plan(biq, kernel, threads, ct, bt, tps, rows)).cpu().numpy()
+             (2, 1024, 64, 2, 1, 64), (2, 512, 64, 2, 2, 128), (2, 256, 64, 2, 6, 704), (2, 64, 64, 2, 3, 100),
+             # ... in latency mode (one step of 16 rows per wave)
+             (2, 1024, 64, 2, 1, 256, 1), (2, 256, 64, 2, 1, 700, 1), (2, 64, 64, 2, 1, 17, 1)]
+    for spec in plans:
+        _say("plan " + str(spec))
+        Y = gpu_gemm(biq, K, ad, Xd, m, n, q, mu, plan=_plan(biq, *spec)).cpu().numpy()
         assert_within_tolerance(Y, ref, alpha, X, "plan")
     # GEMV kernel plans (batch 1)
     B, alpha, X = _rand_inputs(m, n, 3, 1, 7001)
     Bd, ad, Xd = device_inputs(B, alpha, X)
     K = gpu_pack(biq, Bd, mu)
     ref = oracle.gemm_dense(B, alpha, X)
-    for kernel, threads, ct, bt, tps, rows in [(1, 1024, 128, 1, 1, 64), (1, 512, 128, 1, 3, 700),
-                                               (1, 64, 128, 1, 2, 130), (0, 256, 64, 1, 1, 50)]:
-        _say("plan kernel=%d threads=%d ct=%d bt=%d tps=%d rows=%d" % (kernel, threads, ct, bt, tps, rows))
-        Y = gpu_gemm(biq, K, ad, Xd, m, n, 3, mu, plan=_plan(biq, kernel, threads, ct, bt, tps, rows)).cpu().numpy()
+    for spec in [(1, 1024, 128, 1, 1, 64), (1, 512, 128, 1, 3, 700), (1, 64, 128, 1, 2, 130),
+                 (0, 256, 64, 1, 1, 50), (1, 1024, 128, 1, 1, 128, 1), (1, 128, 128, 1, 1, 700, 1),
+                 (1, 64, 128, 1, 1, 9, 1)]:
+        _say("plan " + str(spec))
+        Y = gpu_gemm(biq, K, ad, Xd, m, n, 3, mu, plan=_plan(biq, *spec)).cpu().numpy()
         assert_within_tolerance(Y, ref, alpha, X, "plan")
 
 
