@@ -206,12 +206,10 @@ __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
     // the wave reads row 8*g + t of the block, and the lane with L == t keeps the row's sum, so
     // that after the 8 steps lane j holds row j of the block: alpha and Y are accessed coalesced.
     const int nblk = (nrows + 63) >> 6;
+    // ring of PD steps in flight per wave (PD * Q KiB); fewer for many planes to stay inside
+    // 128 VGPRs
+    constexpr int PD = (Q <= 2) ? 4 : (Q == 3 ? 2 : 1);
     for (int tile = tile0; tile < tile1; ++tile) {
-        if (tile != tile0) __syncthreads();  // every wave is done with the previous tables
-        if constexpr (FUSED) gemv8_build_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
-        else gemv8_copy_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
-        __syncthreads();
-
         const bool have_keys = (uint32_t)(tile * 128 + L * 16) < stride_bytes;
         const char* kbase[Q];
 #pragma unroll
@@ -230,13 +228,17 @@ __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
             }
         };
 
-        // ring of PD steps in flight per wave (PD * Q KiB); fewer for many planes to stay
-        // inside 128 VGPRs
-        constexpr int PD = (Q <= 2) ? 4 : (Q == 3 ? 2 : 1);
+        // the first steps' keys are requested before the tables are (re)built
         u32x4 buf[PD][Q];
         int bk = wave;
 #pragma unroll
         for (int s = 0; s < PD; ++s) load_iter(bk, s, buf[s]);
+
+        if (tile != tile0) __syncthreads();  // every wave is done with the previous tables
+        if constexpr (FUSED) gemv8_build_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
+        else gemv8_copy_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
+        __syncthreads();
+
         for (; bk < nblk; bk += nwaves) {
             const int row_l = 64 * bk + lane;  // the row this lane finishes, relative to r0
             const bool row_ok = row_l < nrows;
