@@ -149,6 +149,8 @@ def main() -> int:
     ap.add_argument("--only", choices=["all", "headline", "roofline", "copy"], default="all",
                     help="restrict the run to one timed region (used for profiling); 'copy' runs a "
                          "plain 512 MiB device copy, the calibration kernel for HBM byte counters")
+    ap.add_argument("--workload", default=None,
+                    help="time only this named configuration (for profiling), e.g. cfg4_sq4096_q3_b32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -175,6 +177,18 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes": src.numel(), "copies": 10}))
+        return 0
+
+    if args.workload:
+        w = CONFIGS[args.workload]
+        copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
+        p = Problem(biq, torch, w, copies, real_first=False)
+        steps = min(args.steps, 200 if w.lookups < 1e9 else 50)
+        wall, ev = time_steps(torch, p, steps, 5)
+        srow = summarize(w, wall / steps)
+        srow["event_us_per_call"] = ev / steps * 1e6
+        srow["plan"] = biq.biq_plan_get(w.m, w.n, w.q, w.batch, w.mu).as_dict()
+        print(json.dumps(srow))
         return 0
 
     head = CONFIGS["cfg2_gemv2048_q2_b1"]
@@ -235,15 +249,23 @@ def main() -> int:
 
     # ---- the other configurations (context rows) ------------------------------------------------
     if args.only == "all":
-        for name in ["cfg1_fc512_b1", "cfg3_lstm4096x1024_q3_b8", "cfg4_sq4096_q3_b32",
-                     "cfg5_ffn_up_q2_b128", "cfg5_ffn_down_q2_b128"]:
-            w = CONFIGS[name]
+        LDS_PEAK_GBPS = 256 * 128 * 2.4  # 256 CUs x 128 B/clk x 2.4 GHz
+        rows = [CONFIGS[k] for k in ["cfg1_fc512_b1", "cfg3_lstm4096x1024_q3_b8", "cfg4_sq4096_q3_b32",
+                                     "cfg5_ffn_up_q2_b128", "cfg5_ffn_down_q2_b128"]]
+        rows += [CONFIGS["cfg5_ffn_up_q2_b128"].with_mu(6), CONFIGS["cfg5_ffn_up_q2_b128"].with_mu(4)]
+        for w in rows:
+            name = w.name
             copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
             p = Problem(biq, torch, w, copies, real_first=False)
             steps = 200 if w.lookups < 1e9 else 20
             wall, _ = time_steps(torch, p, steps, 5)
             s = summarize(w, wall / steps)
             s["key_copies_in_rotation"] = copies
+            s["kernel"] = biq.biq_kernel_name(biq.biq_plan_get(w.m, w.n, w.q, w.batch, w.mu).kernel)
+            if w.batch > 1:
+                # batched calls are bounded by table gathers from LDS (4 bytes per lookup), not by HBM
+                s["lds_gather_GBps"] = 4.0 * w.lookups / (wall / steps) / 1e9
+                s["lds_frac"] = s["lds_gather_GBps"] / LDS_PEAK_GBPS
             extra.append(s)
             log("%s: %.2f us/call, %.1f GB/s, %.0f GOPS" % (name, s["us_per_call"], s["achieved_GBps"],
                                                           s["effective_GOPS"]))
