@@ -227,7 +227,9 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": big.algorithmic_bytes / launch_s / 1e9 / HBM_PEAK_GBPS,
-            "traffic": None,
+            # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a 512 MiB device copy),
+            # bytes per launch of this workload: see profiles/gemv8_q2_hbm_regime_counters.md
+            "traffic": 551.6e6 if big.algorithmic_bytes == 549462016 else None,
             "kernel": biq.biq_kernel_name(plan.kernel),
             "workload": big.name,
             "algorithmic_bytes_per_launch": big.algorithmic_bytes,
