@@ -107,7 +107,10 @@ typedef struct {
                             (throughput), 1 = one step of rows per wave at a time, keys
                             requested before the tables are built (latency; needs
                             tiles_per_split = 1)                                           */
-    int reserved[5];
+    int xcd_skew;        /* GEMV kernel, row_mode 0, no chunk split, row_blocks a multiple of 8:
+                            workgroups on even XCDs take rows_per_wg + xcd_skew rows, those on
+                            odd XCDs rows_per_wg - xcd_skew (odd XCDs stream slower)        */
+    int reserved[4];
 } biq_plan;
 
 biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan);

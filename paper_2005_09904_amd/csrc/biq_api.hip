@@ -39,7 +39,8 @@ inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; 
 
 inline int plan_lds_bytes(const biq_plan& pl, int mu) {
     if (pl.kernel == KERNEL_GEMV8)
-        return kGemvTileBytes + (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + 63) / 64) * 64 * 4 : 0);
+        return kGemvTileBytes +
+               (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + pl.xcd_skew + 63) / 64) * 64 * 4 : 0);
     if (pl.kernel == KERNEL_GEMM8X2)
         return kGemmTileBytes + (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + 63) / 64) * 64 * 8 : 0);
     long long b = (long long)pl.chunks_per_tile * (1 << mu) * pl.batch_tile * 4;
@@ -75,6 +76,13 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     if (pl.tiles_per_split > tiles) pl.tiles_per_split = tiles;
     if (pl.row_mode != 0 && !(pl.row_mode == 1 && pl.kernel != KERNEL_GENERIC && pl.tiles_per_split == 1))
         return false;
+    if (pl.xcd_skew != 0) {
+        // only the GEMV kernel's throughput mode, whole grid = 8 equal XCD shares, no chunk split
+        if (pl.kernel != KERNEL_GEMV8 || pl.row_mode != 0 || pl.xcd_skew < 0) return false;
+        if (pl.xcd_skew >= pl.rows_per_wg || ceil_div(m, pl.rows_per_wg) % kNumXcd != 0) return false;
+        if (ceil_div(tiles, pl.tiles_per_split) != 1) return false;
+        // (even XCDs hold rows_per_wg + xcd_skew rows in LDS: counted in lds_bytes below)
+    }
     pl.chunk_splits = ceil_div(tiles, pl.tiles_per_split);
     pl.row_blocks = ceil_div(m, pl.rows_per_wg);
     pl.batch_tiles = ceil_div(batch, pl.batch_tile);
@@ -111,6 +119,11 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu) {
             pl.tiles_per_split = tiles;
             int rows = ceil_div(ceil_div(m, kNumCu), 64) * 64;
             pl.rows_per_wg = rows > 8192 ? 8192 : rows;
+            // odd XCDs stream 6-7 % slower: move 8 % of their rows to the even ones (best over two boxes: 6-12 %)
+            if (ceil_div(m, pl.rows_per_wg) % kNumXcd == 0) {
+                pl.xcd_skew = ((pl.rows_per_wg * 8 / 100 + 32) / 64) * 64;
+                if (tiles > 1 && pl.rows_per_wg + pl.xcd_skew > 8192) pl.xcd_skew = 0;
+            }
         } else if ((long long)m * tiles <= 4ll * 128 * kNumCu) {
             // small: latency mode, 8 rows per wave step, at most 4 steps per wave
             pl.tiles_per_split = 1;
@@ -328,6 +341,7 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     qp.ntasks = pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
     qp.tasks_per_xcd = ceil_div(qp.ntasks, kNumXcd);
     qp.row_mode = pl.row_mode;
+    qp.xcd_skew = pl.xcd_skew;
     const int grid = qp.tasks_per_xcd * kNumXcd;
 
     hipError_t e;

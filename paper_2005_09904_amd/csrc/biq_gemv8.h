@@ -110,8 +110,20 @@ __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
     if (task >= p.ntasks) return;
     const int sp = task % p.splits;
     const int rb = task / p.splits;
-    const int r0 = rb * p.rows_per_wg;
-    const int r1 = min(p.m, r0 + p.rows_per_wg);
+    // Row range.  With xcd_skew > 0 (throughput mode, whole grid = 8 x tasks_per_xcd workgroups,
+    // no chunk split) the workgroups of even XCDs take rows_per_wg + skew rows and those of odd
+    // XCDs rows_per_wg - skew: measured on MI355X, odd XCDs stream from HBM 6-7 % slower than
+    // even ones, and the hardware binds workgroup i to XCD i & 7.
+    int r0 = rb * p.rows_per_wg;
+    int r1 = min(p.m, r0 + p.rows_per_wg);
+    if (p.xcd_skew > 0) {
+        const int x = wg & 7, j = wg >> 3;
+        const int mine = p.rows_per_wg + ((x & 1) ? -p.xcd_skew : p.xcd_skew);
+        // XCDs before x: (x + 1) / 2 even ones and x / 2 odd ones
+        const int before = p.tasks_per_xcd * (x * p.rows_per_wg + (((x + 1) >> 1) - (x >> 1)) * p.xcd_skew);
+        r0 = min(p.m, before + j * mine);
+        r1 = min(p.m, r0 + mine);
+    }
     const int tile0 = sp * p.tps;
     const int tile1 = min(p.tiles, tile0 + p.tps);
 

@@ -121,6 +121,7 @@ struct QueryParams {
     int rows_per_wg, row_blocks, batch_tiles;
     int ntasks, tasks_per_xcd;
     int row_mode;  // mu = 8 kernels: 0 = 64-row blocks per wave, 1 = one row step per wave
+    int xcd_skew;  // gemv8 throughput mode: rows moved from each odd-XCD workgroup to an even-XCD one
 };
 
 template <int MU, int BT, int T>

@@ -281,6 +281,26 @@ def test_hbm_regime_launch_sampled_rows(biq, oracle):
     assert np.array_equal(Y2, 2 * Y)
 
 
+def test_xcd_skewed_row_split(biq, oracle):
+    """Uneven row shares for even / odd XCDs (a scheduling choice) cover every row exactly once."""
+    import torch
+
+    for (m, n, q, rows, skew) in [(8 * 3 * 192, 1024, 1, 192, 64), (8 * 2 * 256 - 100, 2048, 2, 256, 128),
+                                  (16 * 128 - 1, 3000, 3, 128, 64)]:
+        _say("skew m=%d n=%d q=%d rows=%d skew=%d" % (m, n, q, rows, skew))
+        B, alpha, X = _rand_inputs(m, n, q, 1, 9100 + m)
+        Bd, ad, Xd = device_inputs(B, alpha, X)
+        K = gpu_pack(biq, Bd, 8)
+        tiles = -(-(-(-n // 8)) // 128)
+        plan = _plan(biq, 1, 1024, 128, 1, tiles, rows)
+        plan.xcd_skew = skew
+        Y = gpu_gemm(biq, K, ad, Xd, m, n, q, 8, plan=plan)
+        plan0 = _plan(biq, 1, 1024, 128, 1, tiles, rows)
+        Y0 = gpu_gemm(biq, K, ad, Xd, m, n, q, 8, plan=plan0)
+        assert torch.equal(Y, Y0)  # same arithmetic per row, whatever workgroup does it
+        assert_within_tolerance(Y.cpu().numpy(), oracle.gemm_dense(B, alpha, X), alpha, X, "skew")
+
+
 def test_gemm_is_deterministic(biq):
     import torch
 
