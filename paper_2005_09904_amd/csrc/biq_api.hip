@@ -6,6 +6,7 @@
 #include "biq_kernels.h"
 #include "biq_gemv8.h"
 #include "biq_gemm8x2.h"
+#include "biq_unpack_mfma.h"
 
 namespace {
 
@@ -16,8 +17,9 @@ constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kLdsTableBudget = 128 * 1024;  // tables of one tile (leaves room for 1 WG/CU extras)
 constexpr int kNumCu = 256;
 constexpr int kNumXcd = 8;
+constexpr int kUnpackMinBatch = 64;  // from this many input vectors on, biq_gemm unpacks into the matrix cores
 
-enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL_COUNT };
+enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL_UNPACK_MFMA = 3, KERNEL_COUNT };
 
 inline bool shape_ok(int m, int n, int q, int batch, int mu) {
     if (m < 1 || n < 1 || q < 1 || batch < 1) return false;
@@ -37,6 +39,34 @@ inline int unit_keys(int mu) {
 inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
 
+// Unpack-MFMA kernel: row tiles per wave and plane, by number of planes (a wave holds all planes
+// of its rows so that Eq. 2's sum over planes stays in registers).
+inline int unpack_rpw(int q) { return q == 1 ? 4 : (q == 2 ? 2 : 1); }
+// 16-byte pieces of prepared input per pipeline stage: 4 MFMA steps x column tiles x 3 bf16 terms x 64 lanes
+inline long long unpack_stage_pieces(int batch_tile) { return 4ll * (batch_tile / 32) * 3 * 64; }
+
+// Unpack-MFMA plans: fixed workgroup shape, key groups (32 key bytes of a row) instead of LUT tiles.
+bool plan_finish_unpack(biq_plan& pl, int m, int n, int q, int batch) {
+    if (q > 4 || pl.threads != kUnpackThreads) return false;
+    if (pl.batch_tile != 32 && pl.batch_tile != 64) return false;
+    if (pl.chunks_per_tile != kUnpackGroupBytes) return false;
+    if (pl.rows_per_wg != 128 * unpack_rpw(q)) return false;
+    if (pl.row_mode != 0 || pl.xcd_skew != 0 || pl.tiles_per_split < 1) return false;
+    const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
+    if (pl.tiles_per_split > groups) pl.tiles_per_split = groups;
+    pl.chunk_splits = (groups + pl.tiles_per_split - 1) / pl.tiles_per_split;
+    pl.row_blocks = (m + pl.rows_per_wg - 1) / pl.rows_per_wg;
+    pl.batch_tiles = (batch + pl.batch_tile - 1) / pl.batch_tile;
+    pl.lds_bytes = (int)(2 * unpack_stage_pieces(pl.batch_tile) * 16);
+    const long long tasks = (long long)pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
+    if (tasks > (1ll << 30)) return false;
+    // prepared input: 6 bytes per (padded column, padded element)
+    const long long xf = (long long)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split * 4 *
+                         unpack_stage_pieces(pl.batch_tile) * 16;
+    if (xf > (1ll << 40)) return false;
+    return true;
+}
+
 inline int plan_lds_bytes(const biq_plan& pl, int mu) {
     if (pl.kernel == KERNEL_GEMV8)
         return kGemvTileBytes +
@@ -53,6 +83,7 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     const int UK = unit_keys(mu);
     const int C = ceil_div(n, mu);
     if (pl.kernel < 0 || pl.kernel >= KERNEL_COUNT) return false;
+    if (pl.kernel == KERNEL_UNPACK_MFMA) return plan_finish_unpack(pl, m, n, q, batch);
     if (pl.threads < 64 || pl.threads > 1024 || pl.threads % 64) return false;
     if (pl.kernel == KERNEL_GEMV8) {
         // mu = 8, one input vector, at most 4 planes; one 128-chunk tile per workgroup
@@ -99,11 +130,31 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
 //  - chunk splits: bounded so that the partial sums written stay below about twice the
 //    bytes the method has to move anyway
 //  - rows per workgroup: enough workgroups to fill the 256 CUs several times over
-void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu) {
+void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tables_given = false) {
     const int UK = unit_keys(mu);
     const int C = ceil_div(n, mu);
     const int E = 1 << mu;
     pl = biq_plan{};
+    if (!tables_given && q <= 4 && batch >= kUnpackMinBatch) {
+        // Many input vectors: the contraction is compute bound and the matrix cores beat the
+        // table lookups (the crossover of Sec. IV-B / Fig. 10).  Key groups are split over
+        // workgroups only as far as needed to give every CU a workgroup.
+        pl.kernel = KERNEL_UNPACK_MFMA;
+        pl.threads = kUnpackThreads;
+        pl.chunks_per_tile = kUnpackGroupBytes;
+        pl.batch_tile = batch > 32 ? 64 : 32;
+        pl.rows_per_wg = 128 * unpack_rpw(q);
+        const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
+        const long long wgs = (long long)ceil_div(m, pl.rows_per_wg) * ceil_div(batch, pl.batch_tile);
+        int S = 1;
+        if (wgs < kNumCu) {
+            S = ceil_div(kNumCu, wgs);
+            if (S > groups) S = groups;
+        }
+        pl.tiles_per_split = ceil_div(groups, S);
+        plan_finish(pl, m, n, q, batch, mu);
+        return;
+    }
     if (mu == 8 && batch == 1 && q <= 4) {
         // GEMV: workgroups of 1024 threads, 128-chunk tiles, one workgroup per CU when the
         // rows allow it (every further round of workgroups pays the table build again).  With
@@ -202,8 +253,17 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     plan_finish(pl, m, n, q, batch, mu);
 }
 
+// Bytes of the prepared-input area at the start of the workspace (unpack-MFMA plans only).
+size_t plan_xf_bytes(const biq_plan& pl) {
+    if (pl.kernel != KERNEL_UNPACK_MFMA) return 0;
+    const size_t b = (size_t)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split * 4 *
+                     (size_t)unpack_stage_pieces(pl.batch_tile) * 16;
+    return (b + 255) & ~(size_t)255;
+}
+
 size_t plan_workspace(const biq_plan& pl, int m, int batch) {
-    return pl.chunk_splits > 1 ? (size_t)pl.chunk_splits * batch * m * sizeof(float) : 0;
+    return plan_xf_bytes(pl) +
+           (pl.chunk_splits > 1 ? (size_t)pl.chunk_splits * batch * m * sizeof(float) : 0);
 }
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -298,6 +358,76 @@ hipError_t launch_gemm8x2(int q, const QueryParams& qp, int grid, int threads, i
     }
 }
 
+template <int Q, int RPW, int CT>
+hipError_t launch_unpack_inst(const UnpackParams& up, int grid, int lds, hipStream_t s) {
+    auto kern = unpack_mfma_kernel<Q, RPW, CT>;
+    static bool granted = false;
+    if (!granted) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+        if (e != hipSuccess) return e;
+        granted = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kUnpackThreads), lds, s, up);
+    return hipGetLastError();
+}
+
+template <int CT>
+hipError_t launch_unpack(int q, const UnpackParams& up, int grid, int lds, hipStream_t s) {
+    switch (q) {
+        case 1: return launch_unpack_inst<1, 4, CT>(up, grid, lds, s);
+        case 2: return launch_unpack_inst<2, 2, CT>(up, grid, lds, s);
+        case 3: return launch_unpack_inst<3, 1, CT>(up, grid, lds, s);
+        default: return launch_unpack_inst<4, 1, CT>(up, grid, lds, s);
+    }
+}
+
+// Large-batch path: split X into bf16 terms in MFMA operand order (workspace), contract, and
+// sum the partial results when the key groups were split over workgroups.
+biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* alpha, const float* X,
+                           float* Y, int m, int n, int q, int batch, void* workspace, hipStream_t s) {
+    const int CT = pl.batch_tile / 32;
+    const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
+    const int stages = groups * kUnpackStagesPerGroup;
+    mfma_u32x4* Xf = reinterpret_cast<mfma_u32x4*>(workspace);
+    float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + plan_xf_bytes(pl));
+
+    const long long total = (long long)pl.batch_tiles * stages * 4 * CT * 64;
+    const unsigned sgrid = (unsigned)((total + 255) / 256);
+    if (CT == 2)
+        hipLaunchKernelGGL(xsplit_kernel<2>, dim3(sgrid), dim3(256), 0, s, X, Xf, n, batch, stages, total);
+    else
+        hipLaunchKernelGGL(xsplit_kernel<1>, dim3(sgrid), dim3(256), 0, s, X, Xf, n, batch, stages, total);
+    if (hipGetLastError() != hipSuccess) return BIQ_EHIP;
+
+    UnpackParams up{};
+    up.K = K;
+    up.alpha = alpha;
+    up.Xf = Xf;
+    up.out = pl.chunk_splits > 1 ? partial : Y;
+    up.m = m;
+    up.batch = batch;
+    up.stride_bytes = (uint32_t)biq_key_row_stride(n);
+    up.groups = groups;
+    up.gps = pl.tiles_per_split;
+    up.splits = pl.chunk_splits;
+    up.row_blocks = pl.row_blocks;
+    up.col_groups = pl.batch_tiles;
+    up.ntasks = pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
+    up.tasks_per_xcd = ceil_div(up.ntasks, kNumXcd);
+    const int grid = up.tasks_per_xcd * kNumXcd;
+    const hipError_t e = CT == 2 ? launch_unpack<2>(q, up, grid, pl.lds_bytes, s)
+                                 : launch_unpack<1>(q, up, grid, pl.lds_bytes, s);
+    if (e != hipSuccess) return BIQ_EHIP;
+    if (pl.chunk_splits > 1) {
+        const long long count = (long long)batch * m;
+        hipLaunchKernelGGL(reduce_splits_kernel, dim3(ceil_div(count, 256)), dim3(256), 0, s, partial, Y,
+                           count, pl.chunk_splits);
+        if (hipGetLastError() != hipSuccess) return BIQ_EHIP;
+    }
+    return BIQ_OK;
+}
+
 biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const float* X,
                      const float* LUT, float* Y, int m, int n, int q, int batch, int mu,
                      const biq_plan* user_plan, void* workspace, size_t workspace_bytes,
@@ -311,14 +441,17 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
         pl = *user_plan;
         if (!plan_finish(pl, m, n, q, batch, mu)) return BIQ_EINVAL;
     } else {
-        plan_default(pl, m, n, q, batch, mu);
+        plan_default(pl, m, n, q, batch, mu, !fused);
     }
+    if (pl.kernel == KERNEL_UNPACK_MFMA && !fused) return BIQ_EINVAL;  // that kernel reads X, not tables
     const size_t need = plan_workspace(pl, m, batch);
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return BIQ_EWORKSPACE;
         if (!aligned(workspace, 16)) return BIQ_EINVAL;
     }
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (pl.kernel == KERNEL_UNPACK_MFMA)
+        return run_unpack_mfma(pl, K, alpha, X, Y, m, n, q, batch, workspace, s);
 
     QueryParams qp{};
     qp.K = reinterpret_cast<const uint32_t*>(K);
@@ -416,9 +549,13 @@ size_t biq_plan_workspace_bytes(const biq_plan* plan, int m, int batch) {
 
 size_t biq_workspace_bytes(int m, int n, int q, int batch, int mu) {
     if (!shape_ok(m, n, q, batch, mu)) return 0;
+    // the larger of what biq_gemm's and biq_query's default plans need
     biq_plan pl;
-    plan_default(pl, m, n, q, batch, mu);
-    return plan_workspace(pl, m, batch);
+    plan_default(pl, m, n, q, batch, mu, false);
+    const size_t a = plan_workspace(pl, m, batch);
+    plan_default(pl, m, n, q, batch, mu, true);
+    const size_t b = plan_workspace(pl, m, batch);
+    return a > b ? a : b;
 }
 
 const char* biq_kernel_name(int kernel) {
@@ -426,6 +563,7 @@ const char* biq_kernel_name(int kernel) {
         case KERNEL_GENERIC: return "query_generic";
         case KERNEL_GEMV8: return "gemv8";
         case KERNEL_GEMM8X2: return "gemm8x2";
+        case KERNEL_UNPACK_MFMA: return "unpack_mfma";
     }
     return "unknown";
 }

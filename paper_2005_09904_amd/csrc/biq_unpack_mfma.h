@@ -1,0 +1,289 @@
+// Large-batch path: "GEMM with unpacking" (Sec. IV-B, Algorithm 3) as a dense MFMA contraction.
+//
+// For many input vectors the product is compute bound and the lookup tables stop paying off
+// (the crossover discussed with Fig. 10); the alternative the paper measures is to unpack the
+// sign bits and run an ordinary GEMM.  Here the unpacking happens in registers, straight into
+// the A operand of v_mfma_f32_32x32x16_bf16, and nothing unpacked ever reaches memory:
+//   - a weight bit becomes the bf16 value +1.0 / -1.0 (bit set <-> +1, as in Algorithm 3);
+//   - every fp32 input x is split once into three bf16 terms x = x0 + x1 + x2 (8 significand
+//     bits each, by truncation, so the sum is exact); +-1 * bf16 products are exact and the
+//     matrix cores accumulate in fp32, so the result differs from a plain fp32 evaluation of
+//     Eq. 2 only by the order of the additions;
+//   - the three terms are three B operands multiplied with the same A operand.
+// The kernel does not depend on mu: it reads the packed bitmap, which is the same for all mu.
+//
+// MFMA operand layout (32x32x16, wave of 64 lanes, lane = 32*h + r):
+//   A: lane holds row r of the tile, 8 consecutive k of half h     -> one key byte per lane
+//   B: lane holds column r, the same 8 k of half h                 -> 8 bf16 of one input vector
+//   C: lane holds column r, rows 8*(v/4) + 4*h + v%4 for v = 0..15
+// A lane loads 16 key bytes of its row at once: half 0 takes bytes [32g, 32g+16) of the row,
+// half 1 bytes [32g+16, 32g+32) ("key group" g).  Each of the lane's four key dwords feeds four
+// MFMA steps (see unpack_step for which bits go to which step): the k order of the contraction
+// is a permutation of the columns, which the B side follows.
+//
+// B operands are prepared by xsplit_kernel in exactly the order the main kernel consumes them:
+//   Xf[col_group][stage][step 0..3][col_tile][term 0..2][lane] : 16 bytes (8 bf16)
+// with stage = 4 consecutive MFMA steps (one dword of every lane's 16 key bytes), so a
+// workgroup stages one contiguous block per stage into LDS (double buffered) and its four
+// waves read their fragments from there with conflict-free 128-bit reads.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace biq {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t mfma_u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kUnpackThreads = 256;     // 4 waves
+constexpr int kUnpackGroupBytes = 32;   // key bytes of a row per key group (both halves)
+constexpr int kUnpackStagesPerGroup = 4;
+
+struct UnpackParams {
+    const uint8_t* K;        // [q][m][stride]
+    const float* alpha;      // [q][m]
+    const mfma_u32x4* Xf;    // prepared B operands (see above)
+    float* out;              // Y [batch][m], or partials [splits][batch][m]
+    int m, batch;
+    uint32_t stride_bytes;
+    int groups;              // key groups per row = ceil(stride / 32)
+    int gps;                 // key groups per split
+    int splits;
+    int row_blocks, col_groups;
+    int ntasks, tasks_per_xcd;
+};
+
+// Splits fp32 into three bf16 terms by truncation; returns them as the high halves' bit patterns.
+__device__ __forceinline__ void split3(float x, uint32_t& t0, uint32_t& t1, uint32_t& t2) {
+    const uint32_t b0 = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(b0);       // exact: the low 16 significand bits
+    const uint32_t b1 = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(b1);      // exact: at most 8 significand bits left
+    t0 = b0 >> 16;
+    t1 = b1 >> 16;
+    t2 = __float_as_uint(r2) >> 16;                 // exact in bf16
+}
+
+// One thread per (col_group, stage, step, col_tile, lane): the three 16-byte B fragments of
+// that lane.  Columns past the batch and elements past n are zero.
+template <int CT>
+__global__ __launch_bounds__(256) void xsplit_kernel(const float* __restrict__ X,
+                                                     mfma_u32x4* __restrict__ Xf, int n, int batch,
+                                                     int stages, long long total) {
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int lane = (int)(idx & 63);
+    long long rest = idx >> 6;
+    const int ct = (int)(rest % CT); rest /= CT;
+    const int ks = (int)(rest & 3); rest >>= 2;
+    const int st = (int)(rest % stages);
+    const int cg = (int)(rest / stages);
+    const int col = (cg * CT + ct) * 32 + (lane & 31);
+    const int h = lane >> 5;
+    // dword of the row this stage works on, and the 2 x 4 consecutive elements of this step
+    const long long dw = 8ll * (st >> 2) + 4 * h + (st & 3);
+    const long long j0 = 32 * dw + 8 * (ks >> 1) + 4 * (ks & 1);   // elements j0..j0+3 and j0+16..j0+19
+    float lo[4], hi[4];
+    if (col < batch && j0 + 20 <= n && (n & 3) == 0 && ((reinterpret_cast<uintptr_t>(X) & 15) == 0)) {
+        const float* src = X + (size_t)col * n + j0;
+        const float4 a = *reinterpret_cast<const float4*>(src);
+        const float4 b = *reinterpret_cast<const float4*>(src + 16);
+        lo[0] = a.x; lo[1] = a.y; lo[2] = a.z; lo[3] = a.w;
+        hi[0] = b.x; hi[1] = b.y; hi[2] = b.z; hi[3] = b.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            lo[i] = (col < batch && j0 + i < n) ? X[(size_t)col * n + j0 + i] : 0.0f;
+            hi[i] = (col < batch && j0 + 16 + i < n) ? X[(size_t)col * n + j0 + 16 + i] : 0.0f;
+        }
+    }
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { x[2 * i] = lo[i]; x[2 * i + 1] = hi[i]; }
+    uint32_t t[3][8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) split3(x[e], t[0][e], t[1][e], t[2][e]);
+    mfma_u32x4* dst = Xf + (idx >> 6) * (3 * 64) + lane;
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        mfma_u32x4 v;
+        v.x = t[s][0] | (t[s][1] << 16);
+        v.y = t[s][2] | (t[s][3] << 16);
+        v.z = t[s][4] | (t[s][5] << 16);
+        v.w = t[s][6] | (t[s][7] << 16);
+        dst[s * 64] = v;
+    }
+}
+
+// MFMA step S (0..3) of the complemented key dword w -> the lane's 8 bf16 A elements.  Element
+// e = 2*i + hh is bit 8*(S/2) + 4*(S%2) + i + 16*hh of the dword: bits p and p + 16 land in the
+// sign positions 15 and 31 of one dword with a single shift.  +1.0 where the original bit was
+// set, -1.0 otherwise.
+template <int S>
+__device__ __forceinline__ bf16x8 unpack_step(uint32_t w) {
+    mfma_u32x4 d;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int p = 8 * (S >> 1) + 4 * (S & 1) + i;
+        const uint32_t a = p <= 15 ? (w << (15 - p)) : (w >> (p - 15));
+        d[i] = (a & 0x80008000u) | 0x3f803f80u;
+    }
+    return __builtin_bit_cast(bf16x8, d);
+}
+
+template <int Q, int RPW, int CT>
+__global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const UnpackParams p) {
+    constexpr int RT = Q * RPW;                       // row tiles (32 key rows each) per wave
+    constexpr int PIECES = 4 * CT * 3 * 64;           // 16-byte pieces per stage
+    constexpr int PER_THREAD = PIECES / kUnpackThreads;
+    extern __shared__ __align__(16) mfma_u32x4 stage_buf[];  // [2][PIECES]
+
+    const int wg = blockIdx.x;
+    const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
+    if (task >= p.ntasks) return;
+    const int cg = task % p.col_groups;
+    const int rest = task / p.col_groups;
+    const int sp = rest % p.splits;
+    const int rb = rest / p.splits;
+    const int g0 = sp * p.gps;
+    const int g1 = min(p.groups, g0 + p.gps);
+    const int stages_total = p.groups * kUnpackStagesPerGroup;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int h = lane >> 5;
+    const int lr = lane & 31;
+
+    const int rbase = rb * (128 * RPW) + wave * (32 * RPW);
+    const uint8_t* kptr[RT];
+#pragma unroll
+    for (int i = 0; i < Q; ++i)
+#pragma unroll
+        for (int rp = 0; rp < RPW; ++rp) {
+            const int row = min(rbase + rp * 32 + lr, p.m - 1);  // clamped: masked at the store
+            kptr[i * RPW + rp] = p.K + ((size_t)i * p.m + row) * p.stride_bytes + 16 * h;
+        }
+
+    auto load_keys = [&](int g, mfma_u32x4 (&k)[RT]) {
+        const bool ok = g < g1 && (uint32_t)(32 * g + 16 * h) < p.stride_bytes;
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            k[t] = (mfma_u32x4){0u, 0u, 0u, 0u};
+            if (ok) k[t] = ~*reinterpret_cast<const mfma_u32x4*>(kptr[t] + 32 * g);
+        }
+    };
+
+    const mfma_u32x4* xsrc = p.Xf + ((size_t)cg * stages_total + (size_t)g0 * 4) * PIECES + tid;
+    auto load_stage = [&](int st_rel, mfma_u32x4 (&r)[PER_THREAD]) {
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) r[i] = xsrc[(size_t)st_rel * PIECES + i * kUnpackThreads];
+    };
+    auto store_stage = [&](int buf, const mfma_u32x4 (&r)[PER_THREAD]) {
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) stage_buf[buf * PIECES + i * kUnpackThreads + tid] = r[i];
+    };
+
+    f32x16 acc[RT][CT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][c][v] = 0.0f;
+
+    mfma_u32x4 key[RT], keyn[RT];
+    mfma_u32x4 xr[PER_THREAD];
+    load_keys(g0, key);
+    load_stage(0, xr);
+    store_stage(0, xr);
+    __syncthreads();
+
+    const int nst = (g1 - g0) * kUnpackStagesPerGroup;
+    for (int g = g0; g < g1; ++g) {
+        load_keys(g + 1, keyn);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int st_rel = (g - g0) * 4 + d;
+            const bool more = st_rel + 1 < nst;
+            if (more) load_stage(st_rel + 1, xr);
+            const mfma_u32x4* buf = stage_buf + (d & 1) * PIECES + lane;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                bf16x8 bf[CT][3];
+#pragma unroll
+                for (int c = 0; c < CT; ++c)
+#pragma unroll
+                    for (int s = 0; s < 3; ++s)
+                        bf[c][s] = __builtin_bit_cast(bf16x8, buf[((ks * CT + c) * 3 + s) * 64]);
+                bf16x8 af[RT];
+#pragma unroll
+                for (int t = 0; t < RT; ++t) {
+                    const uint32_t w = key[t][d];
+                    af[t] = ks == 0 ? unpack_step<0>(w) : ks == 1 ? unpack_step<1>(w)
+                          : ks == 2 ? unpack_step<2>(w) : unpack_step<3>(w);
+                }
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+#pragma unroll
+                    for (int t = 0; t < RT; ++t)
+#pragma unroll
+                        for (int c = 0; c < CT; ++c)
+                            acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t], bf[c][s], acc[t][c], 0, 0, 0);
+            }
+            if (more) store_stage((d + 1) & 1, xr);
+            __syncthreads();
+        }
+#pragma unroll
+        for (int t = 0; t < RT; ++t) key[t] = keyn[t];
+    }
+
+    // ---- epilogue: scale by alpha, add the planes (Eq. 2), store ---------------------------------
+    const bool vec_ok = ((p.m & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.out) & 15) == 0) &&
+                        ((reinterpret_cast<uintptr_t>(p.alpha) & 15) == 0);
+#pragma unroll
+    for (int rp = 0; rp < RPW; ++rp) {
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            const int row = rbase + rp * 32 + 8 * vq + 4 * h;   // first of 4 consecutive rows
+            if (row >= p.m) continue;
+            float al[Q][4];
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                if (vec_ok) {
+                    const float4 a = *reinterpret_cast<const float4*>(p.alpha + (size_t)i * p.m + row);
+                    al[i][0] = a.x; al[i][1] = a.y; al[i][2] = a.z; al[i][3] = a.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        al[i][e] = row + e < p.m ? p.alpha[(size_t)i * p.m + row + e] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                const int col = (cg * CT + c) * 32 + lr;
+                if (col >= p.batch) continue;
+                float y[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float v = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < Q; ++i) v = fmaf(al[i][e], acc[i * RPW + rp][c][4 * vq + e], v);
+                    y[e] = v;
+                }
+                float* dst = p.out + ((size_t)sp * p.batch + col) * p.m + row;
+                if (vec_ok) {
+                    *reinterpret_cast<float4*>(dst) = make_float4(y[0], y[1], y[2], y[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (row + e < p.m) dst[e] = y[e];
+                }
+            }
+        }
+    }
+}
+
+}  // namespace biq

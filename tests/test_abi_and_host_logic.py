@@ -78,18 +78,31 @@ def test_default_plans_are_consistent(biq, mu):
                          (4096, 4096, 3, 32), (16384, 4096, 2, 128), (4096, 16384, 2, 128),
                          (1 << 20, 2048, 2, 1), (77, 100000, 1, 3)]:
         p = biq.biq_plan_get(m, n, q, b, mu)
-        C = biq.biq_num_chunks(n, mu)
-        tiles = -(-C // p.chunks_per_tile)
-        assert p.threads % 64 == 0 and 64 <= p.threads <= 1024
-        assert p.batch_tile in (1, 2, 4, 8)
+        name = biq.biq_kernel_name(p.kernel)
+        assert name != "unknown"
+        partial = p.chunk_splits * b * m * 4 if p.chunk_splits > 1 else 0
+        if name == "unpack_mfma":
+            # large batch: key groups of 32 bytes per row instead of LUT tiles, prepared input
+            # (three bf16 terms per element, padded to whole tiles) at the start of the workspace
+            assert b >= 64 and p.threads == 256 and p.batch_tile in (32, 64)
+            tiles = -(-biq.biq_key_row_stride(n) // p.chunks_per_tile)
+            pieces = 4 * (p.batch_tile // 32) * 3 * 64
+            xf = p.batch_tiles * p.chunk_splits * p.tiles_per_split * 4 * pieces * 16
+            xf = (xf + 255) // 256 * 256
+            assert xf >= 6 * b * n
+            assert biq.biq_plan_workspace_bytes(p, m, b) == xf + partial
+            assert biq.biq_workspace_bytes(m, n, q, b, mu) >= xf + partial
+        else:
+            tiles = -(-biq.biq_num_chunks(n, mu) // p.chunks_per_tile)
+            assert p.threads % 64 == 0 and 64 <= p.threads <= 1024
+            assert p.batch_tile in (1, 2, 4, 8)
+            ws = biq.biq_workspace_bytes(m, n, q, b, mu)
+            assert ws == biq.biq_plan_workspace_bytes(p, m, b) == partial
         assert p.chunk_splits * p.tiles_per_split >= tiles
         assert (p.chunk_splits - 1) * p.tiles_per_split < tiles
         assert p.row_blocks * p.rows_per_wg >= m > (p.row_blocks - 1) * p.rows_per_wg
         assert p.batch_tiles * p.batch_tile >= b
         assert 0 < p.lds_bytes <= 160 * 1024
-        ws = biq.biq_workspace_bytes(m, n, q, b, mu)
-        assert ws == biq.biq_plan_workspace_bytes(p, m, b)
-        assert ws == (p.chunk_splits * b * m * 4 if p.chunk_splits > 1 else 0)
         assert biq.biq_kernel_name(p.kernel) != "unknown"
 
 

@@ -330,3 +330,72 @@ def test_error_paths_on_device_buffers(biq):
     assert lib.biq_gemm(K.data_ptr() + 4, alpha.data_ptr(), X.data_ptr(), Y.data_ptr(), m, n, q, b, mu,
                         None, 0, None) == biq.BIQ_EINVAL
     assert need >= 0
+
+
+def _unpack_plan(biq, q, batch_tile, groups_per_split):
+    """Plan for the unpack-into-MFMA kernel (kernel 3): 256 threads, 32-byte key groups."""
+    rpw = {1: 4, 2: 2}.get(q, 1)
+    return _plan(biq, kernel=3, threads=256, ct=32, bt=batch_tile, tps=groups_per_split, rows=128 * rpw)
+
+
+UNPACK_SHAPES = [
+    # m, n, q, batch, batch_tile, key groups per split
+    (256, 256, 2, 64, 64, 1),      # one key group, full tiles
+    (300, 1000, 1, 70, 64, 2),     # ragged rows / columns / vectors, several splits
+    (129, 257, 3, 33, 64, 1),      # n not a multiple of 4 (scalar X reads), odd m (scalar stores)
+    (1024, 2048, 2, 128, 64, 8),   # one split walking 8 key groups
+    (512, 1536, 4, 32, 32, 3),     # four planes, one column tile per workgroup, two splits
+    (64, 128, 1, 1, 32, 1),        # a single input vector, half a key group (n = 128)
+    (2048, 512, 2, 100, 32, 2),    # 32-wide column tiles, ragged batch
+]
+
+
+@pytest.mark.parametrize("m,n,q,b,bt,gps", UNPACK_SHAPES)
+def test_unpack_mfma_parity(biq, oracle, m, n, q, b, bt, gps):
+    _say("unpack_mfma m=%d n=%d q=%d b=%d bt=%d gps=%d" % (m, n, q, b, bt, gps))
+    B, alpha, X = _rand_inputs(m, n, q, b, seed=4200 + m + n + q + b)
+    B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, B_dev)
+    Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps))
+    assert_within_tolerance(Y.cpu().numpy(), oracle.gemm_dense(B, alpha, X), alpha, X,
+                            what="unpack_mfma %s" % ((m, n, q, b, bt, gps),))
+
+
+def test_unpack_mfma_bit_exact_on_exact_inputs(biq, oracle):
+    """Integer inputs: every partial sum is exactly representable, so any summation order, the
+    bf16 three-way split and the fp32 matrix-core accumulation must reproduce Eq. 2 bit for bit."""
+    from paper_2005_09904_amd.workloads import Workload, make_exact_inputs
+
+    m, n, q, b = 384, 1280, 3, 96
+    _say("unpack_mfma exact inputs")
+    B, alpha, X = make_exact_inputs(Workload("exact", m, n, q, b, 8, "uniform", seed=77))
+    B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, B_dev)
+    ref = oracle.gemm_dense(B, alpha, X)
+    for bt, gps in ((64, 2), (32, 5)):
+        Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps))
+        assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref), (bt, gps)
+
+
+def test_unpack_mfma_does_not_depend_on_mu_and_default_plan_picks_it(biq, oracle):
+    """The kernel reads the packed bitmap, which is the same for every mu; from 64 input vectors
+    on it is what biq_gemm runs."""
+    m, n, q, b = 640, 768, 2, 64
+    _say("unpack_mfma default plan")
+    B, alpha, X = _rand_inputs(m, n, q, b, seed=99)
+    B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, B_dev)
+    assert biq.biq_kernel_name(biq.biq_plan_get(m, n, q, b, 8).kernel) == "unpack_mfma"
+    ref = oracle.gemm_dense(B, alpha, X)
+    first = None
+    for mu in (8, 6, 4, 1):
+        Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, mu)
+        assert_within_tolerance(Y.cpu().numpy(), ref, alpha, X, what="unpack_mfma mu=%d" % mu)
+        first = Y if first is None else first
+        assert torch_equal(first, Y)
+
+
+def torch_equal(a, b):
+    import torch
+
+    return torch.equal(a, b)
