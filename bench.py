@@ -33,7 +33,7 @@ def log(msg: str) -> None:
 class Problem:
     """Device buffers of one workload; `copies` packed weight matrices used in rotation."""
 
-    def __init__(self, biq, torch, w, copies: int, real_first: bool = True):
+    def __init__(self, biq, torch, w, copies: int, real_first: bool = True, plan=None):
         self.w = w
         dev = torch.device("cuda:0")
         self.key_bytes_padded = biq.biq_packed_bytes(w.m, w.n, w.q)
@@ -58,13 +58,16 @@ class Problem:
             self.X = torch.randn((w.batch, w.n), device=dev, generator=gen)
         self.Y = torch.zeros((w.batch, w.m), dtype=torch.float32, device=dev)
         ws_bytes = biq.biq_workspace_bytes(w.m, w.n, w.q, w.batch, w.mu)
+        if plan is not None:
+            ws_bytes = max(ws_bytes, biq.biq_plan_workspace_bytes(
+                biq.biq_plan_check(w.m, w.n, w.q, w.batch, w.mu, plan), w.m, w.batch))
         self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
         self.copies = copies
         self.biq = biq
         self.calls = 0
         # one marshalled call per key matrix in the rotation: a step is then one C-ABI call
         self.prepared = [biq.PreparedGemm(self.K[i], self.alpha, self.X, self.Y, w.m, w.n, w.q, w.batch,
-                                          w.mu, workspace=self.ws) for i in range(copies)]
+                                          w.mu, workspace=self.ws, plan=plan) for i in range(copies)]
 
     def step(self):
         self.prepared[self.calls % self.copies]()
@@ -255,24 +258,37 @@ def main() -> int:
         rows = [CONFIGS[k] for k in ["cfg1_fc512_b1", "cfg3_lstm4096x1024_q3_b8", "cfg4_sq4096_q3_b32",
                                      "cfg5_ffn_up_q2_b128", "cfg5_ffn_down_q2_b128"]]
         rows += [CONFIGS["cfg5_ffn_up_q2_b128"].with_mu(6), CONFIGS["cfg5_ffn_up_q2_b128"].with_mu(4)]
+        MFMA_BF16_PEAK_TFLOPS = 2500.0
         for w in rows:
-            name = w.name
-            copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
-            p = Problem(biq, torch, w, copies, real_first=False)
-            steps = 200 if w.lookups < 1e9 else 20
-            wall, _ = time_steps(torch, p, steps, 5)
-            s = summarize(w, wall / steps)
-            s["key_copies_in_rotation"] = copies
-            s["kernel"] = biq.biq_kernel_name(biq.biq_plan_get(w.m, w.n, w.q, w.batch, w.mu).kernel)
-            if w.batch > 1:
-                # batched calls are bounded by table gathers from LDS (4 bytes per lookup), not by HBM
-                s["lds_gather_GBps"] = 4.0 * w.lookups / (wall / steps) / 1e9
-                s["lds_frac"] = s["lds_gather_GBps"] / LDS_PEAK_GBPS
-            extra.append(s)
-            log("%s: %.2f us/call, %.1f GB/s, %.0f GOPS" % (name, s["us_per_call"], s["achieved_GBps"],
-                                                          s["effective_GOPS"]))
-            del p
-            torch.cuda.empty_cache()
+            default = biq.biq_plan_get(w.m, w.n, w.q, w.batch, w.mu)
+            lut = biq.biq_plan_get_lut(w.m, w.n, w.q, w.batch, w.mu)
+            # the library's choice first; where that is the unpack + MFMA kernel, the lookup-table
+            # kernel on the same inputs as a second row
+            for plan in ([None, lut] if default.kernel != lut.kernel else [None]):
+                kname = biq.biq_kernel_name((plan or default).kernel)
+                copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
+                p = Problem(biq, torch, w, copies, real_first=False, plan=plan)
+                steps = 200 if w.lookups < 1e9 else 20
+                wall, _ = time_steps(torch, p, steps, 5)
+                s = summarize(w, wall / steps)
+                s["key_copies_in_rotation"] = copies
+                s["kernel"] = kname
+                s["default_plan"] = plan is None
+                if kname == "unpack_mfma":
+                    # dense contraction: 2 flop per weight and input vector, times the three bf16
+                    # terms of x, on columns padded to the 32-wide MFMA tile
+                    padded = -(-w.batch // 32) * 32
+                    s["mfma_TFLOPs"] = 6.0 * w.q * w.m * w.n * padded / (wall / steps) / 1e12
+                    s["mfma_frac"] = s["mfma_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+                elif w.batch > 1:
+                    # batched table lookups are bounded by gathers from LDS (4 bytes per lookup)
+                    s["lds_gather_GBps"] = 4.0 * w.lookups / (wall / steps) / 1e9
+                    s["lds_frac"] = s["lds_gather_GBps"] / LDS_PEAK_GBPS
+                extra.append(s)
+                log("%s [%s]: %.2f us/call, %.1f GB/s, %.0f GOPS" % (w.name, kname, s["us_per_call"],
+                                                                   s["achieved_GBps"], s["effective_GOPS"]))
+                del p
+                torch.cuda.empty_cache()
         # the batch-1 family: m scaled by powers of two, to show the launch-latency knee
         fam = []
         for k in range(0, 10):

@@ -95,7 +95,9 @@ size_t biq_workspace_bytes(int m, int n, int q, int batch, int mu);
 typedef struct {
     int kernel;          /* kernel family id (see biq_kernel_name)                        */
     int threads;         /* threads per workgroup                                         */
-    int chunks_per_tile; /* chunks whose tables one workgroup holds in LDS at a time      */
+    int chunks_per_tile; /* chunks whose tables one workgroup holds in LDS at a time
+                            (unpack_mfma kernel: 32, the key bytes of a row per key group;
+                            "tile" below then means key group)                            */
     int batch_tile;      /* input vectors served by one workgroup                         */
     int chunk_splits;    /* workgroups sharing one row block along n (partials if > 1)    */
     int tiles_per_split; /* LUT tiles each of those workgroups walks through              */
@@ -114,6 +116,11 @@ typedef struct {
 } biq_plan;
 
 biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan);
+/* The library's choice among the lookup-table kernels only (Algorithm 2 proper): what biq_query
+ * runs, and what biq_gemm runs below the batch size from which it switches to unpacking the
+ * keys into the matrix cores (the large-batch regime of Sec. IV-B where a plain GEMM on
+ * unpacked weights wins). */
+biq_status biq_plan_get_lut(int m, int n, int q, int batch, int mu, biq_plan* plan);
 /* Validates a caller-filled plan (kernel, threads, chunks_per_tile, batch_tile,
  * tiles_per_split, rows_per_wg) against the shape and the device limits and fills in the
  * derived fields (chunk_splits, row_blocks, batch_tiles, lds_bytes). */
@@ -162,6 +169,12 @@ biq_status biq_query(const uint8_t* K, const float* alpha, const float* LUT, flo
  * fly in LDS from X and never written to device memory (Sec. III-B: "not taken
  * from DRAM"), keys are streamed once, partial sums are combined in a fixed
  * order (deterministic: same inputs, same bits).
+ *
+ * For many input vectors (see biq_plan_get / biq_plan_get_lut) the default plan is the
+ * unpack_mfma kernel instead: the "GEMM with unpacking" alternative of Sec. IV-B
+ * (Algorithm 3), with the sign bits expanded to +-1 in registers and contracted on the
+ * matrix cores against X split exactly into three bf16 terms; fp32 accumulation, same
+ * tolerance, same determinism.  It uses the first part of the workspace for the split X.
  */
 biq_status biq_gemm(const uint8_t* K, const float* alpha, const float* X, float* Y,
                     int m, int n, int q, int batch, int mu,

@@ -15,7 +15,7 @@ BIQ_OK, BIQ_EINVAL, BIQ_EUNSUPPORTED, BIQ_EWORKSPACE, BIQ_EHIP = 0, -1, -2, -3, 
 
 EXPORTS = [
     "biq_status_str", "biq_version", "biq_key_row_stride", "biq_packed_bytes", "biq_num_chunks",
-    "biq_lut_bytes", "biq_workspace_bytes", "biq_plan_get", "biq_plan_check", "biq_plan_workspace_bytes",
+    "biq_lut_bytes", "biq_workspace_bytes", "biq_plan_get", "biq_plan_get_lut", "biq_plan_check", "biq_plan_workspace_bytes",
     "biq_kernel_name", "biq_pack", "biq_unpack_keys", "biq_build_lut", "biq_query", "biq_gemm",
     "biq_gemm_ex",
 ]
@@ -66,6 +66,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "biq_lut_bytes": (Z, [I, I, I]),
         "biq_workspace_bytes": (Z, [I, I, I, I, I]),
         "biq_plan_get": (I, [I, I, I, I, I, PL]),
+        "biq_plan_get_lut": (I, [I, I, I, I, I, PL]),
         "biq_plan_check": (I, [I, I, I, I, I, PL]),
         "biq_plan_workspace_bytes": (Z, [PL, I, I]),
         "biq_kernel_name": (ctypes.c_char_p, [I]),
@@ -134,6 +135,12 @@ def biq_workspace_bytes(m: int, n: int, q: int, batch: int, mu: int) -> int:
 def biq_plan_get(m: int, n: int, q: int, batch: int, mu: int) -> BiqPlan:
     plan = BiqPlan()
     _check(load_library().biq_plan_get(m, n, q, batch, mu, ctypes.byref(plan)), "biq_plan_get")
+    return plan
+
+
+def biq_plan_get_lut(m: int, n: int, q: int, batch: int, mu: int) -> BiqPlan:
+    plan = BiqPlan()
+    _check(load_library().biq_plan_get_lut(m, n, q, batch, mu, ctypes.byref(plan)), "biq_plan_get_lut")
     return plan
 
 

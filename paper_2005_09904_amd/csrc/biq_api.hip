@@ -17,7 +17,6 @@ constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kLdsTableBudget = 128 * 1024;  // tables of one tile (leaves room for 1 WG/CU extras)
 constexpr int kNumCu = 256;
 constexpr int kNumXcd = 8;
-constexpr int kUnpackMinBatch = 64;  // from this many input vectors on, biq_gemm unpacks into the matrix cores
 
 enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL_UNPACK_MFMA = 3, KERNEL_COUNT };
 
@@ -39,18 +38,20 @@ inline int unit_keys(int mu) {
 inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
 
-// Unpack-MFMA kernel: row tiles per wave and plane, by number of planes (a wave holds all planes
-// of its rows so that Eq. 2's sum over planes stays in registers).
-inline int unpack_rpw(int q) { return q == 1 ? 4 : (q == 2 ? 2 : 1); }
-// 16-byte pieces of prepared input per pipeline stage: 4 MFMA steps x column tiles x 3 bf16 terms x 64 lanes
-inline long long unpack_stage_pieces(int batch_tile) { return 4ll * (batch_tile / 32) * 3 * 64; }
+// 16-byte pieces of prepared input per pipeline stage: MFMA steps x column tiles (their product is
+// fixed) x 3 bf16 terms x 64 lanes
+inline long long unpack_stage_pieces(int) { return (long long)kUnpackStageSteps * 3 * 64; }
+// ... and per key group (16 MFMA steps)
+inline long long unpack_group_pieces(int batch_tile) { return 16ll * (batch_tile / 32) * 3 * 64; }
 
 // Unpack-MFMA plans: fixed workgroup shape, key groups (32 key bytes of a row) instead of LUT tiles.
 bool plan_finish_unpack(biq_plan& pl, int m, int n, int q, int batch) {
     if (q > 4 || pl.threads != kUnpackThreads) return false;
     if (pl.batch_tile != 32 && pl.batch_tile != 64) return false;
     if (pl.chunks_per_tile != kUnpackGroupBytes) return false;
-    if (pl.rows_per_wg != 128 * unpack_rpw(q)) return false;
+    // 4 waves x RPW row tiles of 32 rows per plane, at most 4 row tiles (all planes) per wave
+    if (pl.rows_per_wg != 128 && pl.rows_per_wg != 256 && pl.rows_per_wg != 512) return false;
+    if (q * (pl.rows_per_wg / 128) > 4) return false;
     if (pl.row_mode != 0 || pl.xcd_skew != 0 || pl.tiles_per_split < 1) return false;
     const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
     if (pl.tiles_per_split > groups) pl.tiles_per_split = groups;
@@ -61,8 +62,8 @@ bool plan_finish_unpack(biq_plan& pl, int m, int n, int q, int batch) {
     const long long tasks = (long long)pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
     if (tasks > (1ll << 30)) return false;
     // prepared input: 6 bytes per (padded column, padded element)
-    const long long xf = (long long)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split * 4 *
-                         unpack_stage_pieces(pl.batch_tile) * 16;
+    const long long xf = (long long)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split *
+                         unpack_group_pieces(pl.batch_tile) * 16;
     if (xf > (1ll << 40)) return false;
     return true;
 }
@@ -124,6 +125,23 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     return true;
 }
 
+// Where the lookup tables stop paying off (the crossover of Sec. IV-B / Fig. 10): estimated
+// run times of both paths from rates measured on MI355X.  Table lookups: about 13e12 lookups/s
+// for the mu = 8 kernels; 6.5e12 for the generic one, which also streams keys at no more than
+// about 0.25 TB/s; plus 6 us of launch and table build.
+// Unpack + MFMA: 2 * 3 flop per weight and padded input vector (three bf16 terms) at 1.3e15
+// flop/s, plus 12 us (input split, launch, combining partial sums).
+bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
+    const double weights = (double)q * m * n;
+    const double lookups = weights / mu * batch;
+    double t_lut = lookups / (mu == 8 ? 13e12 : 6.5e12);
+    if (mu != 8 && t_lut < weights / 8 / 0.25e12) t_lut = weights / 8 / 0.25e12;
+    t_lut += 6e-6;
+    const double padded = (double)((batch + 31) / 32) * 32;
+    const double t_mfma = 12e-6 + 6.0 * weights * padded / 1.3e15;
+    return t_mfma < t_lut;
+}
+
 // Default mapping.  Algorithm 2 leaves the tile sizes open; the choices here are:
 //  - batch tile: as many input vectors as one lookup can serve with a single wide LDS read
 //  - tile width: the largest power-of-two number of key units whose tables fit the LDS budget
@@ -135,22 +153,24 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
     const int C = ceil_div(n, mu);
     const int E = 1 << mu;
     pl = biq_plan{};
-    if (!tables_given && q <= 4 && batch >= kUnpackMinBatch) {
+    if (!tables_given && q <= 4 && unpack_mfma_is_faster(m, n, q, batch, mu)) {
         // Many input vectors: the contraction is compute bound and the matrix cores beat the
-        // table lookups (the crossover of Sec. IV-B / Fig. 10).  Key groups are split over
-        // workgroups only as far as needed to give every CU a workgroup.
+        // table lookups (the crossover of Sec. IV-B / Fig. 10).  Column tile 64 only when that
+        // still leaves two tiles of columns; the most rows per workgroup that still give 128
+        // workgroups before splitting; key groups split (powers of two) until every CU has a
+        // workgroup.
         pl.kernel = KERNEL_UNPACK_MFMA;
         pl.threads = kUnpackThreads;
         pl.chunks_per_tile = kUnpackGroupBytes;
-        pl.batch_tile = batch > 32 ? 64 : 32;
-        pl.rows_per_wg = 128 * unpack_rpw(q);
+        pl.batch_tile = batch >= 128 ? 64 : 32;
+        const int col_groups = ceil_div(batch, pl.batch_tile);
+        int rpw = q == 1 ? 4 : (q == 2 ? 2 : 1);
+        while (rpw > 1 && (long long)ceil_div(m, 128 * rpw) * col_groups < 128) rpw >>= 1;
+        pl.rows_per_wg = 128 * rpw;
         const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
-        const long long wgs = (long long)ceil_div(m, pl.rows_per_wg) * ceil_div(batch, pl.batch_tile);
+        const long long wgs = (long long)ceil_div(m, pl.rows_per_wg) * col_groups;
         int S = 1;
-        if (wgs < kNumCu) {
-            S = ceil_div(kNumCu, wgs);
-            if (S > groups) S = groups;
-        }
+        while (wgs * S < kNumCu && 2 * S <= groups) S *= 2;
         pl.tiles_per_split = ceil_div(groups, S);
         plan_finish(pl, m, n, q, batch, mu);
         return;
@@ -256,8 +276,8 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
 // Bytes of the prepared-input area at the start of the workspace (unpack-MFMA plans only).
 size_t plan_xf_bytes(const biq_plan& pl) {
     if (pl.kernel != KERNEL_UNPACK_MFMA) return 0;
-    const size_t b = (size_t)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split * 4 *
-                     (size_t)unpack_stage_pieces(pl.batch_tile) * 16;
+    const size_t b = (size_t)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split *
+                     (size_t)unpack_group_pieces(pl.batch_tile) * 16;
     return (b + 255) & ~(size_t)255;
 }
 
@@ -373,13 +393,17 @@ hipError_t launch_unpack_inst(const UnpackParams& up, int grid, int lds, hipStre
 }
 
 template <int CT>
-hipError_t launch_unpack(int q, const UnpackParams& up, int grid, int lds, hipStream_t s) {
-    switch (q) {
-        case 1: return launch_unpack_inst<1, 4, CT>(up, grid, lds, s);
-        case 2: return launch_unpack_inst<2, 2, CT>(up, grid, lds, s);
-        case 3: return launch_unpack_inst<3, 1, CT>(up, grid, lds, s);
-        default: return launch_unpack_inst<4, 1, CT>(up, grid, lds, s);
+hipError_t launch_unpack(int q, int rpw, const UnpackParams& up, int grid, int lds, hipStream_t s) {
+    switch (q * 8 + rpw) {
+        case 1 * 8 + 1: return launch_unpack_inst<1, 1, CT>(up, grid, lds, s);
+        case 1 * 8 + 2: return launch_unpack_inst<1, 2, CT>(up, grid, lds, s);
+        case 1 * 8 + 4: return launch_unpack_inst<1, 4, CT>(up, grid, lds, s);
+        case 2 * 8 + 1: return launch_unpack_inst<2, 1, CT>(up, grid, lds, s);
+        case 2 * 8 + 2: return launch_unpack_inst<2, 2, CT>(up, grid, lds, s);
+        case 3 * 8 + 1: return launch_unpack_inst<3, 1, CT>(up, grid, lds, s);
+        case 4 * 8 + 1: return launch_unpack_inst<4, 1, CT>(up, grid, lds, s);
     }
+    return hipErrorInvalidValue;  // plan_finish_unpack admits no other combination
 }
 
 // Large-batch path: split X into bf16 terms in MFMA operand order (workspace), contract, and
@@ -388,16 +412,16 @@ biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* al
                            float* Y, int m, int n, int q, int batch, void* workspace, hipStream_t s) {
     const int CT = pl.batch_tile / 32;
     const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
-    const int stages = groups * kUnpackStagesPerGroup;
+    const int steps = groups * 16;  // MFMA steps along a row
     mfma_u32x4* Xf = reinterpret_cast<mfma_u32x4*>(workspace);
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + plan_xf_bytes(pl));
 
-    const long long total = (long long)pl.batch_tiles * stages * 4 * CT * 64;
+    const long long total = (long long)pl.batch_tiles * steps * CT * 64;
     const unsigned sgrid = (unsigned)((total + 255) / 256);
     if (CT == 2)
-        hipLaunchKernelGGL(xsplit_kernel<2>, dim3(sgrid), dim3(256), 0, s, X, Xf, n, batch, stages, total);
+        hipLaunchKernelGGL(xsplit_kernel<2>, dim3(sgrid), dim3(256), 0, s, X, Xf, n, batch, steps, total);
     else
-        hipLaunchKernelGGL(xsplit_kernel<1>, dim3(sgrid), dim3(256), 0, s, X, Xf, n, batch, stages, total);
+        hipLaunchKernelGGL(xsplit_kernel<1>, dim3(sgrid), dim3(256), 0, s, X, Xf, n, batch, steps, total);
     if (hipGetLastError() != hipSuccess) return BIQ_EHIP;
 
     UnpackParams up{};
@@ -416,8 +440,9 @@ biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* al
     up.ntasks = pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
     up.tasks_per_xcd = ceil_div(up.ntasks, kNumXcd);
     const int grid = up.tasks_per_xcd * kNumXcd;
-    const hipError_t e = CT == 2 ? launch_unpack<2>(q, up, grid, pl.lds_bytes, s)
-                                 : launch_unpack<1>(q, up, grid, pl.lds_bytes, s);
+    const int rpw = pl.rows_per_wg / 128;
+    const hipError_t e = CT == 2 ? launch_unpack<2>(q, rpw, up, grid, pl.lds_bytes, s)
+                                 : launch_unpack<1>(q, rpw, up, grid, pl.lds_bytes, s);
     if (e != hipSuccess) return BIQ_EHIP;
     if (pl.chunk_splits > 1) {
         const long long count = (long long)batch * m;
@@ -534,6 +559,12 @@ size_t biq_lut_bytes(int n, int batch, int mu) {
 biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan) {
     if (!plan || !shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
     plan_default(*plan, m, n, q, batch, mu);
+    return BIQ_OK;
+}
+
+biq_status biq_plan_get_lut(int m, int n, int q, int batch, int mu, biq_plan* plan) {
+    if (!plan || !shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
+    plan_default(*plan, m, n, q, batch, mu, true);
     return BIQ_OK;
 }
 

@@ -4,7 +4,8 @@
 // (the crossover discussed with Fig. 10); the alternative the paper measures is to unpack the
 // sign bits and run an ordinary GEMM.  Here the unpacking happens in registers, straight into
 // the A operand of v_mfma_f32_32x32x16_bf16, and nothing unpacked ever reaches memory:
-//   - a weight bit becomes the bf16 value +1.0 / -1.0 (bit set <-> +1, as in Algorithm 3);
+//   - a weight bit becomes the bf16 value +1.0 / -1.0 (bit set <-> +1, as in Algorithm 3; the
+//     kernel forms the negated value, whose sign bit is the key bit, and negates alpha);
 //   - every fp32 input x is split once into three bf16 terms x = x0 + x1 + x2 (8 significand
 //     bits each, by truncation, so the sum is exact); +-1 * bf16 products are exact and the
 //     matrix cores accumulate in fp32, so the result differs from a plain fp32 evaluation of
@@ -22,10 +23,10 @@
 // is a permutation of the columns, which the B side follows.
 //
 // B operands are prepared by xsplit_kernel in exactly the order the main kernel consumes them:
-//   Xf[col_group][stage][step 0..3][col_tile][term 0..2][lane] : 16 bytes (8 bf16)
-// with stage = 4 consecutive MFMA steps (one dword of every lane's 16 key bytes), so a
-// workgroup stages one contiguous block per stage into LDS (double buffered) and its four
-// waves read their fragments from there with conflict-free 128-bit reads.
+//   Xf[col_group][step][col_tile][term 0..2][lane] : 16 bytes (8 bf16)
+// (step = MFMA step along the row, 16 per key group), so a workgroup stages one contiguous
+// block per pipeline stage into LDS (double buffered) and its four waves read their fragments
+// from there with conflict-free 128-bit reads.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -39,7 +40,7 @@ typedef uint32_t mfma_u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kUnpackThreads = 256;     // 4 waves
 constexpr int kUnpackGroupBytes = 32;   // key bytes of a row per key group (both halves)
-constexpr int kUnpackStagesPerGroup = 4;
+constexpr int kUnpackStageSteps = 8;     // MFMA steps x column tiles per pipeline stage (48 KiB of LDS for two stages)
 
 struct UnpackParams {
     const uint8_t* K;        // [q][m][stride]
@@ -66,24 +67,24 @@ __device__ __forceinline__ void split3(float x, uint32_t& t0, uint32_t& t1, uint
     t2 = __float_as_uint(r2) >> 16;                 // exact in bf16
 }
 
-// One thread per (col_group, stage, step, col_tile, lane): the three 16-byte B fragments of
-// that lane.  Columns past the batch and elements past n are zero.
+// One thread per (col_group, step, col_tile, lane): the three 16-byte B fragments of that lane.
+// Columns past the batch and elements past n are zero.
 template <int CT>
 __global__ __launch_bounds__(256) void xsplit_kernel(const float* __restrict__ X,
                                                      mfma_u32x4* __restrict__ Xf, int n, int batch,
-                                                     int stages, long long total) {
+                                                     int steps, long long total) {
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int lane = (int)(idx & 63);
     long long rest = idx >> 6;
     const int ct = (int)(rest % CT); rest /= CT;
-    const int ks = (int)(rest & 3); rest >>= 2;
-    const int st = (int)(rest % stages);
-    const int cg = (int)(rest / stages);
+    const int step = (int)(rest % steps);   // MFMA step along the row: 16 per key group
+    const int cg = (int)(rest / steps);
     const int col = (cg * CT + ct) * 32 + (lane & 31);
     const int h = lane >> 5;
-    // dword of the row this stage works on, and the 2 x 4 consecutive elements of this step
-    const long long dw = 8ll * (st >> 2) + 4 * h + (st & 3);
+    const int ks = step & 3;
+    // dword of the row this step works on, and its 2 x 4 consecutive elements (see unpack_step)
+    const long long dw = 8ll * (step >> 4) + 4 * h + ((step >> 2) & 3);
     const long long j0 = 32 * dw + 8 * (ks >> 1) + 4 * (ks & 1);   // elements j0..j0+3 and j0+16..j0+19
     float lo[4], hi[4];
     if (col < batch && j0 + 20 <= n && (n & 3) == 0 && ((reinterpret_cast<uintptr_t>(X) & 15) == 0)) {
@@ -117,27 +118,33 @@ __global__ __launch_bounds__(256) void xsplit_kernel(const float* __restrict__ X
     }
 }
 
-// MFMA step S (0..3) of the complemented key dword w -> the lane's 8 bf16 A elements.  Element
-// e = 2*i + hh is bit 8*(S/2) + 4*(S%2) + i + 16*hh of the dword: bits p and p + 16 land in the
-// sign positions 15 and 31 of one dword with a single shift.  +1.0 where the original bit was
-// set, -1.0 otherwise.
+// MFMA step S (0..3) of key dword w -> the lane's 8 bf16 A elements, with the OPPOSITE sign:
+// -1.0 where the bit is set, +1.0 otherwise (the sign bit is the key bit; the epilogue multiplies
+// by -alpha).  Element e = 2*i + hh is bit 8*(S/2) + 4*(S%2) + i + 16*hh of the dword: bits p
+// and p + 16 land in the sign positions 15 and 31 of one dword with a single shift.  `one2`
+// holds two bf16 1.0 (0x3f803f80) in a VGPR so that mask-and-merge is one v_and_or_b32.
 template <int S>
-__device__ __forceinline__ bf16x8 unpack_step(uint32_t w) {
+__device__ __forceinline__ bf16x8 unpack_step(uint32_t w, uint32_t one2) {
     mfma_u32x4 d;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int p = 8 * (S >> 1) + 4 * (S & 1) + i;
         const uint32_t a = p <= 15 ? (w << (15 - p)) : (w >> (p - 15));
-        d[i] = (a & 0x80008000u) | 0x3f803f80u;
+        uint32_t r;
+        asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(0x80008000u), "v"(one2));
+        d[i] = r;
     }
     return __builtin_bit_cast(bf16x8, d);
 }
 
 template <int Q, int RPW, int CT>
 __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const UnpackParams p) {
+    constexpr int KS = kUnpackStageSteps / CT;        // MFMA steps per pipeline stage
     constexpr int RT = Q * RPW;                       // row tiles (32 key rows each) per wave
-    constexpr int PIECES = 4 * CT * 3 * 64;           // 16-byte pieces per stage
+    constexpr int SPIECES = CT * 3 * 64;              // pieces per MFMA step
+    constexpr int PIECES = KS * SPIECES;              // pieces per stage
     constexpr int PER_THREAD = PIECES / kUnpackThreads;
+    static_assert(PIECES % kUnpackThreads == 0, "");
     extern __shared__ __align__(16) mfma_u32x4 stage_buf[];  // [2][PIECES]
 
     const int wg = blockIdx.x;
@@ -149,7 +156,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     const int rb = rest / p.splits;
     const int g0 = sp * p.gps;
     const int g1 = min(p.groups, g0 + p.gps);
-    const int stages_total = p.groups * kUnpackStagesPerGroup;
+    const int steps_total = p.groups * 16;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -163,20 +170,18 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     for (int i = 0; i < Q; ++i)
 #pragma unroll
         for (int rp = 0; rp < RPW; ++rp) {
-            const int row = min(rbase + rp * 32 + lr, p.m - 1);  // clamped: masked at the store
+            const int row = min(rbase + rp * 32 + lr, p.m - 1);
             kptr[i * RPW + rp] = p.K + ((size_t)i * p.m + row) * p.stride_bytes + 16 * h;
         }
-
     auto load_keys = [&](int g, mfma_u32x4 (&k)[RT]) {
         const bool ok = g < g1 && (uint32_t)(32 * g + 16 * h) < p.stride_bytes;
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
             k[t] = (mfma_u32x4){0u, 0u, 0u, 0u};
-            if (ok) k[t] = ~*reinterpret_cast<const mfma_u32x4*>(kptr[t] + 32 * g);
+            if (ok) k[t] = *reinterpret_cast<const mfma_u32x4*>(kptr[t] + 32 * g);
         }
     };
-
-    const mfma_u32x4* xsrc = p.Xf + ((size_t)cg * stages_total + (size_t)g0 * 4) * PIECES + tid;
+    const mfma_u32x4* xsrc = p.Xf + ((size_t)cg * steps_total + (size_t)g0 * 16) * SPIECES + tid;
     auto load_stage = [&](int st_rel, mfma_u32x4 (&r)[PER_THREAD]) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) r[i] = xsrc[(size_t)st_rel * PIECES + i * kUnpackThreads];
@@ -185,7 +190,6 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) stage_buf[buf * PIECES + i * kUnpackThreads + tid] = r[i];
     };
-
     f32x16 acc[RT][CT];
 #pragma unroll
     for (int t = 0; t < RT; ++t)
@@ -194,6 +198,8 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][c][v] = 0.0f;
 
+    uint32_t one2 = 0x3f803f80u;
+    asm volatile("" : "+v"(one2));
     mfma_u32x4 key[RT], keyn[RT];
     mfma_u32x4 xr[PER_THREAD];
     load_keys(g0, key);
@@ -201,64 +207,73 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     store_stage(0, xr);
     __syncthreads();
 
-    const int nst = (g1 - g0) * kUnpackStagesPerGroup;
+    constexpr int SPG = 16 / KS;   // stages per key group
+    const int nst = (g1 - g0) * SPG;
     for (int g = g0; g < g1; ++g) {
         load_keys(g + 1, keyn);
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const int st_rel = (g - g0) * 4 + d;
+        for (int sg = 0; sg < SPG; ++sg) {
+            const int st_rel = (g - g0) * SPG + sg;
             const bool more = st_rel + 1 < nst;
             if (more) load_stage(st_rel + 1, xr);
-            const mfma_u32x4* buf = stage_buf + (d & 1) * PIECES + lane;
+            const mfma_u32x4* buf = stage_buf + (sg & 1) * PIECES + lane;
+            bf16x8 bf[2][CT][3];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                bf16x8 bf[CT][3];
+            for (int c = 0; c < CT; ++c)
 #pragma unroll
-                for (int c = 0; c < CT; ++c)
+                for (int s = 0; s < 3; ++s) bf[0][c][s] = __builtin_bit_cast(bf16x8, buf[(c * 3 + s) * 64]);
 #pragma unroll
-                    for (int s = 0; s < 3; ++s)
-                        bf[c][s] = __builtin_bit_cast(bf16x8, buf[((ks * CT + c) * 3 + s) * 64]);
+            for (int kk = 0; kk < KS; ++kk) {
+                const int step = sg * KS + kk;     // 0..15 within the group
+                const int d = step >> 2, ks = step & 3;
+                if (kk + 1 < KS) {
+#pragma unroll
+                    for (int c = 0; c < CT; ++c)
+#pragma unroll
+                        for (int s = 0; s < 3; ++s)
+                            bf[(kk + 1) & 1][c][s] = __builtin_bit_cast(bf16x8, buf[(((kk + 1) * CT + c) * 3 + s) * 64]);
+                }
                 bf16x8 af[RT];
 #pragma unroll
                 for (int t = 0; t < RT; ++t) {
                     const uint32_t w = key[t][d];
-                    af[t] = ks == 0 ? unpack_step<0>(w) : ks == 1 ? unpack_step<1>(w)
-                          : ks == 2 ? unpack_step<2>(w) : unpack_step<3>(w);
+                    af[t] = ks == 0 ? unpack_step<0>(w, one2) : ks == 1 ? unpack_step<1>(w, one2)
+                          : ks == 2 ? unpack_step<2>(w, one2) : unpack_step<3>(w, one2);
                 }
+                const int cur = kk & 1;
 #pragma unroll
                 for (int s = 0; s < 3; ++s)
 #pragma unroll
                     for (int t = 0; t < RT; ++t)
 #pragma unroll
                         for (int c = 0; c < CT; ++c)
-                            acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t], bf[c][s], acc[t][c], 0, 0, 0);
+                            acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t], bf[cur][c][s], acc[t][c], 0, 0, 0);
             }
-            if (more) store_stage((d + 1) & 1, xr);
+            if (more) store_stage((sg + 1) & 1, xr);
             __syncthreads();
         }
 #pragma unroll
         for (int t = 0; t < RT; ++t) key[t] = keyn[t];
     }
-
-    // ---- epilogue: scale by alpha, add the planes (Eq. 2), store ---------------------------------
+    // epilogue (weights were unpacked with the opposite sign: bit set -> -1)
     const bool vec_ok = ((p.m & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.out) & 15) == 0) &&
                         ((reinterpret_cast<uintptr_t>(p.alpha) & 15) == 0);
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) {
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
-            const int row = rbase + rp * 32 + 8 * vq + 4 * h;   // first of 4 consecutive rows
+            const int row = rbase + rp * 32 + 8 * vq + 4 * h;
             if (row >= p.m) continue;
             float al[Q][4];
 #pragma unroll
             for (int i = 0; i < Q; ++i) {
                 if (vec_ok) {
                     const float4 a = *reinterpret_cast<const float4*>(p.alpha + (size_t)i * p.m + row);
-                    al[i][0] = a.x; al[i][1] = a.y; al[i][2] = a.z; al[i][3] = a.w;
+                    al[i][0] = -a.x; al[i][1] = -a.y; al[i][2] = -a.z; al[i][3] = -a.w;
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        al[i][e] = row + e < p.m ? p.alpha[(size_t)i * p.m + row + e] : 0.0f;
+                        al[i][e] = row + e < p.m ? -p.alpha[(size_t)i * p.m + row + e] : 0.0f;
                 }
             }
 #pragma unroll

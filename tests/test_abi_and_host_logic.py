@@ -84,10 +84,10 @@ def test_default_plans_are_consistent(biq, mu):
         if name == "unpack_mfma":
             # large batch: key groups of 32 bytes per row instead of LUT tiles, prepared input
             # (three bf16 terms per element, padded to whole tiles) at the start of the workspace
-            assert b >= 64 and p.threads == 256 and p.batch_tile in (32, 64)
+            assert p.threads == 256 and p.batch_tile in (32, 64)
             tiles = -(-biq.biq_key_row_stride(n) // p.chunks_per_tile)
-            pieces = 4 * (p.batch_tile // 32) * 3 * 64
-            xf = p.batch_tiles * p.chunk_splits * p.tiles_per_split * 4 * pieces * 16
+            pieces = 16 * (p.batch_tile // 32) * 3 * 64  # per key group: 16 MFMA steps
+            xf = p.batch_tiles * p.chunk_splits * p.tiles_per_split * pieces * 16
             xf = (xf + 255) // 256 * 256
             assert xf >= 6 * b * n
             assert biq.biq_plan_workspace_bytes(p, m, b) == xf + partial
@@ -98,6 +98,10 @@ def test_default_plans_are_consistent(biq, mu):
             assert p.batch_tile in (1, 2, 4, 8)
             ws = biq.biq_workspace_bytes(m, n, q, b, mu)
             assert ws == biq.biq_plan_workspace_bytes(p, m, b) == partial
+            lut = biq.biq_plan_get_lut(m, n, q, b, mu)
+            assert biq.biq_kernel_name(lut.kernel) == name
+        assert biq.biq_kernel_name(biq.biq_plan_get_lut(m, n, q, b, mu).kernel) in (
+            "query_generic", "gemv8", "gemm8x2")
         assert p.chunk_splits * p.tiles_per_split >= tiles
         assert (p.chunk_splits - 1) * p.tiles_per_split < tiles
         assert p.row_blocks * p.rows_per_wg >= m > (p.row_blocks - 1) * p.rows_per_wg

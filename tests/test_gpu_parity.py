@@ -144,10 +144,16 @@ def test_gemm_parity_large_configs_sampled_rows(biq, oracle, name, mus):
     Kh = K.cpu().numpy().reshape(w.q, w.m, -1)
     assert np.array_equal(Kh[:, rows, :], bitmap_rows)
     for mu in mus:
-        _say("gemm %s mu=%d (sampled rows)" % (name, mu))
-        Y = gpu_gemm(biq, K, ad, Xd, w.m, w.n, w.q, mu).cpu().numpy()
-        assert np.all(np.isfinite(Y))
-        assert_within_tolerance(Y[:, rows], ref, alpha[:, rows], X, "%s mu=%d" % (name, mu))
+        # the default plan (for these sizes: keys unpacked into the matrix cores) and the
+        # lookup-table kernels, both in the launch configuration bench.py times
+        default = biq.biq_plan_get(w.m, w.n, w.q, w.batch, mu)
+        lut = biq.biq_plan_get_lut(w.m, w.n, w.q, w.batch, mu)
+        for plan in ([None, lut] if default.kernel != lut.kernel else [None]):
+            kname = biq.biq_kernel_name((plan or default).kernel)
+            _say("gemm %s mu=%d %s (sampled rows)" % (name, mu, kname))
+            Y = gpu_gemm(biq, K, ad, Xd, w.m, w.n, w.q, mu, plan=plan).cpu().numpy()
+            assert np.all(np.isfinite(Y))
+            assert_within_tolerance(Y[:, rows], ref, alpha[:, rows], X, "%s mu=%d %s" % (name, mu, kname))
     torch.cuda.empty_cache()
 
 
@@ -378,21 +384,26 @@ def test_unpack_mfma_bit_exact_on_exact_inputs(biq, oracle):
 
 
 def test_unpack_mfma_does_not_depend_on_mu_and_default_plan_picks_it(biq, oracle):
-    """The kernel reads the packed bitmap, which is the same for every mu; from 64 input vectors
-    on it is what biq_gemm runs."""
-    m, n, q, b = 640, 768, 2, 64
+    """The kernel reads the packed bitmap, which is the same for every mu; for enough input
+    vectors and weights it is what biq_gemm runs, while biq_plan_get_lut keeps to the tables."""
+    m, n, q, b = 4096, 2048, 2, 96
     _say("unpack_mfma default plan")
     B, alpha, X = _rand_inputs(m, n, q, b, seed=99)
     B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
     K = gpu_pack(biq, B_dev)
-    assert biq.biq_kernel_name(biq.biq_plan_get(m, n, q, b, 8).kernel) == "unpack_mfma"
-    ref = oracle.gemm_dense(B, alpha, X)
+    rows = np.unique(np.random.default_rng(5).integers(0, m, size=200)).astype(np.int64)
+    ref = oracle.gemm_dense(B, alpha, X, rows=rows)
     first = None
     for mu in (8, 6, 4, 1):
+        assert biq.biq_kernel_name(biq.biq_plan_get(m, n, q, b, mu).kernel) == "unpack_mfma"
+        assert biq.biq_kernel_name(biq.biq_plan_get_lut(m, n, q, b, mu).kernel) != "unpack_mfma"
         Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, mu)
-        assert_within_tolerance(Y.cpu().numpy(), ref, alpha, X, what="unpack_mfma mu=%d" % mu)
+        assert_within_tolerance(Y.cpu().numpy()[:, rows], ref, alpha[:, rows], X, what="unpack_mfma mu=%d" % mu)
         first = Y if first is None else first
         assert torch_equal(first, Y)
+    # the table kernels on the same inputs, through an explicit plan
+    Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=biq.biq_plan_get_lut(m, n, q, b, 8))
+    assert_within_tolerance(Y.cpu().numpy()[:, rows], ref, alpha[:, rows], X, what="lut plan")
 
 
 def torch_equal(a, b):
