@@ -112,7 +112,12 @@ typedef struct {
     int xcd_skew;        /* GEMV kernel, row_mode 0, no chunk split, row_blocks a multiple of 8:
                             workgroups on even XCDs take rows_per_wg + xcd_skew rows, those on
                             odd XCDs rows_per_wg - xcd_skew (odd XCDs stream slower)        */
-    int reserved[4];
+    int wave_splits;     /* unpack_mfma kernel: 1, 2 or 4 groups of waves inside a workgroup, each
+                            contracting its own part of the workgroup's key groups; their partial
+                            sums are added in LDS (0 is read as 1).  rows_per_wg is then
+                            (4 / wave_splits) * 32 * r with r row tiles per wave and plane,
+                            r in {1, 2, 4}, q * r <= 4                                       */
+    int reserved[3];
 } biq_plan;
 
 biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan);

@@ -38,27 +38,30 @@ inline int unit_keys(int mu) {
 inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
 
-// 16-byte pieces of prepared input per pipeline stage: MFMA steps x column tiles (their product is
-// fixed) x 3 bf16 terms x 64 lanes
-inline long long unpack_stage_pieces(int) { return (long long)kUnpackStageSteps * 3 * 64; }
-// ... and per key group (16 MFMA steps)
+// 16-byte pieces of prepared input per key group (16 MFMA steps): column tiles x 3 bf16 terms x 64 lanes
 inline long long unpack_group_pieces(int batch_tile) { return 16ll * (batch_tile / 32) * 3 * 64; }
 
-// Unpack-MFMA plans: fixed workgroup shape, key groups (32 key bytes of a row) instead of LUT tiles.
+// Unpack-MFMA plans: workgroups of 4 waves, key groups (32 key bytes of a row) instead of LUT tiles.
 bool plan_finish_unpack(biq_plan& pl, int m, int n, int q, int batch) {
     if (q > 4 || pl.threads != kUnpackThreads) return false;
     if (pl.batch_tile != 32 && pl.batch_tile != 64) return false;
     if (pl.chunks_per_tile != kUnpackGroupBytes) return false;
-    // 4 waves x RPW row tiles of 32 rows per plane, at most 4 row tiles (all planes) per wave
-    if (pl.rows_per_wg != 128 && pl.rows_per_wg != 256 && pl.rows_per_wg != 512) return false;
-    if (q * (pl.rows_per_wg / 128) > 4) return false;
+    if (pl.wave_splits == 0) pl.wave_splits = 1;
+    const int ws = pl.wave_splits;
+    if (ws != 1 && ws != 2 && ws != 4) return false;
+    // (4 / ws) waves side by side x r row tiles of 32 rows per plane, at most 4 row tiles per wave
+    const int per_r = (4 / ws) * 32;
+    if (pl.rows_per_wg % per_r) return false;
+    const int r = pl.rows_per_wg / per_r;
+    if ((r != 1 && r != 2 && r != 4) || q * r > 4) return false;
+    if (ws == 4 && q * r * (pl.batch_tile / 32) == 8) return false;  // would not fit the register file
     if (pl.row_mode != 0 || pl.xcd_skew != 0 || pl.tiles_per_split < 1) return false;
     const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
     if (pl.tiles_per_split > groups) pl.tiles_per_split = groups;
     pl.chunk_splits = (groups + pl.tiles_per_split - 1) / pl.tiles_per_split;
     pl.row_blocks = (m + pl.rows_per_wg - 1) / pl.rows_per_wg;
     pl.batch_tiles = (batch + pl.batch_tile - 1) / pl.batch_tile;
-    pl.lds_bytes = (int)(2 * unpack_stage_pieces(pl.batch_tile) * 16);
+    pl.lds_bytes = ws == 1 ? 48 * 1024 : 96 * 1024;   // two pipeline stages (UnpackGeom::LDS_BYTES)
     const long long tasks = (long long)pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
     if (tasks > (1ll << 30)) return false;
     // prepared input: 6 bytes per (padded column, padded element)
@@ -85,6 +88,7 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     const int C = ceil_div(n, mu);
     if (pl.kernel < 0 || pl.kernel >= KERNEL_COUNT) return false;
     if (pl.kernel == KERNEL_UNPACK_MFMA) return plan_finish_unpack(pl, m, n, q, batch);
+    if (pl.wave_splits != 0) return false;  // unpack_mfma only
     if (pl.threads < 64 || pl.threads > 1024 || pl.threads % 64) return false;
     if (pl.kernel == KERNEL_GEMV8) {
         // mu = 8, one input vector, at most 4 planes; one 128-chunk tile per workgroup
@@ -156,22 +160,34 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
     if (!tables_given && q <= 4 && unpack_mfma_is_faster(m, n, q, batch, mu)) {
         // Many input vectors: the contraction is compute bound and the matrix cores beat the
         // table lookups (the crossover of Sec. IV-B / Fig. 10).  Column tile 64 only when that
-        // still leaves two tiles of columns; the most rows per workgroup that still give 128
-        // workgroups before splitting; key groups split (powers of two) until every CU has a
-        // workgroup.
+        // still leaves two tiles of columns.  Waves hold as many MFMA tiles as the planes allow
+        // (fewer B-operand reads and bit expansions per MFMA); to give every CU a workgroup the
+        // contraction is split over workgroups (partial results through the workspace, summed by
+        // a second kernel); only if that is not enough, waves take fewer rows.  For short calls
+        // (below about 25 us of MFMA work) the first factor 2 of the split goes to two wave
+        // groups inside a workgroup instead (partial sums added in LDS), which there saves more
+        // on the second kernel than it costs in the first; measured, with 3 or more tiles per wave.
         pl.kernel = KERNEL_UNPACK_MFMA;
         pl.threads = kUnpackThreads;
         pl.chunks_per_tile = kUnpackGroupBytes;
         pl.batch_tile = batch >= 128 ? 64 : 32;
+        const int ct = pl.batch_tile / 32;
         const int col_groups = ceil_div(batch, pl.batch_tile);
-        int rpw = q == 1 ? 4 : (q == 2 ? 2 : 1);
-        while (rpw > 1 && (long long)ceil_div(m, 128 * rpw) * col_groups < 128) rpw >>= 1;
-        pl.rows_per_wg = 128 * rpw;
         const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
-        const long long wgs = (long long)ceil_div(m, pl.rows_per_wg) * col_groups;
-        int S = 1;
-        while (wgs * S < kNumCu && 2 * S <= groups) S *= 2;
-        pl.tiles_per_split = ceil_div(groups, S);
+        for (int rpw = q == 1 ? 4 : (q == 2 ? 2 : 1); rpw >= 1; rpw >>= 1) {
+            const bool short_call = 6.0 * q * m * n * (col_groups * pl.batch_tile) / 1.3e15 < 25e-6;
+            const int ws = (short_call && q * rpw * ct >= 3 && groups >= 2) ? 2 : 1;
+            const int rows = (4 / ws) * 32 * rpw;
+            const long long wgs = (long long)ceil_div(m, rows) * col_groups;
+            int S = 1;
+            while (wgs * S < kNumCu && 2 * S * ws <= groups) S *= 2;
+            if (wgs * S >= 3 * kNumCu / 4 || rpw == 1) {
+                pl.wave_splits = ws;
+                pl.rows_per_wg = rows;
+                pl.tiles_per_split = ceil_div(groups, S);
+                break;
+            }
+        }
         plan_finish(pl, m, n, q, batch, mu);
         return;
     }
@@ -378,9 +394,10 @@ hipError_t launch_gemm8x2(int q, const QueryParams& qp, int grid, int threads, i
     }
 }
 
-template <int Q, int RPW, int CT>
+template <int Q, int RPW, int CT, int WS>
 hipError_t launch_unpack_inst(const UnpackParams& up, int grid, int lds, hipStream_t s) {
-    auto kern = unpack_mfma_kernel<Q, RPW, CT>;
+    auto kern = unpack_mfma_kernel<Q, RPW, CT, WS>;
+    if (lds != UnpackGeom<CT, WS>::LDS_BYTES) return hipErrorInvalidValue;
     static bool granted = false;
     if (!granted) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -392,18 +409,31 @@ hipError_t launch_unpack_inst(const UnpackParams& up, int grid, int lds, hipStre
     return hipGetLastError();
 }
 
-template <int CT>
-hipError_t launch_unpack(int q, int rpw, const UnpackParams& up, int grid, int lds, hipStream_t s) {
+template <int CT, int WS>
+hipError_t launch_unpack_qr(int q, int rpw, const UnpackParams& up, int grid, int lds, hipStream_t s) {
     switch (q * 8 + rpw) {
-        case 1 * 8 + 1: return launch_unpack_inst<1, 1, CT>(up, grid, lds, s);
-        case 1 * 8 + 2: return launch_unpack_inst<1, 2, CT>(up, grid, lds, s);
-        case 1 * 8 + 4: return launch_unpack_inst<1, 4, CT>(up, grid, lds, s);
-        case 2 * 8 + 1: return launch_unpack_inst<2, 1, CT>(up, grid, lds, s);
-        case 2 * 8 + 2: return launch_unpack_inst<2, 2, CT>(up, grid, lds, s);
-        case 3 * 8 + 1: return launch_unpack_inst<3, 1, CT>(up, grid, lds, s);
-        case 4 * 8 + 1: return launch_unpack_inst<4, 1, CT>(up, grid, lds, s);
+        case 1 * 8 + 1: return launch_unpack_inst<1, 1, CT, WS>(up, grid, lds, s);
+        case 1 * 8 + 2: return launch_unpack_inst<1, 2, CT, WS>(up, grid, lds, s);
+        case 1 * 8 + 4: return launch_unpack_inst<1, 4, CT, WS>(up, grid, lds, s);
+        case 2 * 8 + 1: return launch_unpack_inst<2, 1, CT, WS>(up, grid, lds, s);
+        case 2 * 8 + 2: return launch_unpack_inst<2, 2, CT, WS>(up, grid, lds, s);
+        case 3 * 8 + 1: return launch_unpack_inst<3, 1, CT, WS>(up, grid, lds, s);
+        case 4 * 8 + 1: return launch_unpack_inst<4, 1, CT, WS>(up, grid, lds, s);
     }
     return hipErrorInvalidValue;  // plan_finish_unpack admits no other combination
+}
+
+hipError_t launch_unpack(int q, int rpw, int ct, int ws, const UnpackParams& up, int grid, int lds,
+                         hipStream_t s) {
+    switch (ct * 8 + ws) {
+        case 1 * 8 + 1: return launch_unpack_qr<1, 1>(q, rpw, up, grid, lds, s);
+        case 1 * 8 + 2: return launch_unpack_qr<1, 2>(q, rpw, up, grid, lds, s);
+        case 1 * 8 + 4: return launch_unpack_qr<1, 4>(q, rpw, up, grid, lds, s);
+        case 2 * 8 + 1: return launch_unpack_qr<2, 1>(q, rpw, up, grid, lds, s);
+        case 2 * 8 + 2: return launch_unpack_qr<2, 2>(q, rpw, up, grid, lds, s);
+        case 2 * 8 + 4: return launch_unpack_qr<2, 4>(q, rpw, up, grid, lds, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 // Large-batch path: split X into bf16 terms in MFMA operand order (workspace), contract, and
@@ -440,9 +470,8 @@ biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* al
     up.ntasks = pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
     up.tasks_per_xcd = ceil_div(up.ntasks, kNumXcd);
     const int grid = up.tasks_per_xcd * kNumXcd;
-    const int rpw = pl.rows_per_wg / 128;
-    const hipError_t e = CT == 2 ? launch_unpack<2>(q, rpw, up, grid, pl.lds_bytes, s)
-                                 : launch_unpack<1>(q, rpw, up, grid, pl.lds_bytes, s);
+    const int rpw = pl.rows_per_wg / ((4 / pl.wave_splits) * 32);
+    const hipError_t e = launch_unpack(q, rpw, CT, pl.wave_splits, up, grid, pl.lds_bytes, s);
     if (e != hipSuccess) return BIQ_EHIP;
     if (pl.chunk_splits > 1) {
         const long long count = (long long)batch * m;

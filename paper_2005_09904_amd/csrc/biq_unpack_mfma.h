@@ -137,15 +137,33 @@ __device__ __forceinline__ bf16x8 unpack_step(uint32_t w, uint32_t one2) {
     return __builtin_bit_cast(bf16x8, d);
 }
 
-template <int Q, int RPW, int CT>
+// Pipeline-stage geometry.  A workgroup's four waves form WS groups along the contraction
+// ("wave splits"): group kg works on its own contiguous part of the workgroup's key groups with
+// 4 / WS waves side by side along the rows, and the WS partial accumulators are added through
+// LDS in a fixed order at the end.  A stage holds KS MFMA steps of B operands for every wave
+// group; two stages are resident (48 KiB for WS = 1, 96 KiB otherwise).
+template <int CT, int WS>
+struct UnpackGeom {
+    static constexpr int KS = kUnpackStageSteps / CT / (WS == 4 ? 2 : 1);  // MFMA steps per stage
+    static constexpr int SPIECES = CT * 3 * 64;                           // 16-byte pieces per step
+    static constexpr int GPIECES = KS * SPIECES;                          // ... per stage and wave group
+    static constexpr int PIECES = WS * GPIECES;                           // ... per stage
+    static constexpr int LDS_BYTES = 2 * PIECES * 16;
+};
+
+template <int Q, int RPW, int CT, int WS>
 __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const UnpackParams p) {
-    constexpr int KS = kUnpackStageSteps / CT;        // MFMA steps per pipeline stage
+    using G = UnpackGeom<CT, WS>;
+    constexpr int KS = G::KS;
     constexpr int RT = Q * RPW;                       // row tiles (32 key rows each) per wave
-    constexpr int SPIECES = CT * 3 * 64;              // pieces per MFMA step
-    constexpr int PIECES = KS * SPIECES;              // pieces per stage
-    constexpr int PER_THREAD = PIECES / kUnpackThreads;
-    static_assert(PIECES % kUnpackThreads == 0, "");
-    extern __shared__ __align__(16) mfma_u32x4 stage_buf[];  // [2][PIECES]
+    constexpr int WROWS = 4 / WS;                     // waves side by side along the rows
+    constexpr int SPIECES = G::SPIECES;
+    constexpr int GPIECES = G::GPIECES;
+    constexpr int PIECES = G::PIECES;
+    constexpr int PER_THREAD = GPIECES / kUnpackThreads;  // per wave group
+    static_assert(GPIECES % kUnpackThreads == 0, "stage copy must divide evenly over the threads");
+    static_assert((WS - 1) * WROWS * RT * CT * 4096 <= G::LDS_BYTES, "partial sums must fit the stage buffers");
+    extern __shared__ __align__(16) mfma_u32x4 stage_buf[];  // [2][WS][GPIECES]
 
     const int wg = blockIdx.x;
     const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
@@ -157,39 +175,59 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     const int g0 = sp * p.gps;
     const int g1 = min(p.groups, g0 + p.gps);
     const int steps_total = p.groups * 16;
+    const int per = (g1 - g0 + WS - 1) / WS;          // key groups per wave group (the last may get fewer)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    const int kg = wave / WROWS;                      // this wave's group along the contraction
+    const int wrow = wave % WROWS;
     const int h = lane >> 5;
     const int lr = lane & 31;
+    const int ga = g0 + kg * per;                     // this wave's key groups [ga, gb)
+    const int gb = min(g1, ga + per);
 
-    const int rbase = rb * (128 * RPW) + wave * (32 * RPW);
+    const int rbase = rb * (WROWS * 32 * RPW) + wrow * (32 * RPW);
     const uint8_t* kptr[RT];
 #pragma unroll
     for (int i = 0; i < Q; ++i)
 #pragma unroll
         for (int rp = 0; rp < RPW; ++rp) {
-            const int row = min(rbase + rp * 32 + lr, p.m - 1);
+            const int row = min(rbase + rp * 32 + lr, p.m - 1);  // clamped: masked at the store
             kptr[i * RPW + rp] = p.K + ((size_t)i * p.m + row) * p.stride_bytes + 16 * h;
         }
     auto load_keys = [&](int g, mfma_u32x4 (&k)[RT]) {
-        const bool ok = g < g1 && (uint32_t)(32 * g + 16 * h) < p.stride_bytes;
+        const bool ok = g < gb && (uint32_t)(32 * g + 16 * h) < p.stride_bytes;
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
             k[t] = (mfma_u32x4){0u, 0u, 0u, 0u};
             if (ok) k[t] = *reinterpret_cast<const mfma_u32x4*>(kptr[t] + 32 * g);
         }
     };
+
+    // Stage copies: every thread moves PER_THREAD pieces for each wave group.  Stage `st` of wave
+    // group j covers MFMA steps [(g0 + j*per)*16 + st*KS, +KS) of the row.
+    constexpr int SPG = 16 / KS;                      // stages per key group
     const mfma_u32x4* xsrc = p.Xf + ((size_t)cg * steps_total + (size_t)g0 * 16) * SPIECES + tid;
-    auto load_stage = [&](int st_rel, mfma_u32x4 (&r)[PER_THREAD]) {
+    auto load_stage = [&](int st, mfma_u32x4 (&r)[WS][PER_THREAD]) {
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) r[i] = xsrc[(size_t)st_rel * PIECES + i * kUnpackThreads];
-    };
-    auto store_stage = [&](int buf, const mfma_u32x4 (&r)[PER_THREAD]) {
+        for (int j = 0; j < WS; ++j) {
+            const int gj = g0 + j * per + st / SPG;   // key group this stage belongs to
+            if (gj < min(g1, g0 + (j + 1) * per)) {
+                const mfma_u32x4* src = xsrc + ((size_t)j * per * 16 + (size_t)st * KS) * SPIECES;
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) stage_buf[buf * PIECES + i * kUnpackThreads + tid] = r[i];
+                for (int i = 0; i < PER_THREAD; ++i) r[j][i] = src[i * kUnpackThreads];
+            }
+        }
     };
+    auto store_stage = [&](int buf, const mfma_u32x4 (&r)[WS][PER_THREAD]) {
+#pragma unroll
+        for (int j = 0; j < WS; ++j)
+#pragma unroll
+            for (int i = 0; i < PER_THREAD; ++i)
+                stage_buf[buf * PIECES + j * GPIECES + i * kUnpackThreads + tid] = r[j][i];
+    };
+
     f32x16 acc[RT][CT];
 #pragma unroll
     for (int t = 0; t < RT; ++t)
@@ -198,56 +236,64 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][c][v] = 0.0f;
 
-    uint32_t one2 = 0x3f803f80u;
+    uint32_t one2 = 0x3f803f80u;        // two bf16 1.0, kept in a VGPR (see unpack_step)
     asm volatile("" : "+v"(one2));
     mfma_u32x4 key[RT], keyn[RT];
-    mfma_u32x4 xr[PER_THREAD];
-    load_keys(g0, key);
+    mfma_u32x4 xr[WS][PER_THREAD];
+#pragma unroll
+    for (int j = 0; j < WS; ++j)
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) xr[j][i] = (mfma_u32x4){0u, 0u, 0u, 0u};
+    load_keys(ga, key);
     load_stage(0, xr);
     store_stage(0, xr);
     __syncthreads();
 
-    constexpr int SPG = 16 / KS;   // stages per key group
-    const int nst = (g1 - g0) * SPG;
-    for (int g = g0; g < g1; ++g) {
+    const int nst = per * SPG;          // stages every wave walks through (barriers are workgroup wide)
+    for (int gi = 0; gi < per; ++gi) {
+        const int g = ga + gi;
+        const bool active = g < gb;     // wave uniform
         load_keys(g + 1, keyn);
 #pragma unroll
         for (int sg = 0; sg < SPG; ++sg) {
-            const int st_rel = (g - g0) * SPG + sg;
-            const bool more = st_rel + 1 < nst;
-            if (more) load_stage(st_rel + 1, xr);
-            const mfma_u32x4* buf = stage_buf + (sg & 1) * PIECES + lane;
-            bf16x8 bf[2][CT][3];
+            const int st = gi * SPG + sg;
+            const bool more = st + 1 < nst;
+            if (more) load_stage(st + 1, xr);
+            if (active) {
+                const mfma_u32x4* buf = stage_buf + (sg & 1) * PIECES + kg * GPIECES + lane;
+                bf16x8 bf[2][CT][3];
 #pragma unroll
-            for (int c = 0; c < CT; ++c)
+                for (int c = 0; c < CT; ++c)
 #pragma unroll
-                for (int s = 0; s < 3; ++s) bf[0][c][s] = __builtin_bit_cast(bf16x8, buf[(c * 3 + s) * 64]);
+                    for (int s = 0; s < 3; ++s) bf[0][c][s] = __builtin_bit_cast(bf16x8, buf[(c * 3 + s) * 64]);
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk) {
-                const int step = sg * KS + kk;     // 0..15 within the group
-                const int d = step >> 2, ks = step & 3;
-                if (kk + 1 < KS) {
-#pragma unroll
-                    for (int c = 0; c < CT; ++c)
-#pragma unroll
-                        for (int s = 0; s < 3; ++s)
-                            bf[(kk + 1) & 1][c][s] = __builtin_bit_cast(bf16x8, buf[(((kk + 1) * CT + c) * 3 + s) * 64]);
-                }
-                bf16x8 af[RT];
-#pragma unroll
-                for (int t = 0; t < RT; ++t) {
-                    const uint32_t w = key[t][d];
-                    af[t] = ks == 0 ? unpack_step<0>(w, one2) : ks == 1 ? unpack_step<1>(w, one2)
-                          : ks == 2 ? unpack_step<2>(w, one2) : unpack_step<3>(w, one2);
-                }
-                const int cur = kk & 1;
-#pragma unroll
-                for (int s = 0; s < 3; ++s)
-#pragma unroll
-                    for (int t = 0; t < RT; ++t)
+                for (int kk = 0; kk < KS; ++kk) {
+                    const int step = sg * KS + kk;     // 0..15 within the key group
+                    const int d = step >> 2, ks = step & 3;
+                    if (kk + 1 < KS) {
 #pragma unroll
                         for (int c = 0; c < CT; ++c)
-                            acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t], bf[cur][c][s], acc[t][c], 0, 0, 0);
+#pragma unroll
+                            for (int s = 0; s < 3; ++s)
+                                bf[(kk + 1) & 1][c][s] =
+                                    __builtin_bit_cast(bf16x8, buf[(((kk + 1) * CT + c) * 3 + s) * 64]);
+                    }
+                    bf16x8 af[RT];
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) {
+                        const uint32_t w = key[t][d];
+                        af[t] = ks == 0 ? unpack_step<0>(w, one2) : ks == 1 ? unpack_step<1>(w, one2)
+                              : ks == 2 ? unpack_step<2>(w, one2) : unpack_step<3>(w, one2);
+                    }
+#pragma unroll
+                    for (int s = 0; s < 3; ++s)
+#pragma unroll
+                        for (int t = 0; t < RT; ++t)
+#pragma unroll
+                            for (int c = 0; c < CT; ++c)
+                                acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t], bf[kk & 1][c][s],
+                                                                                    acc[t][c], 0, 0, 0);
+                }
             }
             if (more) store_stage((sg + 1) & 1, xr);
             __syncthreads();
@@ -255,7 +301,44 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
 #pragma unroll
         for (int t = 0; t < RT; ++t) key[t] = keyn[t];
     }
-    // epilogue (weights were unpacked with the opposite sign: bit set -> -1)
+
+    // ---- sum over the wave groups: groups 1.. hand their accumulators to group 0 through LDS ----
+    if constexpr (WS > 1) {
+        float4* red = reinterpret_cast<float4*>(stage_buf);   // [WS - 1][WROWS][RT * CT * 4][64 lanes]
+        if (kg > 0) {
+            float4* dst = red + ((size_t)((kg - 1) * WROWS + wrow) * (RT * CT * 4)) * 64 + lane;
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+#pragma unroll
+                for (int c = 0; c < CT; ++c)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq)
+                        dst[((t * CT + c) * 4 + vq) * 64] =
+                            make_float4(acc[t][c][4 * vq], acc[t][c][4 * vq + 1], acc[t][c][4 * vq + 2],
+                                        acc[t][c][4 * vq + 3]);
+        }
+        __syncthreads();
+        if (kg > 0) return;
+#pragma unroll
+        for (int j = 1; j < WS; ++j) {
+            const float4* src = red + ((size_t)((j - 1) * WROWS + wrow) * (RT * CT * 4)) * 64 + lane;
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+#pragma unroll
+                for (int c = 0; c < CT; ++c)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const float4 v = src[((t * CT + c) * 4 + vq) * 64];
+                        acc[t][c][4 * vq] += v.x;
+                        acc[t][c][4 * vq + 1] += v.y;
+                        acc[t][c][4 * vq + 2] += v.z;
+                        acc[t][c][4 * vq + 3] += v.w;
+                    }
+        }
+    }
+
+    // ---- epilogue: scale by -alpha (the weights were unpacked with the opposite sign), add the
+    // planes (Eq. 2), store ------------------------------------------------------------------------
     const bool vec_ok = ((p.m & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.out) & 15) == 0) &&
                         ((reinterpret_cast<uintptr_t>(p.alpha) & 15) == 0);
 #pragma unroll

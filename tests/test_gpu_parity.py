@@ -338,33 +338,47 @@ def test_error_paths_on_device_buffers(biq):
     assert need >= 0
 
 
-def _unpack_plan(biq, q, batch_tile, groups_per_split):
-    """Plan for the unpack-into-MFMA kernel (kernel 3): 256 threads, 32-byte key groups."""
-    rpw = {1: 4, 2: 2}.get(q, 1)
-    return _plan(biq, kernel=3, threads=256, ct=32, bt=batch_tile, tps=groups_per_split, rows=128 * rpw)
+def _unpack_plan(biq, q, batch_tile, groups_per_split, wave_splits=1, rpw=None):
+    """Plan for the unpack-into-MFMA kernel (kernel 3): 256 threads, 32-byte key groups,
+    rows_per_wg = (4 / wave_splits) waves x rpw row tiles of 32 rows."""
+    if rpw is None:
+        rpw = {1: 4, 2: 2}.get(q, 1)
+    plan = _plan(biq, kernel=3, threads=256, ct=32, bt=batch_tile, tps=groups_per_split,
+                 rows=(4 // wave_splits) * 32 * rpw)
+    plan.wave_splits = wave_splits
+    return plan
 
 
 UNPACK_SHAPES = [
-    # m, n, q, batch, batch_tile, key groups per split
-    (256, 256, 2, 64, 64, 1),      # one key group, full tiles
-    (300, 1000, 1, 70, 64, 2),     # ragged rows / columns / vectors, several splits
-    (129, 257, 3, 33, 64, 1),      # n not a multiple of 4 (scalar X reads), odd m (scalar stores)
-    (1024, 2048, 2, 128, 64, 8),   # one split walking 8 key groups
-    (512, 1536, 4, 32, 32, 3),     # four planes, one column tile per workgroup, two splits
-    (64, 128, 1, 1, 32, 1),        # a single input vector, half a key group (n = 128)
-    (2048, 512, 2, 100, 32, 2),    # 32-wide column tiles, ragged batch
+    # m, n, q, batch, batch_tile, key groups per split, wave splits, row tiles per wave and plane
+    (256, 256, 2, 64, 64, 1, 1, 2),      # one key group, full tiles
+    (300, 1000, 1, 70, 64, 2, 1, 4),     # ragged rows / columns / vectors, several splits
+    (129, 257, 3, 33, 64, 1, 1, 1),      # n not a multiple of 4 (scalar X reads), odd m (scalar stores)
+    (1024, 2048, 2, 128, 64, 8, 1, 2),   # one split walking 8 key groups
+    (512, 1536, 4, 32, 32, 3, 1, 1),     # four planes, one column tile per workgroup, two splits
+    (64, 128, 1, 1, 32, 1, 1, 1),        # a single input vector, half a key group (n = 128)
+    (2048, 512, 2, 100, 32, 2, 1, 1),    # 32-wide column tiles, ragged batch
+    # contraction split over the waves of a workgroup
+    (512, 2048, 2, 64, 64, 8, 2, 2),     # two wave groups, 4 key groups each
+    (300, 1800, 2, 40, 64, 8, 2, 1),     # 8 key groups asked, 8 there (1800 -> 240 B stride): 4 + 4
+    (200, 1300, 3, 33, 32, 6, 2, 1),     # 6 key groups: 3 + 3, ragged everything
+    (200, 1300, 1, 65, 64, 5, 2, 2),     # 5 of 6 key groups per split: 3 + 2, then 1 + 0
+    (1024, 4096, 3, 32, 32, 16, 4, 1),   # four wave groups, 4 key groups each
+    (100, 2300, 2, 20, 32, 10, 4, 1),    # 10 key groups: 3 + 3 + 3 + 1
+    (64, 512, 4, 96, 32, 2, 4, 1),       # fewer key groups (2) than wave groups: two of them idle
+    (96, 256, 1, 32, 32, 1, 2, 4),       # one key group, second wave group idle
 ]
 
 
-@pytest.mark.parametrize("m,n,q,b,bt,gps", UNPACK_SHAPES)
-def test_unpack_mfma_parity(biq, oracle, m, n, q, b, bt, gps):
-    _say("unpack_mfma m=%d n=%d q=%d b=%d bt=%d gps=%d" % (m, n, q, b, bt, gps))
+@pytest.mark.parametrize("m,n,q,b,bt,gps,ws,rpw", UNPACK_SHAPES)
+def test_unpack_mfma_parity(biq, oracle, m, n, q, b, bt, gps, ws, rpw):
+    _say("unpack_mfma m=%d n=%d q=%d b=%d bt=%d gps=%d ws=%d rpw=%d" % (m, n, q, b, bt, gps, ws, rpw))
     B, alpha, X = _rand_inputs(m, n, q, b, seed=4200 + m + n + q + b)
     B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
     K = gpu_pack(biq, B_dev)
-    Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps))
+    Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps, ws, rpw))
     assert_within_tolerance(Y.cpu().numpy(), oracle.gemm_dense(B, alpha, X), alpha, X,
-                            what="unpack_mfma %s" % ((m, n, q, b, bt, gps),))
+                            what="unpack_mfma %s" % ((m, n, q, b, bt, gps, ws, rpw),))
 
 
 def test_unpack_mfma_bit_exact_on_exact_inputs(biq, oracle):
@@ -378,9 +392,9 @@ def test_unpack_mfma_bit_exact_on_exact_inputs(biq, oracle):
     B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
     K = gpu_pack(biq, B_dev)
     ref = oracle.gemm_dense(B, alpha, X)
-    for bt, gps in ((64, 2), (32, 5)):
-        Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps))
-        assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref), (bt, gps)
+    for bt, gps, ws in ((64, 2, 1), (32, 5, 1), (64, 5, 2), (32, 3, 4)):
+        Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps, ws))
+        assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref), (bt, gps, ws)
 
 
 def test_unpack_mfma_does_not_depend_on_mu_and_default_plan_picks_it(biq, oracle):
