@@ -424,3 +424,48 @@ def torch_equal(a, b):
     import torch
 
     return torch.equal(a, b)
+
+
+def test_hip_graph_replay_matches_eager(biq, oracle):
+    """A sequence of biq_gemm calls (GEMV with chunk split + reduce, batched table kernel,
+    unpack_mfma with its input split and partial sums) captured into a HIP graph: every replay,
+    with eager work in between, reproduces the eager results bit for bit.  The library records
+    no memset nodes and allocates nothing, so its calls can be captured."""
+    import torch
+
+    shapes = [(2048, 2048, 2, 1), (600, 1000, 3, 6), (1024, 2048, 2, 128)]
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        calls, outs, refs = [], [], []
+        for i, (m, n, q, b) in enumerate(shapes):
+            B, alpha, X = _rand_inputs(m, n, q, b, seed=31 + i)
+            Bd, ad, Xd = device_inputs(B, alpha, X)
+            K = gpu_pack(biq, Bd)
+            Y = torch.zeros((b, m), dtype=torch.float32, device="cuda")
+            ws = torch.empty(max(biq.biq_workspace_bytes(m, n, q, b, 8), 16), dtype=torch.uint8, device="cuda")
+            plan = None
+            if i == 2:  # make sure the matrix-core path is in the graph whatever the planner prefers
+                plan = biq.biq_plan_check(m, n, q, b, 8, _unpack_plan(biq, q, 64, 4))
+                ws = torch.empty(biq.biq_plan_workspace_bytes(plan, m, b), dtype=torch.uint8, device="cuda")
+            calls.append(biq.PreparedGemm(K, ad, Xd, Y, m, n, q, b, 8, workspace=ws, plan=plan))
+            outs.append(Y)
+            refs.append((oracle.gemm_dense(B, alpha, X), alpha, X))
+        for c in calls:
+            c()
+        torch.cuda.synchronize()
+        eager = [y.clone() for y in outs]
+        for y, (ref, alpha, X) in zip(eager, refs):
+            assert_within_tolerance(y.cpu().numpy(), ref, alpha, X, "eager")
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            for c in calls:
+                c()
+        for rep in range(4):
+            _say("graph replay %d" % rep)
+            for y in outs:
+                y.fill_(float("nan"))        # eager work between replays
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for y, e in zip(outs, eager):
+                assert torch.equal(y, e), "replay %d differs from the eager result" % rep
