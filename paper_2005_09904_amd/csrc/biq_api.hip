@@ -6,6 +6,7 @@
 #include "biq_kernels.h"
 #include "biq_gemv8.h"
 #include "biq_gemm8x2.h"
+#include "biq_gemv8h.h"
 #include "biq_unpack_mfma.h"
 
 namespace {
@@ -18,7 +19,7 @@ constexpr int kLdsTableBudget = 128 * 1024;  // tables of one tile (leaves room 
 constexpr int kNumCu = 256;
 constexpr int kNumXcd = 8;
 
-enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL_UNPACK_MFMA = 3, KERNEL_COUNT };
+enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL_UNPACK_MFMA = 3, KERNEL_GEMV8H = 4, KERNEL_COUNT };
 
 inline bool shape_ok(int m, int n, int q, int batch, int mu) {
     if (m < 1 || n < 1 || q < 1 || batch < 1) return false;
@@ -75,6 +76,7 @@ inline int plan_lds_bytes(const biq_plan& pl, int mu) {
     if (pl.kernel == KERNEL_GEMV8)
         return kGemvTileBytes +
                (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + pl.xcd_skew + 63) / 64) * 64 * 4 : 0);
+    if (pl.kernel == KERNEL_GEMV8H) return kGemvHalfTileBytes;
     if (pl.kernel == KERNEL_GEMM8X2)
         return kGemmTileBytes + (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + 63) / 64) * 64 * 8 : 0);
     long long b = (long long)pl.chunks_per_tile * (1 << mu) * pl.batch_tile * 4;
@@ -96,6 +98,13 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
         if (pl.chunks_per_tile != kGemvTileChunks || pl.batch_tile != 1) return false;
         // 32-bit byte offsets inside a workgroup's row block
         if ((long long)pl.rows_per_wg * (long long)biq_key_row_stride(n) >= (1ll << 31)) return false;
+    }
+    if (pl.kernel == KERNEL_GEMV8H) {
+        // mu = 8, one input vector, at most 4 planes; one 256-chunk tile of half tables per
+        // workgroup, latency mode only
+        if (mu != 8 || batch != 1 || q > 4) return false;
+        if (pl.chunks_per_tile != kGemvHalfTileChunks || pl.batch_tile != 1) return false;
+        if (pl.row_mode != 1 || pl.tiles_per_split != 1) return false;
     }
     if (pl.kernel == KERNEL_GEMM8X2) {
         // mu = 8, at most 4 planes; 64-chunk tiles of two input vectors
@@ -211,12 +220,24 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
                 pl.xcd_skew = ((pl.rows_per_wg * 8 / 100 + 32) / 64) * 64;
                 if (tiles > 1 && pl.rows_per_wg + pl.xcd_skew > 8192) pl.xcd_skew = 0;
             }
+        } else if (C > kGemvTileChunks && (long long)m * ceil_div(C, kGemvHalfTileChunks) <= 256ll * kNumCu) {
+            // small, wider than one full-table tile: half tables (256 chunks per workgroup), so that
+            // rows up to n = 2048 need no split and no second kernel.  One workgroup per CU if the
+            // rows allow it (a second round of workgroups pays the table build again), at least
+            // 8 rows each; 4 rows per wave step, at most 4 steps per wave.
+            pl.kernel = KERNEL_GEMV8H;
+            pl.chunks_per_tile = kGemvHalfTileChunks;
+            pl.tiles_per_split = 1;
+            pl.row_mode = 1;
+            const int tiles_h = ceil_div(C, kGemvHalfTileChunks);
+            int rows = ceil_div(ceil_div((long long)m * tiles_h, kNumCu), 4) * 4;
+            pl.rows_per_wg = rows < 8 ? 8 : rows;
         } else if ((long long)m * tiles <= 4ll * 128 * kNumCu) {
             // small: latency mode, 8 rows per wave step, at most 4 steps per wave
             pl.tiles_per_split = 1;
             pl.row_mode = 1;
-            int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 128) * 128;
-            pl.rows_per_wg = rows;
+            int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 8) * 8;
+            pl.rows_per_wg = rows < 8 ? 8 : rows;
         } else {
             pl.tiles_per_split = 1;
             int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 64) * 64;
@@ -367,6 +388,30 @@ hipError_t launch_gemv8(int q, const QueryParams& qp, int grid, int threads, int
         case 2: return launch_gemv8_inst<2, FUSED>(qp, grid, threads, lds, s);
         case 3: return launch_gemv8_inst<3, FUSED>(qp, grid, threads, lds, s);
         default: return launch_gemv8_inst<4, FUSED>(qp, grid, threads, lds, s);
+    }
+}
+
+template <int Q, bool FUSED>
+hipError_t launch_gemv8h_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    auto kern = gemv8h_kernel<Q, FUSED>;
+    static bool granted = false;
+    if (!granted) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+        if (e != hipSuccess) return e;
+        granted = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
+    return hipGetLastError();
+}
+
+template <bool FUSED>
+hipError_t launch_gemv8h(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    switch (q) {
+        case 1: return launch_gemv8h_inst<1, FUSED>(qp, grid, threads, lds, s);
+        case 2: return launch_gemv8h_inst<2, FUSED>(qp, grid, threads, lds, s);
+        case 3: return launch_gemv8h_inst<3, FUSED>(qp, grid, threads, lds, s);
+        default: return launch_gemv8h_inst<4, FUSED>(qp, grid, threads, lds, s);
     }
 }
 
@@ -535,6 +580,9 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     if (pl.kernel == KERNEL_GEMV8)
         e = fused ? launch_gemv8<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
                   : launch_gemv8<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
+    else if (pl.kernel == KERNEL_GEMV8H)
+        e = fused ? launch_gemv8h<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
+                  : launch_gemv8h<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
     else if (pl.kernel == KERNEL_GEMM8X2)
         e = fused ? launch_gemm8x2<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
                   : launch_gemm8x2<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
@@ -624,6 +672,7 @@ const char* biq_kernel_name(int kernel) {
         case KERNEL_GEMV8: return "gemv8";
         case KERNEL_GEMM8X2: return "gemm8x2";
         case KERNEL_UNPACK_MFMA: return "unpack_mfma";
+        case KERNEL_GEMV8H: return "gemv8_half";
     }
     return "unknown";
 }

@@ -1,0 +1,177 @@
+// LUT query for mu = 8, batch = 1, small layers: half tables.
+//
+// Algorithm 1 fills the second half of a table by negating the first (q[2^mu - 1 - k] = -q[k]).
+// This kernel does not store that half at all: LDS holds entries 0..127 of every chunk and a
+// lookup with key k >= 128 reads entry ~k & 127 and negates it.  A 128 KiB tile then covers 256
+// chunks (n = 2048) instead of 128, so that layers up to that width need no split of the row
+// over workgroups and no second kernel to add partial sums - which is what the run time of a
+// small GEMV consists of.  The price is 4 more VALU instructions per lookup, irrelevant here;
+// the streaming kernel for large matrices (biq_gemv8.h) keeps full tables.
+//
+// LDS layout.  A row's 256-byte key segment is covered by 16 lanes (lane L holds bytes
+// [16L, 16L+16)), a wave load covers 4 rows.  Chunk c = 16*L + 4*td + e of the tile (td = dword
+// of the lane's 16 bytes, e = byte in the dword), entry idx (0..127):
+//       td * 32768 + idx * 256 + (e >> 1) * 128 + (e & 1) * 64 + L * 4
+// The bank is L + 16 * (e & 1).  LDS serves a wave in halves of 32 lanes = 2 rows x 16 L; at
+// static step te the lane of row rho visits byte e = (te + rho) & 3, so the two rows of a half
+// use different parities of e and the 32 lanes hit 32 different banks for any keys.
+#pragma once
+
+#include "biq_gemv8.h"
+
+namespace biq {
+
+constexpr int kGemvHalfTileChunks = 256;
+constexpr int kGemvHalfTileBytes = kGemvHalfTileChunks * 128 * 4;  // 131072
+
+__device__ __forceinline__ uint32_t gemv8h_slot_offset(int L, int td, int e) {
+    return (uint32_t)(td * 32768 + (e >> 1) * 128 + (e & 1) * 64 + L * 4);
+}
+
+// Sum over each aligned group of 16 lanes; every lane of the group gets the total.
+__device__ __forceinline__ float reduce16(float v) {
+    v = reduce8(v);
+    v = dpp_add<0x140>(v);  // row_mirror
+    return v;
+}
+
+// Entries 0..127 of the tables of chunks [c0, c0 + 256), built from X into the layout above.
+// One job = (pair of chunks adjacent in L, 16 keys): 8 x 4 x 4 x 8 = 1024 jobs.
+__device__ __forceinline__ void gemv8h_build_tile(const QueryParams& p, char* lds_bytes, int c0,
+                                                  int tid, int nthreads) {
+    const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+    for (int job = tid; job < 1024; job += nthreads) {
+        const int Lp = job & 7, e = (job >> 3) & 3, td = (job >> 5) & 3, h = job >> 7;
+        float xa[8], xb[8], ea[16], eb[16];
+        const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
+        const int cb = ca + 16;
+        if (vec_ok && 8 * cb + 8 <= p.n) {
+            const float4* xv = reinterpret_cast<const float4*>(p.X);
+            const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], b0 = xv[2 * cb], b1 = xv[2 * cb + 1];
+            xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
+            xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
+            xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w;
+            xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
+        } else {
+            load_chunk_x<8>(p.X, p.n, 1, 0, ca, xa);
+            load_chunk_x<8>(p.X, p.n, 1, 0, cb, xb);
+        }
+        table16(xa, (uint32_t)h, ea);   // keys 16h .. 16h + 15, h < 8: the stored half
+        table16(xb, (uint32_t)h, eb);
+        char* dst = lds_bytes + gemv8h_slot_offset(2 * Lp, td, e) + (h * 16) * 256;
+#pragma unroll
+        for (int l = 0; l < 16; ++l)
+            *reinterpret_cast<float2*>(dst + l * 256) = make_float2(ea[l], eb[l]);
+    }
+}
+
+// The same half tables copied from tables in device memory (LUT [C][256][1]).
+__device__ __forceinline__ void gemv8h_copy_tile(const QueryParams& p, char* lds_bytes, int c0,
+                                                 int tid, int nthreads) {
+    for (int i = tid; i < kGemvHalfTileChunks * 128; i += nthreads) {
+        const int idx = i & 127, c = i >> 7;
+        const int cL = c >> 4, td = (c >> 2) & 3, e = c & 3;
+        float v = 0.0f;
+        if (c0 + c < p.C) v = p.LUT[(size_t)(c0 + c) * 256 + idx];
+        *reinterpret_cast<float*>(lds_bytes + gemv8h_slot_offset(cL, td, e) + idx * 256) = v;
+    }
+}
+
+// One 256-chunk tile per workgroup, one step of 4 rows per wave at a time; the first step's
+// keys and scales are requested before the tables are built.
+template <int Q, bool FUSED>
+__global__ __launch_bounds__(1024) void gemv8h_kernel(const QueryParams p) {
+    extern __shared__ __align__(16) float lds[];
+    char* const lds_bytes = reinterpret_cast<char*>(lds);
+
+    const int wg = blockIdx.x;
+    const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
+    if (task >= p.ntasks) return;
+    const int sp = task % p.splits;
+    const int rb = task / p.splits;
+    const int r0 = rb * p.rows_per_wg;
+    const int r1 = min(p.m, r0 + p.rows_per_wg);
+    const int tile = sp;  // one tile per split
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    // lookups address LDS absolutely (see lds_read_abs)
+    if (lds_address_of(lds) != 0u) return;
+
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int nwaves = nthreads >> 6;
+    const int L = lane & 15;
+    const int rsub = lane >> 4;  // row inside the wave step, 0..3
+    const int rho = rsub & 1;    // the two rows of a 32-lane half use different byte parities
+
+    // v_perm_b32: S0 = key dword, S1 = base; byte 0 <- base byte 0, byte 1 <- key byte
+    // (te + rho) & 3, byte 2 <- base byte 2 (td >> 1), byte 3 <- 0.
+    uint32_t sel[4], base[2][4];
+#pragma unroll
+    for (int te = 0; te < 4; ++te) {
+        const int e = (te + rho) & 3;
+        sel[te] = 0x0c020000u | ((uint32_t)(4 + e) << 8);
+        base[0][te] = (uint32_t)((e >> 1) * 128 + (e & 1) * 64 + L * 4);
+        base[1][te] = base[0][te] | 0x10000u;
+    }
+
+    auto lookup16 = [&](const u32x4& k) -> float {
+        const uint32_t w[4] = {k.x, k.y, k.z, k.w};
+        float a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+        for (int td = 0; td < 4; ++td) {
+#pragma unroll
+            for (int te = 0; te < 4; ++te) {
+                const uint32_t t = __builtin_amdgcn_perm(w[td], base[td >> 1][te], sel[te]);
+                // bit 15 = bit 7 of the key: entry ~key & 127, negated
+                const int32_t neg = (int32_t)(t << 16) >> 31;                  // 0 or -1
+                const uint32_t addr = t ^ ((uint32_t)neg & 0xff00u);           // clears bit 15 as well
+                const float v = lds_read_abs(addr + (td & 1) * 32768);
+                const float sgn = __uint_as_float(((uint32_t)neg & 0x80000000u) | 0x3f800000u);
+                if (te & 1) a1 = fmaf(v, sgn, a1);
+                else a0 = fmaf(v, sgn, a0);
+            }
+        }
+        return a0 + a1;
+    };
+
+    const uint32_t stride_bytes = (uint32_t)p.stride_dw * 4u;
+    const int nrows = r1 - r0;
+    const bool have_keys = (uint32_t)(tile * 256 + L * 16) < stride_bytes;
+    const int nsteps = (nrows + 3) >> 2;
+    auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q]) {
+        const int row = 4 * s + rsub;
+        const bool ok = have_keys && s < nsteps && row < nrows;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) {
+            k[i] = (u32x4){0u, 0u, 0u, 0u};
+            al[i] = 0.0f;
+            if (ok) {
+                const size_t kr = (size_t)i * p.m + r0 + row;
+                k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(
+                    reinterpret_cast<const char*>(p.K) + kr * stride_bytes + tile * 256 + 16 * L));
+                al[i] = p.alpha[kr];
+            }
+        }
+    };
+    u32x4 k[Q], kn[Q];
+    float al[Q], aln[Q];
+    load_step(wave, k, al);
+    if constexpr (FUSED) gemv8h_build_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
+    else gemv8h_copy_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
+    __syncthreads();
+    for (int s = wave; s < nsteps; s += nwaves) {
+        load_step(s + nwaves, kn, aln);
+        float y = 0.0f;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) y = fmaf(al[i], lookup16(k[i]), y);
+        y = reduce16(y);
+        const int row = 4 * s + rsub;
+        if (L == 0 && row < nrows) p.out[(size_t)sp * p.m + r0 + row] = y;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) { k[i] = kn[i]; al[i] = aln[i]; }
+    }
+}
+
+}  // namespace biq

@@ -238,7 +238,10 @@ def test_explicit_plans_give_the_same_result(biq, oracle):
     ref = oracle.gemm_dense(B, alpha, X)
     for spec in [(1, 1024, 128, 1, 1, 64), (1, 512, 128, 1, 3, 700), (1, 64, 128, 1, 2, 130),
                  (0, 256, 64, 1, 1, 50), (1, 1024, 128, 1, 1, 128, 1), (1, 128, 128, 1, 1, 700, 1),
-                 (1, 64, 128, 1, 1, 9, 1)]:
+                 (1, 64, 128, 1, 1, 9, 1),
+                 # half-table kernel: 256-chunk tiles, 4 rows per wave step
+                 (4, 1024, 256, 1, 1, 64, 1), (4, 256, 256, 1, 1, 700, 1), (4, 64, 256, 1, 1, 5, 1),
+                 (4, 512, 256, 1, 1, 130, 1)]:
         _say("plan " + str(spec))
         Y = gpu_gemm(biq, K, ad, Xd, m, n, 3, mu, plan=_plan(biq, *spec)).cpu().numpy()
         assert_within_tolerance(Y, ref, alpha, X, "plan")
