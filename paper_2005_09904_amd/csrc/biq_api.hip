@@ -7,6 +7,7 @@
 #include "biq_gemv8.h"
 #include "biq_gemm8x2.h"
 #include "biq_gemv8h.h"
+#include "biq_gemm8x2h.h"
 #include "biq_unpack_mfma.h"
 
 namespace {
@@ -19,7 +20,7 @@ constexpr int kLdsTableBudget = 128 * 1024;  // tables of one tile (leaves room 
 constexpr int kNumCu = 256;
 constexpr int kNumXcd = 8;
 
-enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL_UNPACK_MFMA = 3, KERNEL_GEMV8H = 4, KERNEL_COUNT };
+enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL_UNPACK_MFMA = 3, KERNEL_GEMV8H = 4, KERNEL_GEMM8X2H = 5, KERNEL_COUNT };
 
 inline bool shape_ok(int m, int n, int q, int batch, int mu) {
     if (m < 1 || n < 1 || q < 1 || batch < 1) return false;
@@ -77,6 +78,7 @@ inline int plan_lds_bytes(const biq_plan& pl, int mu) {
         return kGemvTileBytes +
                (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + pl.xcd_skew + 63) / 64) * 64 * 4 : 0);
     if (pl.kernel == KERNEL_GEMV8H) return kGemvHalfTileBytes;
+    if (pl.kernel == KERNEL_GEMM8X2H) return kGemmHalfTileBytes;
     if (pl.kernel == KERNEL_GEMM8X2)
         return kGemmTileBytes + (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + 63) / 64) * 64 * 8 : 0);
     long long b = (long long)pl.chunks_per_tile * (1 << mu) * pl.batch_tile * 4;
@@ -104,6 +106,13 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
         // workgroup, latency mode only
         if (mu != 8 || batch != 1 || q > 4) return false;
         if (pl.chunks_per_tile != kGemvHalfTileChunks || pl.batch_tile != 1) return false;
+        if (pl.row_mode != 1 || pl.tiles_per_split != 1) return false;
+    }
+    if (pl.kernel == KERNEL_GEMM8X2H) {
+        // mu = 8, at most 4 planes; one 128-chunk tile of half tables for two input vectors per
+        // workgroup, latency mode only
+        if (mu != 8 || q > 4) return false;
+        if (pl.chunks_per_tile != kGemmHalfTileChunks || pl.batch_tile != 2) return false;
         if (pl.row_mode != 1 || pl.tiles_per_split != 1) return false;
     }
     if (pl.kernel == KERNEL_GEMM8X2) {
@@ -243,6 +252,24 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
             int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 64) * 64;
             pl.rows_per_wg = rows > 8192 ? 8192 : rows;
         }
+        plan_finish(pl, m, n, q, batch, mu);
+        return;
+    }
+    if (mu == 8 && batch >= 2 && q <= 4 && C > kGemmTileChunks &&
+        (long long)m * ceil_div(C, kGemmHalfTileChunks) * ceil_div(batch, 2) <= 512ll * kNumCu) {
+        // Small batched calls wider than one full-table tile: half tables (128 chunks x 2 input
+        // vectors per workgroup) halve the number of row splits; up to n = 1024 there is none and
+        // no second kernel.  One workgroup per CU if the rows allow it, at least 8 rows each;
+        // 8 rows per wave step, at most 4 steps per wave.
+        pl.kernel = KERNEL_GEMM8X2H;
+        pl.threads = 1024;
+        pl.chunks_per_tile = kGemmHalfTileChunks;
+        pl.batch_tile = 2;
+        pl.tiles_per_split = 1;
+        pl.row_mode = 1;
+        const long long units = (long long)m * ceil_div(C, kGemmHalfTileChunks) * ceil_div(batch, 2);
+        int rows = ceil_div(ceil_div(units, kNumCu), 8) * 8;
+        pl.rows_per_wg = rows < 8 ? 8 : rows;
         plan_finish(pl, m, n, q, batch, mu);
         return;
     }
@@ -416,6 +443,30 @@ hipError_t launch_gemv8h(int q, const QueryParams& qp, int grid, int threads, in
 }
 
 template <int Q, bool FUSED>
+hipError_t launch_gemm8x2h_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    auto kern = gemm8x2h_kernel<Q, FUSED>;
+    static bool granted = false;
+    if (!granted) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+        if (e != hipSuccess) return e;
+        granted = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
+    return hipGetLastError();
+}
+
+template <bool FUSED>
+hipError_t launch_gemm8x2h(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    switch (q) {
+        case 1: return launch_gemm8x2h_inst<1, FUSED>(qp, grid, threads, lds, s);
+        case 2: return launch_gemm8x2h_inst<2, FUSED>(qp, grid, threads, lds, s);
+        case 3: return launch_gemm8x2h_inst<3, FUSED>(qp, grid, threads, lds, s);
+        default: return launch_gemm8x2h_inst<4, FUSED>(qp, grid, threads, lds, s);
+    }
+}
+
+template <int Q, bool FUSED>
 hipError_t launch_gemm8x2_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     auto kern = gemm8x2_kernel<Q, FUSED>;
     static bool granted = false;
@@ -583,6 +634,9 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     else if (pl.kernel == KERNEL_GEMV8H)
         e = fused ? launch_gemv8h<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
                   : launch_gemv8h<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
+    else if (pl.kernel == KERNEL_GEMM8X2H)
+        e = fused ? launch_gemm8x2h<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
+                  : launch_gemm8x2h<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
     else if (pl.kernel == KERNEL_GEMM8X2)
         e = fused ? launch_gemm8x2<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
                   : launch_gemm8x2<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
@@ -673,6 +727,7 @@ const char* biq_kernel_name(int kernel) {
         case KERNEL_GEMM8X2: return "gemm8x2";
         case KERNEL_UNPACK_MFMA: return "unpack_mfma";
         case KERNEL_GEMV8H: return "gemv8_half";
+        case KERNEL_GEMM8X2H: return "gemm8x2_half";
     }
     return "unknown";
 }

@@ -1,0 +1,185 @@
+// LUT query for mu = 8, batch >= 2, small layers: half tables, two input vectors per pass.
+//
+// The batched counterpart of biq_gemv8h.h: LDS holds entries 0..127 of every table (the upper
+// half is the negated lower half, Algorithm 1), a key k >= 128 reads entry ~k & 127 and the
+// value enters the sum with factor -1.  A 128 KiB tile then covers 128 chunks x 2 input vectors
+// instead of 64 x 2, so layers up to n = 1024 need no split of the row over workgroups and no
+// second kernel for partial sums.  Used for small calls only (run time = dispatch + latencies).
+//
+// LDS layout.  8 lanes cover a row's 128-byte key segment, a wave load covers 8 rows.  Chunk
+// c = 16*L + 4*td + e of the tile, vector v (0/1), entry idx (0..127):
+//       td * 32768 + idx * 256 + v * 128 + (L + 8*e) * 4
+// One address serves both vectors (128 bytes apart, one ds_read2_b32).  The bank is L + 8*e; an
+// LDS half-wave is 4 rows x 8 L and row rho visits byte e = (te + rho) & 3 at static step te:
+// 32 different banks for any keys.
+#pragma once
+
+#include "biq_gemv8h.h"
+
+namespace biq {
+
+constexpr int kGemmHalfTileChunks = 128;
+constexpr int kGemmHalfTileBytes = kGemmHalfTileChunks * 128 * 2 * 4;  // 131072
+
+__device__ __forceinline__ uint32_t gemm8x2h_slot_offset(int L, int td, int e, int v) {
+    return (uint32_t)(td * 32768 + v * 128 + (L + 8 * e) * 4);
+}
+
+// Entries 0..127 of the tables of chunks [c0, c0 + 128) for input vectors b0, b0 + 1.
+// One job = (vector, pair of chunks adjacent in L, 16 keys): 2 x 4 x 4 x 4 x 8 = 1024 jobs.
+__device__ __forceinline__ void gemm8x2h_build_tile(const QueryParams& p, char* lds_bytes, int c0,
+                                                    int b0, int tid, int nthreads) {
+    const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+    for (int job = tid; job < 1024; job += nthreads) {
+        const int Lp = job & 3, e = (job >> 2) & 3, td = (job >> 4) & 3, v = (job >> 6) & 1, h = job >> 7;
+        float xa[8], xb[8], ea[16], eb[16];
+        const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
+        const int cb = ca + 16;
+        const int col = b0 + v;
+        if (vec_ok && col < p.batch && 8 * cb + 8 <= p.n) {
+            const float4* xv = reinterpret_cast<const float4*>(p.X + (size_t)col * p.n);
+            const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], q0 = xv[2 * cb], q1 = xv[2 * cb + 1];
+            xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
+            xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
+            xb[0] = q0.x; xb[1] = q0.y; xb[2] = q0.z; xb[3] = q0.w;
+            xb[4] = q1.x; xb[5] = q1.y; xb[6] = q1.z; xb[7] = q1.w;
+        } else {
+            load_chunk_x<8>(p.X, p.n, p.batch, col, ca, xa);
+            load_chunk_x<8>(p.X, p.n, p.batch, col, cb, xb);
+        }
+        table16(xa, (uint32_t)h, ea);   // keys 16h .. 16h + 15, h < 8: the stored half
+        table16(xb, (uint32_t)h, eb);
+        char* dst = lds_bytes + gemm8x2h_slot_offset(2 * Lp, td, e, v) + (h * 16) * 256;
+#pragma unroll
+        for (int l = 0; l < 16; ++l)
+            *reinterpret_cast<float2*>(dst + l * 256) = make_float2(ea[l], eb[l]);
+    }
+}
+
+// The same half tables copied from tables in device memory (LUT [C][256][batch]).
+__device__ __forceinline__ void gemm8x2h_copy_tile(const QueryParams& p, char* lds_bytes, int c0,
+                                                   int b0, int tid, int nthreads) {
+    for (int i = tid; i < kGemmHalfTileChunks * 128 * 2; i += nthreads) {
+        const int v = i & 1, idx = (i >> 1) & 127, c = i >> 8;
+        const int cL = c >> 4, td = (c >> 2) & 3, e = c & 3;
+        float val = 0.0f;
+        if (c0 + c < p.C && b0 + v < p.batch)
+            val = p.LUT[((size_t)(c0 + c) * 256 + idx) * p.batch + b0 + v];
+        *reinterpret_cast<float*>(lds_bytes + gemm8x2h_slot_offset(cL, td, e, v) + idx * 256) = val;
+    }
+}
+
+// One 128-chunk tile and one pair of input vectors per workgroup, one step of 8 rows per wave
+// at a time; the first step's keys and scales are requested before the tables are built.
+template <int Q, bool FUSED>
+__global__ __launch_bounds__(1024) void gemm8x2h_kernel(const QueryParams p) {
+    extern __shared__ __align__(16) float lds[];
+    char* const lds_bytes = reinterpret_cast<char*>(lds);
+
+    const int wg = blockIdx.x;
+    const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
+    if (task >= p.ntasks) return;
+    const int bt = task % p.batch_tiles;
+    const int rest = task / p.batch_tiles;
+    const int sp = rest % p.splits;
+    const int rb = rest / p.splits;
+    const int b0 = bt * 2;
+    const int r0 = rb * p.rows_per_wg;
+    const int r1 = min(p.m, r0 + p.rows_per_wg);
+    const int tile = sp;  // one tile per split
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    // lookups address LDS absolutely (see lds_read_abs)
+    if (lds_address_of(lds) != 0u) return;
+
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int nwaves = nthreads >> 6;
+    const int L = lane & 7;
+    const int rsub = lane >> 3;  // row inside the wave step, 0..7
+    const int rho = rsub & 3;    // byte rotation: the 4 rows of a 32-lane half get distinct values
+
+    // v_perm_b32: S0 = key dword, S1 = base; byte 0 <- base byte 0, byte 1 <- key byte
+    // (te + rho) & 3, byte 2 <- base byte 2 (td >> 1), byte 3 <- 0.
+    uint32_t sel[4], base[2][4];
+#pragma unroll
+    for (int te = 0; te < 4; ++te) {
+        const int e = (te + rho) & 3;
+        sel[te] = 0x0c020000u | ((uint32_t)(4 + e) << 8);
+        base[0][te] = (uint32_t)((L + 8 * e) * 4);
+        base[1][te] = base[0][te] | 0x10000u;
+    }
+
+    auto lookup16 = [&](const u32x4& k, float& s0, float& s1) {
+        const uint32_t w[4] = {k.x, k.y, k.z, k.w};
+        float a0 = 0.0f, a1 = 0.0f, c0 = 0.0f, c1 = 0.0f;
+#pragma unroll
+        for (int td = 0; td < 4; ++td) {
+#pragma unroll
+            for (int te = 0; te < 4; ++te) {
+                const uint32_t t = __builtin_amdgcn_perm(w[td], base[td >> 1][te], sel[te]);
+                // bit 15 = bit 7 of the key: entry ~key & 127, negated
+                const int32_t neg = (int32_t)(t << 16) >> 31;                  // 0 or -1
+                uint32_t addr = t ^ ((uint32_t)neg & 0xff00u);                 // clears bit 15 as well
+                if (td & 1) addr |= 0x8000u;
+                const float v0 = lds_read_abs(addr);
+                const float v1 = lds_read_abs(addr + 128);
+                const float sgn = __uint_as_float(((uint32_t)neg & 0x80000000u) | 0x3f800000u);
+                if (te & 1) { a1 = fmaf(v0, sgn, a1); c1 = fmaf(v1, sgn, c1); }
+                else { a0 = fmaf(v0, sgn, a0); c0 = fmaf(v1, sgn, c0); }
+            }
+        }
+        s0 = a0 + a1;
+        s1 = c0 + c1;
+    };
+
+    const uint32_t stride_bytes = (uint32_t)p.stride_dw * 4u;
+    const int nrows = r1 - r0;
+    const bool have_keys = (uint32_t)(tile * 128 + L * 16) < stride_bytes;
+    const int nsteps = (nrows + 7) >> 3;
+    auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q]) {
+        const int row = 8 * s + rsub;
+        const bool ok = have_keys && s < nsteps && row < nrows;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) {
+            k[i] = (u32x4){0u, 0u, 0u, 0u};
+            al[i] = 0.0f;
+            if (ok) {
+                const size_t kr = (size_t)i * p.m + r0 + row;
+                k[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.K) +
+                                                       kr * stride_bytes + tile * 128 + 16 * L);
+                al[i] = p.alpha[kr];
+            }
+        }
+    };
+    u32x4 k[Q], kn[Q];
+    float al[Q], aln[Q];
+    load_step(wave, k, al);
+    if constexpr (FUSED) gemm8x2h_build_tile(p, lds_bytes, tile * kGemmHalfTileChunks, b0, tid, nthreads);
+    else gemm8x2h_copy_tile(p, lds_bytes, tile * kGemmHalfTileChunks, b0, tid, nthreads);
+    __syncthreads();
+    for (int s = wave; s < nsteps; s += nwaves) {
+        load_step(s + nwaves, kn, aln);
+        float y0 = 0.0f, y1 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) {
+            float s0, s1;
+            lookup16(k[i], s0, s1);
+            y0 = fmaf(al[i], s0, y0);
+            y1 = fmaf(al[i], s1, y1);
+        }
+        y0 = reduce8(y0);
+        y1 = reduce8(y1);
+        const int row = 8 * s + rsub;
+        if (L == 0 && row < nrows) {
+            float* out = p.out + ((size_t)sp * p.batch + b0) * p.m + r0 + row;
+            out[0] = y0;
+            if (b0 + 1 < p.batch) out[p.m] = y1;
+        }
+#pragma unroll
+        for (int i = 0; i < Q; ++i) { k[i] = kn[i]; al[i] = aln[i]; }
+    }
+}
+
+}  // namespace biq

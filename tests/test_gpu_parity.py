@@ -225,6 +225,8 @@ def test_explicit_plans_give_the_same_result(biq, oracle):
              (0, 1024, 128, 1, 2, 33), (0, 128, 16, 8, 7, 1),
              # batched mu=8 kernel: 64-chunk tiles of 2 vectors
              (2, 1024, 64, 2, 1, 64), (2, 512, 64, 2, 2, 128), (2, 256, 64, 2, 6, 704), (2, 64, 64, 2, 3, 100),
+             # half-table batched kernel: 128-chunk tiles of 2 vectors, 8 rows per wave step
+             (5, 1024, 128, 2, 1, 64, 1), (5, 256, 128, 2, 1, 700, 1), (5, 64, 128, 2, 1, 9, 1),
              # ... in latency mode (one step of 16 rows per wave)
              (2, 1024, 64, 2, 1, 256, 1), (2, 256, 64, 2, 1, 700, 1), (2, 64, 64, 2, 1, 17, 1)]
     for spec in plans:
