@@ -57,6 +57,7 @@ def _load():
         lib.biqo_gemm_dense_rows.argtypes = [P, P, P, L, L, I, L, P, L, P]
         lib.biqo_gemm_dense.argtypes = [P, P, P, L, L, I, L, P]
         lib.biqo_gemm_lut.argtypes = [P, P, P, L, L, I, L, I, P]
+        lib.biqo_quantize_greedy.argtypes = [P, L, L, I, P, P, P]
         _lib = lib
     return _lib
 
@@ -180,3 +181,18 @@ def gemm_lut(keys, alpha, X, mu: int) -> np.ndarray:
     Y = np.zeros((b, m), dtype=np.float64)
     _check(_load().biqo_gemm_lut(_ptr(keys), _ptr(alpha), _ptr(X), m, n, q, b, mu, _ptr(Y)), "gemm_lut")
     return Y
+
+
+def quantize_greedy(W, q: int, with_residuals: bool = False):
+    """Greedy binary-coding quantisation of each row of W (Eq. 1): returns (B int8 [q][m][n],
+    alpha float64 [q][m]) and, on request, the residual every plane's signs were taken from."""
+    W = _arr(W, np.float32, 2)
+    m, n = W.shape
+    if q < 1:
+        raise OracleError("q must be >= 1")
+    B = np.zeros((q, m, n), dtype=np.int8)
+    alpha = np.zeros((q, m), dtype=np.float64)
+    R = np.zeros((q, m, n), dtype=np.float64) if with_residuals else None
+    _check(_load().biqo_quantize_greedy(_ptr(W), m, n, q, _ptr(B), _ptr(alpha),
+                                        _ptr(R) if R is not None else None), "quantize_greedy")
+    return (B, alpha, R) if with_residuals else (B, alpha)

@@ -241,3 +241,40 @@ int biqo_gemm_lut(const uint16_t* keys, const float* alpha, const float* X, long
     free(Q);
     return BIQO_OK;
 }
+
+/*
+ * Binary-coding quantisation of a matrix, row by row (Sec. II-B, Eq. 1):
+ * w ~ sum_{i=1..q} alpha_i b_i with b_i in {-1,+1}^n, one alpha per row and plane.
+ * The paper names the heuristic only ("greedy approximation"); the procedure here is the greedy
+ * one that Eq. 1 itself suggests, one plane at a time on the residual r (r = w at the start):
+ *     b_i = sign(r)      (for fixed alpha > 0 this minimises ||r - alpha b||^2 element by element;
+ *                         sign(0) is taken as +1)
+ *     alpha_i = (r . b_i) / n = mean |r|        (least squares in alpha for that b)
+ *     r <- r - alpha_i b_i
+ * so that every step is the exact minimiser of Eq. 1 for q = 1 applied to the residual, and
+ * ||r_new||^2 = ||r||^2 - n alpha_i^2.
+ * W float [m][n]; B int8 [q][m][n]; alpha double [q][m]; R (may be NULL) double [q][m][n] receives
+ * the residual each plane's signs were taken from (its magnitude tells how firm a sign is).
+ */
+int biqo_quantize_greedy(const float* W, long m, long n, int q, int8_t* B, double* alpha, double* R) {
+    if (!W || !B || !alpha || m < 1 || n < 1 || q < 1) return BIQO_EINVAL;
+    double* r = (double*)malloc((size_t)n * sizeof(double));
+    if (!r) return BIQO_ENOMEM;
+    for (long row = 0; row < m; ++row) {
+        for (long j = 0; j < n; ++j) r[j] = (double)W[row * n + j];
+        for (int i = 0; i < q; ++i) {
+            double sum_abs = 0.0;
+            for (long j = 0; j < n; ++j) sum_abs += r[j] < 0.0 ? -r[j] : r[j];
+            const double a = sum_abs / (double)n;
+            alpha[(long)i * m + row] = a;
+            for (long j = 0; j < n; ++j) {
+                const int8_t b = r[j] < 0.0 ? -1 : 1;
+                B[((long)i * m + row) * n + j] = b;
+                if (R) R[((long)i * m + row) * n + j] = r[j];
+                r[j] -= a * (double)b;
+            }
+        }
+    }
+    free(r);
+    return BIQO_OK;
+}
