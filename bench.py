@@ -289,6 +289,29 @@ def main() -> int:
                                                                    s["achieved_GBps"], s["effective_GOPS"]))
                 del p
                 torch.cuda.empty_cache()
+        # quantiser front end (Eq. 1, greedy): fp32 W -> packed signs + scales, HBM bound
+        quant = []
+        for (m, n, q) in [(4096, 4096, 3), (16384, 4096, 2)]:
+            Wd = torch.randn((m, n), device="cuda")
+            Kq = torch.empty(biq.biq_packed_bytes(m, n, q), dtype=torch.uint8, device="cuda")
+            aq = torch.empty((q, m), device="cuda")
+            for _ in range(3):
+                biq.biq_quantize(Wd, Kq, aq, m, n, q)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            reps = 20
+            for _ in range(reps):
+                biq.biq_quantize(Wd, Kq, aq, m, n, q)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / reps
+            nbytes = 4 * m * n + q * m * n // 8 + 4 * q * m
+            quant.append({"m": m, "n": n, "q": q, "us_per_call": dt * 1e6, "algorithmic_bytes": nbytes,
+                          "achieved_GBps": nbytes / dt / 1e9, "hbm_frac": nbytes / dt / 1e9 / HBM_PEAK_GBPS})
+            log("quantize %dx%d q=%d: %.1f us, %.0f GB/s (%.1f%% of HBM peak)" %
+                (m, n, q, dt * 1e6, nbytes / dt / 1e9, 100 * nbytes / dt / 1e9 / HBM_PEAK_GBPS))
+            del Wd, Kq, aq
+            torch.cuda.empty_cache()
+        out["quantize"] = quant
         # the batch-1 family: m scaled by powers of two, to show the launch-latency knee
         fam = []
         for k in range(0, 10):

@@ -145,6 +145,18 @@ const char* biq_kernel_name(int kernel);
 biq_status biq_pack(const int8_t* B, uint8_t* K, int m, int n, int q, int mu, void* stream);
 
 /*
+ * Binary-coding quantisation of a weight matrix (Sec. II-B, Eq. 1), row by row:
+ * W[r] ~ sum_i alpha[i][r] * B_i[r], B_i in {-1,+1}.  The paper names the heuristic only
+ * ("greedy approximation"); implemented is the greedy residual method that Eq. 1 implies: with
+ * r = W[r] at the start, for i = 1..q: B_i = sign(r) (sign(0) = +1), alpha_i = mean|r|,
+ * r <- r - alpha_i B_i; every step is the exact minimiser of Eq. 1 for q = 1 on the residual.
+ * W device float [m][n] (row-major) -> K device uint8 [q][m][stride] (packed signs, padding 0)
+ * and alpha device float [q][m], ready for biq_gemm.  fp32 arithmetic, sums in a fixed order
+ * (deterministic).  n <= 32768 (BIQ_EUNSUPPORTED beyond); m * q < 2^31.
+ */
+biq_status biq_quantize(const float* W, uint8_t* K, float* alpha, int m, int n, int q, void* stream);
+
+/*
  * The table indices exactly as the query kernels extract them from K:
  * keys device uint8 [q][m][C], keys[i][r][c] = bit field [mu*c, mu*c+mu) of
  * packed row (i, r).  For checking indices bit for bit against a reference.

@@ -17,7 +17,7 @@ EXPORTS = [
     "biq_status_str", "biq_version", "biq_key_row_stride", "biq_packed_bytes", "biq_num_chunks",
     "biq_lut_bytes", "biq_workspace_bytes", "biq_plan_get", "biq_plan_get_lut", "biq_plan_check", "biq_plan_workspace_bytes",
     "biq_kernel_name", "biq_pack", "biq_unpack_keys", "biq_build_lut", "biq_query", "biq_gemm",
-    "biq_gemm_ex",
+    "biq_gemm_ex", "biq_quantize",
 ]
 
 
@@ -76,6 +76,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "biq_query": (I, [P, P, P, P, I, I, I, I, I, P, Z, P]),
         "biq_gemm": (I, [P, P, P, P, I, I, I, I, I, P, Z, P]),
         "biq_gemm_ex": (I, [P, P, P, P, I, I, I, I, I, PL, P, Z, P]),
+        "biq_quantize": (I, [P, P, P, I, I, I, P]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -161,6 +162,11 @@ def biq_kernel_name(kernel: int) -> str:
 
 def biq_pack(B, K, m: int, n: int, q: int, mu: int, stream=None) -> None:
     _check(load_library().biq_pack(_ptr(B), _ptr(K), m, n, q, mu, _stream(stream)), "biq_pack")
+
+
+def biq_quantize(W, K, alpha, m: int, n: int, q: int, stream=None) -> None:
+    _check(load_library().biq_quantize(_ptr(W), _ptr(K), _ptr(alpha), m, n, q, _stream(stream)),
+           "biq_quantize")
 
 
 def biq_unpack_keys(K, keys, m: int, n: int, q: int, mu: int, stream=None) -> None:

@@ -18,6 +18,7 @@ HEADERS = [
     os.path.join(CSRC, "biq_gemv8h.h"),
     os.path.join(CSRC, "biq_gemm8x2h.h"),
     os.path.join(CSRC, "biq_unpack_mfma.h"),
+    os.path.join(CSRC, "biq_quantize.h"),
     os.path.join(ROOT, "include", "biq.h"),
 ]
 
