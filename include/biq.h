@@ -93,7 +93,11 @@ size_t biq_workspace_bytes(int m, int n, int q, int batch, int mu);
  * accepts a caller-supplied one (for tuning sweeps).
  */
 typedef struct {
-    int kernel;          /* kernel family id (see biq_kernel_name)                        */
+    int kernel;          /* kernel family (biq_kernel_name): 0 query_generic (any mu, q),
+                            1 gemv8 (mu 8, batch 1, q <= 4), 2 gemm8x2 (mu 8, q <= 4, two input
+                            vectors per pass), 3 unpack_mfma (any mu, q <= 4, matrix cores),
+                            4 gemv8_half / 5 gemm8x2_half (as 1 / 2 with half tables: 256 /
+                            128 chunks per tile, row_mode 1 and tiles_per_split 1 only)     */
     int threads;         /* threads per workgroup                                         */
     int chunks_per_tile; /* chunks whose tables one workgroup holds in LDS at a time
                             (unpack_mfma kernel: 32, the key bytes of a row per key group;
