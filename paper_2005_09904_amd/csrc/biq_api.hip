@@ -493,17 +493,21 @@ hipError_t launch_gemm8x2(int q, const QueryParams& qp, int grid, int threads, i
 
 template <int Q, int RPW, int CT, int WS>
 hipError_t launch_unpack_inst(const UnpackParams& up, int grid, int lds, hipStream_t s) {
-    auto kern = unpack_mfma_kernel<Q, RPW, CT, WS>;
-    if (lds != UnpackGeom<CT, WS>::LDS_BYTES) return hipErrorInvalidValue;
-    static bool granted = false;
-    if (!granted) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
-        if (e != hipSuccess) return e;
-        granted = true;
+    if constexpr (WS == 4 && Q * RPW * CT == 8) {
+        return hipErrorInvalidValue;  // not built (register file, LDS): plan_finish_unpack rejects it
+    } else {
+        auto kern = unpack_mfma_kernel<Q, RPW, CT, WS>;
+        if (lds != UnpackGeom<CT, WS>::LDS_BYTES) return hipErrorInvalidValue;
+        static bool granted = false;
+        if (!granted) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+            if (e != hipSuccess) return e;
+            granted = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kUnpackThreads), lds, s, up);
+        return hipGetLastError();
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kUnpackThreads), lds, s, up);
-    return hipGetLastError();
 }
 
 template <int CT, int WS>

@@ -338,46 +338,68 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     }
 
     // ---- epilogue: scale by -alpha (the weights were unpacked with the opposite sign), add the
-    // planes (Eq. 2), store ------------------------------------------------------------------------
+    // planes (Eq. 2), store.  An accumulator tile has one input vector per lane and its 32 rows
+    // spread over 4 registers x 2 half-waves; stored like that, every 128-byte line of Y[b][m]
+    // would be written by 8 separate instructions.  Each tile therefore goes through a 32 x 36
+    // float patch of LDS (private to the wave) and leaves as 128 contiguous bytes per 8 lanes.
+    constexpr int TP = 36;                                      // patch pitch in floats (16-byte aligned rows)
+    constexpr int RED_FLOATS = (WS - 1) * WROWS * RT * CT * 1024;  // partial sums above, still being read
+    static_assert((RED_FLOATS + WROWS * 32 * TP) * 4 <= G::LDS_BYTES, "transpose patches must fit");
+    float* const patch = reinterpret_cast<float*>(stage_buf) + RED_FLOATS + wrow * (32 * TP);
     const bool vec_ok = ((p.m & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.out) & 15) == 0) &&
                         ((reinterpret_cast<uintptr_t>(p.alpha) & 15) == 0);
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) {
+        const int row0 = rbase + rp * 32;                       // first row of this tile
+        float al[4][Q][4];                                      // -alpha of the lane's 16 rows
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
-            const int row = rbase + rp * 32 + 8 * vq + 4 * h;
-            if (row >= p.m) continue;
-            float al[Q][4];
+            const int row = row0 + 8 * vq + 4 * h;
 #pragma unroll
             for (int i = 0; i < Q; ++i) {
-                if (vec_ok) {
+                if (vec_ok && row < p.m) {
                     const float4 a = *reinterpret_cast<const float4*>(p.alpha + (size_t)i * p.m + row);
-                    al[i][0] = -a.x; al[i][1] = -a.y; al[i][2] = -a.z; al[i][3] = -a.w;
+                    al[vq][i][0] = -a.x; al[vq][i][1] = -a.y; al[vq][i][2] = -a.z; al[vq][i][3] = -a.w;
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        al[i][e] = row + e < p.m ? -p.alpha[(size_t)i * p.m + row + e] : 0.0f;
+                        al[vq][i][e] = row + e < p.m ? -p.alpha[(size_t)i * p.m + row + e] : 0.0f;
                 }
             }
+        }
 #pragma unroll
-            for (int c = 0; c < CT; ++c) {
-                const int col = (cg * CT + c) * 32 + lr;
-                if (col >= p.batch) continue;
+        for (int c = 0; c < CT; ++c) {
+            // tile -> patch[column lr][row]
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
                 float y[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float v = 0.0f;
 #pragma unroll
-                    for (int i = 0; i < Q; ++i) v = fmaf(al[i][e], acc[i * RPW + rp][c][4 * vq + e], v);
+                    for (int i = 0; i < Q; ++i) v = fmaf(al[vq][i][e], acc[i * RPW + rp][c][4 * vq + e], v);
                     y[e] = v;
                 }
-                float* dst = p.out + ((size_t)sp * p.batch + col) * p.m + row;
-                if (vec_ok) {
-                    *reinterpret_cast<float4*>(dst) = make_float4(y[0], y[1], y[2], y[3]);
-                } else {
+                *reinterpret_cast<float4*>(patch + lr * TP + 8 * vq + 4 * h) = make_float4(y[0], y[1], y[2], y[3]);
+            }
+            // patch -> Y: lane = 8 * (column in group of 8) + (4 rows), 4 column groups
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (row + e < p.m) dst[e] = y[e];
+            for (int i = 0; i < 4; ++i) {
+                const int pc = 8 * i + (lane >> 3);
+                const int pr = 4 * (lane & 7);
+                const float4 v = *reinterpret_cast<const float4*>(patch + pc * TP + pr);
+                const int col = (cg * CT + c) * 32 + pc;
+                const int row = row0 + pr;
+                if (col < p.batch && row < p.m) {
+                    float* dst = p.out + ((size_t)sp * p.batch + col) * p.m + row;
+                    if (vec_ok) {
+                        *reinterpret_cast<float4*>(dst) = v;
+                    } else {
+                        dst[0] = v.x;
+                        if (row + 1 < p.m) dst[1] = v.y;
+                        if (row + 2 < p.m) dst[2] = v.z;
+                        if (row + 3 < p.m) dst[3] = v.w;
+                    }
                 }
             }
         }
