@@ -334,6 +334,12 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
     long long k = (row_iters * splits * batch_tiles) / want_wgs;
     if (k < 1) k = 1;
     if (k > 64) k = 64;
+    if (pl.tiles_per_split > 1) {
+        // row accumulators share the LDS with the tables
+        const long long table_bytes = (long long)pl.chunks_per_tile * E * pl.batch_tile * 4;
+        const long long fit = (kLdsPerCu - table_bytes) / (4ll * pl.batch_tile * groups);
+        if (k > fit) k = fit < 1 ? 1 : fit;
+    }
     pl.rows_per_wg = (int)(k * groups);
     plan_finish(pl, m, n, q, batch, mu);
 }
@@ -597,6 +603,8 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
         if (!plan_finish(pl, m, n, q, batch, mu)) return BIQ_EINVAL;
     } else {
         plan_default(pl, m, n, q, batch, mu, !fused);
+        biq_plan checked = pl;
+        if (!plan_finish(checked, m, n, q, batch, mu)) return BIQ_EUNSUPPORTED;  // planner defect: never launch it
     }
     if (pl.kernel == KERNEL_UNPACK_MFMA && !fused) return BIQ_EINVAL;  // that kernel reads X, not tables
     const size_t need = plan_workspace(pl, m, batch);

@@ -158,3 +158,30 @@ def test_product_path_does_not_import_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text, f
                 assert "biq_oracle" not in text, f
+
+
+def test_default_plans_pass_their_own_check_on_random_shapes(biq):
+    """Whatever the planner returns is a plan biq_plan_check accepts unchanged, for both planners,
+    over a few thousand random shapes including tiny, huge, skinny and ragged ones."""
+    import numpy as np
+
+    rng = np.random.default_rng(2005)
+    fields = ("kernel", "threads", "chunks_per_tile", "batch_tile", "chunk_splits", "tiles_per_split",
+              "rows_per_wg", "row_blocks", "batch_tiles", "lds_bytes", "row_mode", "xcd_skew", "wave_splits")
+    for _ in range(3000):
+        m = int(rng.choice([1, 2, 7, 64, 100, 511, 2048, 4097, 16384, 100000, 1 << 20]))
+        n = int(rng.choice([1, 5, 64, 127, 128, 1000, 1024, 2048, 2050, 4096, 16384, 32768, 100000]))
+        q = int(rng.integers(1, 7))
+        b = int(rng.choice([1, 2, 3, 8, 17, 32, 33, 64, 100, 128, 500]))
+        mu = int(rng.integers(1, 9))
+        if m * q >= 1 << 31:
+            continue
+        for get in (biq.biq_plan_get, biq.biq_plan_get_lut):
+            p = get(m, n, q, b, mu)
+            before = {k: getattr(p, k) for k in fields}
+            biq.biq_plan_check(m, n, q, b, mu, p)          # raises if the plan is rejected
+            after = {k: getattr(p, k) for k in fields}
+            assert before == after, (m, n, q, b, mu, before, after)
+            assert p.row_blocks * p.rows_per_wg >= m and p.batch_tiles * p.batch_tile >= b
+            assert 0 < p.lds_bytes <= 160 * 1024
+            assert biq.biq_workspace_bytes(m, n, q, b, mu) >= biq.biq_plan_workspace_bytes(p, m, b)

@@ -474,3 +474,22 @@ def test_hip_graph_replay_matches_eager(biq, oracle):
             torch.cuda.synchronize()
             for y, e in zip(outs, eager):
                 assert torch.equal(y, e), "replay %d differs from the eager result" % rep
+
+
+def test_generic_kernel_with_full_lds(biq, oracle):
+    """Generic kernel, several tiles per workgroup: tables (128 KiB) plus row accumulators fill
+    the 160 KiB of LDS exactly at 1024 rows x 8 input vectors; one row more is refused."""
+    m, n, q, b, mu = 2100, 1600, 2, 9, 6
+    B, alpha, X = _rand_inputs(m, n, q, b, 7100)
+    Bd, ad, Xd = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, Bd, mu)
+    plan = biq.biq_plan_check(m, n, q, b, mu, _plan(biq, 0, 256, 64, 8, 2, 1024))
+    assert plan.lds_bytes == 160 * 1024 and plan.tiles_per_split == 2
+    _say("generic kernel, LDS full")
+    Y = gpu_gemm(biq, K, ad, Xd, m, n, q, mu, plan=plan).cpu().numpy()
+    assert_within_tolerance(Y, oracle.gemm_dense(B, alpha, X), alpha, X, "generic full LDS")
+    with pytest.raises(biq.BiqError):
+        biq.biq_plan_check(m, n, q, b, mu, _plan(biq, 0, 256, 64, 8, 2, 1025))
+    # a large-batch shape the planner sends to the generic kernel with two tiles per workgroup
+    p = biq.biq_plan_get(8192, 2048, 5, 256, 6)
+    assert biq.biq_kernel_name(p.kernel) == "query_generic" and p.lds_bytes <= 160 * 1024
