@@ -493,3 +493,38 @@ def test_generic_kernel_with_full_lds(biq, oracle):
     # a large-batch shape the planner sends to the generic kernel with two tiles per workgroup
     p = biq.biq_plan_get(8192, 2048, 5, 256, 6)
     assert biq.biq_kernel_name(p.kernel) == "query_generic" and p.lds_bytes <= 160 * 1024
+
+
+def test_random_shapes_default_plans(biq, oracle):
+    """Seeded random shapes through biq_gemm with the planner's own choice: every kernel family
+    meets ragged m, n, batch (including the half-table and matrix-core kernels)."""
+    rng = np.random.default_rng(777)
+    seen = set()
+    for case in range(70):
+        mu = int(rng.integers(1, 9))
+        q = int(rng.integers(1, 6))
+        b = int(rng.choice([1, 1, 2, 3, 5, 8, 33, 70, 130]))
+        n = int(rng.choice([int(rng.integers(1, 300)), int(rng.integers(300, 2200)), int(rng.integers(2200, 9000))]))
+        m = int(rng.integers(1, 700))
+        while m * n * q * b > 60_000_000:
+            m = max(1, m // 2)
+        if case % 7 == 0:                      # make sure the wide small GEMV / batched cases occur
+            mu, b, n = 8, int(rng.choice([1, 4])), int(rng.integers(1030, 2048))
+        if case % 10 == 3:                     # ... and the matrix-core path
+            m, n, q, b = int(rng.integers(2000, 3000)), int(rng.integers(1500, 2500)), 2, 130
+        kname = biq.biq_kernel_name(biq.biq_plan_get(m, n, q, b, mu).kernel)
+        seen.add(kname)
+        _say("random case %d: m=%d n=%d q=%d b=%d mu=%d -> %s" % (case, m, n, q, b, mu, kname))
+        B, alpha, X = _rand_inputs(m, n, q, b, 9900 + case)
+        Bd, ad, Xd = device_inputs(B, alpha, X)
+        K = gpu_pack(biq, Bd, mu)
+        Y = gpu_gemm(biq, K, ad, Xd, m, n, q, mu).cpu().numpy()
+        rows = None
+        if m * n * q * b > 60_000_000:
+            rows = np.unique(rng.integers(0, m, size=64)).astype(np.int64)
+        ref = oracle.gemm_dense(B, alpha, X, rows=rows)
+        if rows is None:
+            assert_within_tolerance(Y, ref, alpha, X, "random case %d" % case)
+        else:
+            assert_within_tolerance(Y[:, rows], ref, alpha[:, rows], X, "random case %d" % case)
+    assert {"query_generic", "gemv8", "gemv8_half", "gemm8x2", "gemm8x2_half", "unpack_mfma"} <= seen, seen
