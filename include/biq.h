@@ -97,7 +97,9 @@ typedef struct {
                             1 gemv8 (mu 8, batch 1, q <= 4), 2 gemm8x2 (mu 8, q <= 4, two input
                             vectors per pass), 3 unpack_mfma (any mu, q <= 4, matrix cores),
                             4 gemv8_half / 5 gemm8x2_half (as 1 / 2 with half tables: 256 /
-                            128 chunks per tile, row_mode 1 and tiles_per_split 1 only)     */
+                            128 chunks per tile, row_mode 1 and tiles_per_split 1 only),
+                            6 query_wide (mu <= 6, any q: 32 key units per tile, batch_tile 4 / 2 /
+                            1 for mu <= 3 / 4 / 5-6, tiles_per_split 1)                      */
     int threads;         /* threads per workgroup                                         */
     int chunks_per_tile; /* chunks whose tables one workgroup holds in LDS at a time
                             (unpack_mfma kernel: 32, the key bytes of a row per key group;

@@ -17,6 +17,7 @@ HEADERS = [
     os.path.join(CSRC, "biq_gemm8x2.h"),
     os.path.join(CSRC, "biq_gemv8h.h"),
     os.path.join(CSRC, "biq_gemm8x2h.h"),
+    os.path.join(CSRC, "biq_query_wide.h"),
     os.path.join(CSRC, "biq_unpack_mfma.h"),
     os.path.join(CSRC, "biq_quantize.h"),
     os.path.join(ROOT, "include", "biq.h"),

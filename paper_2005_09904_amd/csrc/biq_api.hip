@@ -8,6 +8,7 @@
 #include "biq_gemm8x2.h"
 #include "biq_gemv8h.h"
 #include "biq_gemm8x2h.h"
+#include "biq_query_wide.h"
 #include "biq_unpack_mfma.h"
 #include "biq_quantize.h"
 
@@ -21,7 +22,7 @@ constexpr int kLdsTableBudget = 128 * 1024;  // tables of one tile (leaves room 
 constexpr int kNumCu = 256;
 constexpr int kNumXcd = 8;
 
-enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL_UNPACK_MFMA = 3, KERNEL_GEMV8H = 4, KERNEL_GEMM8X2H = 5, KERNEL_COUNT };
+enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL_UNPACK_MFMA = 3, KERNEL_GEMV8H = 4, KERNEL_GEMM8X2H = 5, KERNEL_WIDE = 6, KERNEL_COUNT };
 
 inline bool shape_ok(int m, int n, int q, int batch, int mu) {
     if (m < 1 || n < 1 || q < 1 || batch < 1) return false;
@@ -80,6 +81,7 @@ inline int plan_lds_bytes(const biq_plan& pl, int mu) {
                (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + pl.xcd_skew + 63) / 64) * 64 * 4 : 0);
     if (pl.kernel == KERNEL_GEMV8H) return kGemvHalfTileBytes;
     if (pl.kernel == KERNEL_GEMM8X2H) return kGemmHalfTileBytes;
+    if (pl.kernel == KERNEL_WIDE) return 128 * 1024;
     if (pl.kernel == KERNEL_GEMM8X2)
         return kGemmTileBytes + (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + 63) / 64) * 64 * 8 : 0);
     long long b = (long long)pl.chunks_per_tile * (1 << mu) * pl.batch_tile * 4;
@@ -108,6 +110,12 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
         if (mu != 8 || batch != 1 || q > 4) return false;
         if (pl.chunks_per_tile != kGemvHalfTileChunks || pl.batch_tile != 1) return false;
         if (pl.row_mode != 1 || pl.tiles_per_split != 1) return false;
+    }
+    if (pl.kernel == KERNEL_WIDE) {
+        // mu <= 6; one tile of 32 key units per workgroup, batch tile fixed by mu (tables fill 128 KiB)
+        if (mu > 6 || pl.chunks_per_tile != 32 * UK) return false;
+        if (pl.batch_tile != (128 * 1024) / (32 * UK * (1 << mu) * 4)) return false;
+        if (pl.row_mode != 0 || pl.tiles_per_split != 1) return false;
     }
     if (pl.kernel == KERNEL_GEMM8X2H) {
         // mu = 8, at most 4 planes; one 128-chunk tile of half tables for two input vectors per
@@ -150,15 +158,16 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
 
 // Where the lookup tables stop paying off (the crossover of Sec. IV-B / Fig. 10): estimated
 // run times of both paths from rates measured on MI355X.  Table lookups: about 13e12 lookups/s
-// for the mu = 8 kernels; 6.5e12 for the generic one, which also streams keys at no more than
-// about 0.25 TB/s; plus 6 us of launch and table build.
-// Unpack + MFMA: 2 * 3 flop per weight and padded input vector (three bf16 terms) at 1.3e15
-// flop/s, plus 12 us (input split, launch, combining partial sums).
+// for the conflict-free kernels (mu = 8, mu <= 5, mu = 6 up to 4 input vectors); 6.5e12 for the
+// generic one, which also streams keys at no more than about 0.25 TB/s; plus 6 us of launch
+// and table build.  Unpack + MFMA: 2 * 3 flop per weight and padded input vector (three bf16
+// terms) at 1.3e15 flop/s, plus 12 us (input split, launch, combining partial sums).
 bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
     const double weights = (double)q * m * n;
     const double lookups = weights / mu * batch;
-    double t_lut = lookups / (mu == 8 ? 13e12 : 6.5e12);
-    if (mu != 8 && t_lut < weights / 8 / 0.25e12) t_lut = weights / 8 / 0.25e12;
+    const bool tuned = mu == 8 || mu <= 5 || (mu == 6 && batch <= 4);
+    double t_lut = lookups / (tuned ? 13e12 : 6.5e12);
+    if (!tuned && t_lut < weights / 8 / 0.25e12) t_lut = weights / 8 / 0.25e12;
     t_lut += 6e-6;
     const double padded = (double)((batch + 31) / 32) * 32;
     const double t_mfma = 12e-6 + 6.0 * weights * padded / 1.3e15;
@@ -308,6 +317,25 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
         plan_finish(pl, m, n, q, batch, mu);
         return;
     }
+    if ((mu <= 5 || (mu == 6 && batch <= 4)) && 2 * C >= 32 * UK) {
+        // Narrow keys, rows at least half a tile wide: 32 lanes per row, conflict-free gathers.
+        // (mu = 6 holds one input vector per pass only and re-reads the keys per vector: measured
+        // faster than the generic kernel up to 4 input vectors, slower from 16 on.)
+        // One tile per workgroup (wider rows are split, partial sums through the workspace); two
+        // workgroups per CU, at least 32 rows (one step of the 16 waves) each.
+        pl.kernel = KERNEL_WIDE;
+        pl.threads = 1024;
+        pl.chunks_per_tile = 32 * UK;
+        pl.batch_tile = (128 * 1024) / (32 * UK * E * 4);
+        pl.tiles_per_split = 1;
+        const long long units = (long long)m * ceil_div(C, pl.chunks_per_tile) * ceil_div(batch, pl.batch_tile);
+        long long rows = ceil_div(ceil_div(units, 2 * kNumCu), 32) * 32ll;
+        if (rows < 32) rows = 32;
+        if (rows > (1 << 20)) rows = 1 << 20;
+        pl.rows_per_wg = (int)rows;
+        plan_finish(pl, m, n, q, batch, mu);
+        return;
+    }
     pl.kernel = KERNEL_GENERIC;
     pl.batch_tile = batch >= 5 ? 8 : batch >= 3 ? 4 : batch;
     // widest tile: G units, G a power of two, tables within the budget, no wider than the row
@@ -401,6 +429,33 @@ hipError_t launch_query_mu(int mu, int bt, const QueryParams& qp, int grid, int 
         case 7: return launch_query_bt<7, FUSED>(bt, qp, grid, threads, lds, s);
         default: return launch_query_bt<8, FUSED>(bt, qp, grid, threads, lds, s);
     }
+}
+
+template <int MU, bool FUSED>
+hipError_t launch_wide_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    auto kern = query_wide_kernel<MU, FUSED>;
+    static bool granted = false;
+    if (!granted) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+        if (e != hipSuccess) return e;
+        granted = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
+    return hipGetLastError();
+}
+
+template <bool FUSED>
+hipError_t launch_wide(int mu, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    switch (mu) {
+        case 1: return launch_wide_inst<1, FUSED>(qp, grid, threads, lds, s);
+        case 2: return launch_wide_inst<2, FUSED>(qp, grid, threads, lds, s);
+        case 3: return launch_wide_inst<3, FUSED>(qp, grid, threads, lds, s);
+        case 4: return launch_wide_inst<4, FUSED>(qp, grid, threads, lds, s);
+        case 5: return launch_wide_inst<5, FUSED>(qp, grid, threads, lds, s);
+        case 6: return launch_wide_inst<6, FUSED>(qp, grid, threads, lds, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 template <int Q, bool FUSED>
@@ -649,6 +704,9 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     else if (pl.kernel == KERNEL_GEMV8H)
         e = fused ? launch_gemv8h<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
                   : launch_gemv8h<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
+    else if (pl.kernel == KERNEL_WIDE)
+        e = fused ? launch_wide<true>(mu, qp, grid, pl.threads, pl.lds_bytes, s)
+                  : launch_wide<false>(mu, qp, grid, pl.threads, pl.lds_bytes, s);
     else if (pl.kernel == KERNEL_GEMM8X2H)
         e = fused ? launch_gemm8x2h<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
                   : launch_gemm8x2h<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
@@ -743,6 +801,7 @@ const char* biq_kernel_name(int kernel) {
         case KERNEL_UNPACK_MFMA: return "unpack_mfma";
         case KERNEL_GEMV8H: return "gemv8_half";
         case KERNEL_GEMM8X2H: return "gemm8x2_half";
+        case KERNEL_WIDE: return "query_wide";
     }
     return "unknown";
 }

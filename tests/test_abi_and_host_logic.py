@@ -101,7 +101,7 @@ def test_default_plans_are_consistent(biq, mu):
             lut = biq.biq_plan_get_lut(m, n, q, b, mu)
             assert biq.biq_kernel_name(lut.kernel) == name
         assert biq.biq_kernel_name(biq.biq_plan_get_lut(m, n, q, b, mu).kernel) in (
-            "query_generic", "gemv8", "gemv8_half", "gemm8x2", "gemm8x2_half")
+            "query_generic", "query_wide", "gemv8", "gemv8_half", "gemm8x2", "gemm8x2_half")
         assert p.chunk_splits * p.tiles_per_split >= tiles
         assert (p.chunk_splits - 1) * p.tiles_per_split < tiles
         assert p.row_blocks * p.rows_per_wg >= m > (p.row_blocks - 1) * p.rows_per_wg

@@ -491,7 +491,7 @@ def test_generic_kernel_with_full_lds(biq, oracle):
     with pytest.raises(biq.BiqError):
         biq.biq_plan_check(m, n, q, b, mu, _plan(biq, 0, 256, 64, 8, 2, 1025))
     # a large-batch shape the planner sends to the generic kernel with two tiles per workgroup
-    p = biq.biq_plan_get(8192, 2048, 5, 256, 6)
+    p = biq.biq_plan_get(8192, 2048, 5, 256, 7)
     assert biq.biq_kernel_name(p.kernel) == "query_generic" and p.lds_bytes <= 160 * 1024
 
 
@@ -528,3 +528,31 @@ def test_random_shapes_default_plans(biq, oracle):
         else:
             assert_within_tolerance(Y[:, rows], ref, alpha[:, rows], X, "random case %d" % case)
     assert {"query_generic", "gemv8", "gemv8_half", "gemm8x2", "gemm8x2_half", "unpack_mfma"} <= seen, seen
+
+
+@pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6])
+def test_wide_kernel_plans(biq, oracle, mu):
+    """query_wide (32 lanes per row, conflict-free gathers for mu <= 6) with explicit plans:
+    threads, rows per workgroup, rows narrower and wider than one tile, ragged batch, q = 5."""
+    uk = {1: 128, 2: 64, 3: 32, 4: 32, 5: 32, 6: 16}[mu]
+    bt = (128 * 1024) // (32 * uk * (1 << mu) * 4)
+    for (m, n, q, b) in [(300, 3000, 3, 5), (77, mu * 32 * uk * 2 + 37, 2, 3), (5, 100, 5, 1)]:
+        B, alpha, X = _rand_inputs(m, n, q, b, 7300 + mu + m)
+        Bd, ad, Xd = device_inputs(B, alpha, X)
+        K = gpu_pack(biq, Bd, mu)
+        ref = oracle.gemm_dense(B, alpha, X)
+        for threads, rows in [(1024, 64), (256, 33), (64, 1), (512, 300)]:
+            _say("wide mu=%d m=%d n=%d q=%d b=%d threads=%d rows=%d" % (mu, m, n, q, b, threads, rows))
+            plan = _plan(biq, 6, threads, 32 * uk, bt, 1, rows)
+            Y = gpu_gemm(biq, K, ad, Xd, m, n, q, mu, plan=plan).cpu().numpy()
+            assert_within_tolerance(Y, ref, alpha, X, "wide mu=%d" % mu)
+    # exactly representable inputs: bit for bit
+    from paper_2005_09904_amd.workloads import Workload, make_exact_inputs
+
+    w = Workload("exact", 129, 5000, 2, 3, mu, "uniform", seed=600 + mu)
+    B, alpha, X = make_exact_inputs(w)
+    Bd, ad, Xd = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, Bd, mu)
+    assert biq.biq_kernel_name(biq.biq_plan_get(129, 5000, 2, 3, mu).kernel) == "query_wide"
+    Y = gpu_gemm(biq, K, ad, Xd, 129, 5000, 2, mu).cpu().numpy()
+    assert np.array_equal(Y.astype(np.float64), oracle.gemm_dense(B, alpha, X))
