@@ -262,6 +262,8 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
             int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 64) * 64;
             pl.rows_per_wg = rows > 8192 ? 8192 : rows;
         }
+        // 4 planes in the streaming modes: 512 threads (the 1024-thread kernel spills registers)
+        if (q == 4 && pl.kernel == KERNEL_GEMV8 && pl.row_mode == 0) pl.threads = 512;
         plan_finish(pl, m, n, q, batch, mu);
         return;
     }
@@ -458,9 +460,10 @@ hipError_t launch_wide(int mu, const QueryParams& qp, int grid, int threads, int
     return hipErrorInvalidValue;
 }
 
-template <int Q, bool FUSED>
+template <int Q, bool FUSED, int MAXT>
 hipError_t launch_gemv8_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    auto kern = gemv8_kernel<Q, FUSED>;
+    auto kern = gemv8_kernel<Q, FUSED, MAXT>;
+    if (threads > MAXT) return hipErrorInvalidValue;
     static bool granted = false;
     if (!granted) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -475,10 +478,13 @@ hipError_t launch_gemv8_inst(const QueryParams& qp, int grid, int threads, int l
 template <bool FUSED>
 hipError_t launch_gemv8(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     switch (q) {
-        case 1: return launch_gemv8_inst<1, FUSED>(qp, grid, threads, lds, s);
-        case 2: return launch_gemv8_inst<2, FUSED>(qp, grid, threads, lds, s);
-        case 3: return launch_gemv8_inst<3, FUSED>(qp, grid, threads, lds, s);
-        default: return launch_gemv8_inst<4, FUSED>(qp, grid, threads, lds, s);
+        case 1: return launch_gemv8_inst<1, FUSED, 1024>(qp, grid, threads, lds, s);
+        case 2: return launch_gemv8_inst<2, FUSED, 1024>(qp, grid, threads, lds, s);
+        case 3: return launch_gemv8_inst<3, FUSED, 1024>(qp, grid, threads, lds, s);
+        default:
+            // 4 planes: up to 512 threads run the instantiation with the larger register budget
+            return threads <= 512 ? launch_gemv8_inst<4, FUSED, 512>(qp, grid, threads, lds, s)
+                                  : launch_gemv8_inst<4, FUSED, 1024>(qp, grid, threads, lds, s);
     }
 }
 

@@ -99,8 +99,11 @@ __device__ __forceinline__ void gemv8_copy_tile(const QueryParams& p, char* lds_
     }
 }
 
-template <int Q, bool FUSED>
-__global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
+// MAXT = largest workgroup the instantiation may be launched with: 1024 threads leave 128
+// VGPRs per lane, which 4 planes with their key ring do not fit into (they spill); the 512
+// instantiation has 256.
+template <int Q, bool FUSED, int MAXT = 1024>
+__global__ __launch_bounds__(MAXT) void gemv8_kernel(const QueryParams p) {
     extern __shared__ __align__(16) float lds[];
     char* const lds_bytes = reinterpret_cast<char*>(lds);
     float* const yacc = lds + kGemvTileBytes / 4;  // [rows_per_wg], used when a workgroup walks > 1 tile
@@ -220,7 +223,7 @@ __global__ __launch_bounds__(1024) void gemv8_kernel(const QueryParams p) {
     const int nblk = (nrows + 63) >> 6;
     // ring of PD steps in flight per wave (PD * Q KiB); fewer for many planes to stay inside
     // 128 VGPRs
-    constexpr int PD = (Q <= 2) ? 4 : (Q == 3 ? 2 : 1);
+    constexpr int PD = (Q <= 2 || MAXT <= 512) ? 4 : (Q == 3 ? 2 : 1);
     for (int tile = tile0; tile < tile1; ++tile) {
         const bool have_keys = (uint32_t)(tile * 128 + L * 16) < stride_bytes;
         const char* kbase[Q];
