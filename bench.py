@@ -312,6 +312,28 @@ def main() -> int:
             del Wd, Kq, aq
             torch.cuda.empty_cache()
         out["quantize"] = quant
+        # tables to device memory (biq_build_lut, the unfused a2 step): HBM write bound
+        luts = []
+        for (n, b, mu) in [(4096, 32, 8), (4096, 128, 8), (4096, 128, 4)]:
+            Xd = torch.randn((b, n), device="cuda")
+            nbytes = biq.biq_lut_bytes(n, b, mu)
+            Ld = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda")
+            for _ in range(3):
+                biq.biq_build_lut(Xd, Ld, n, b, mu)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            reps = 50
+            for _ in range(reps):
+                biq.biq_build_lut(Xd, Ld, n, b, mu)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / reps
+            luts.append({"n": n, "batch": b, "mu": mu, "us_per_call": dt * 1e6, "lut_bytes": nbytes,
+                         "achieved_GBps": (nbytes + 4 * n * b) / dt / 1e9,
+                         "hbm_frac": (nbytes + 4 * n * b) / dt / 1e9 / HBM_PEAK_GBPS})
+            log("build_lut n=%d b=%d mu=%d: %.1f us, %.0f GB/s written" % (n, b, mu, dt * 1e6, nbytes / dt / 1e9))
+            del Xd, Ld
+            torch.cuda.empty_cache()
+        out["build_lut"] = luts
         # the batch-1 family: m scaled by powers of two, to show the launch-latency knee
         fam = []
         for k in range(0, 10):

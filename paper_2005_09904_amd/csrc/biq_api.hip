@@ -893,12 +893,18 @@ biq_status biq_build_lut(const float* X, float* LUT, int n, int batch, int mu, v
     if (!aligned(X, 4) || !aligned(LUT, 4)) return BIQ_EINVAL;
     const int C = ceil_div(n, mu);
     const int HG = mu > 4 ? (1 << (mu - 4)) : 1;
-    const long long total = (long long)C * HG * batch;
+    const bool vec4 = (batch % 4 == 0) && aligned(LUT, 16);
+    const long long total = (long long)C * HG * (vec4 ? batch / 4 : batch);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const unsigned grid = (unsigned)((total + 255) / 256);
-#define BIQ_LUT_CASE(MU)                                                                          \
-    case MU:                                                                                      \
-        hipLaunchKernelGGL(build_lut_kernel<MU>, dim3(grid), dim3(256), 0, s, X, LUT, n, batch, C); \
+#define BIQ_LUT_CASE(MU)                                                                           \
+    case MU:                                                                                       \
+        if (vec4)                                                                                  \
+            hipLaunchKernelGGL((build_lut_kernel<MU, 4>), dim3(grid), dim3(256), 0, s, X, LUT, n,  \
+                               batch, C);                                                          \
+        else                                                                                       \
+            hipLaunchKernelGGL((build_lut_kernel<MU, 1>), dim3(grid), dim3(256), 0, s, X, LUT, n,  \
+                               batch, C);                                                          \
         break;
     switch (mu) {
         BIQ_LUT_CASE(1) BIQ_LUT_CASE(2) BIQ_LUT_CASE(3) BIQ_LUT_CASE(4)

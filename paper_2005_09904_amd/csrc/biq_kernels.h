@@ -74,28 +74,41 @@ __global__ __launch_bounds__(256) void unpack_keys_kernel(const uint32_t* __rest
 
 // =====================================================================================
 // biq_build_lut: X [batch][n] -> LUT [C][2^MU][batch] in device memory (Sec. III-B).
-// One thread per (chunk, input vector, group of 16 keys).
+// One thread per (chunk, VEC adjacent input vectors, group of 16 keys); VEC = 4 (16-byte
+// stores) when the batch is a multiple of 4 and LUT is 16-byte aligned, else 1.
 // =====================================================================================
-template <int MU>
+template <int MU, int VEC>
 __global__ __launch_bounds__(256) void build_lut_kernel(const float* __restrict__ X,
                                                         float* __restrict__ LUT, int n, int batch,
                                                         int C) {
     constexpr int E = 1 << MU;
     constexpr int HG = (MU > 4) ? (1 << (MU - 4)) : 1;  // groups of 16 keys per table
     constexpr int LN = (MU > 4) ? 16 : E;               // keys per group
+    const int bv = batch / VEC;                         // VEC divides batch
     const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long long total = (long long)C * HG * batch;
+    const long long total = (long long)C * HG * bv;
     if (gid >= total) return;
-    const int a = (int)(gid % batch);
-    const long long rest = gid / batch;
+    const int a = (int)(gid % bv) * VEC;
+    const long long rest = gid / bv;
     const int h = (int)(rest % HG);
     const int c = (int)(rest / HG);
-    float x[8], ent[16];
-    load_chunk_x<MU>(X, n, batch, a, c, x);
-    table16(x, (uint32_t)h, ent);
+    float ent[VEC][16];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+        float x[8];
+        load_chunk_x<MU>(X, n, batch, a + v, c, x);
+        table16(x, (uint32_t)h, ent[v]);
+    }
     float* dst = LUT + ((size_t)c * E + (size_t)h * 16) * batch + a;
 #pragma unroll
-    for (int l = 0; l < LN; ++l) dst[(size_t)l * batch] = ent[l];
+    for (int l = 0; l < LN; ++l) {
+        if constexpr (VEC == 4) {
+            *reinterpret_cast<float4*>(dst + (size_t)l * batch) =
+                make_float4(ent[0][l], ent[1][l], ent[2][l], ent[3][l]);
+        } else {
+            dst[(size_t)l * batch] = ent[0][l];
+        }
+    }
 }
 
 // =====================================================================================

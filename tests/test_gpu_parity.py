@@ -81,7 +81,7 @@ def test_table_indices_bit_exact(biq, oracle, mu):
 def test_build_lut_parity_and_antisymmetry(biq, oracle, mu):
     import torch
 
-    for (n, b) in [(1, 1), (50, 3), (1024, 1), (333, 8)]:
+    for (n, b) in [(1, 1), (50, 3), (1024, 1), (333, 8), (700, 12), (64, 4), (129, 6)]:
         _say("build_lut mu=%d n=%d b=%d" % (mu, n, b))
         X = np.random.default_rng(3000 + mu + n).standard_normal((b, n), dtype=np.float32)
         C = biq.biq_num_chunks(n, mu)
