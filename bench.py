@@ -312,6 +312,28 @@ def main() -> int:
             del Wd, Kq, aq
             torch.cuda.empty_cache()
         out["quantize"] = quant
+        # key packing (a1): int8 signs -> bit stream, HBM read bound (1 byte in, 1 bit out per weight)
+        packs = []
+        for (m, n, q) in [(4096, 4096, 3), (16384, 4096, 2)]:
+            Bd = (torch.randint(0, 2, (q, m, n), dtype=torch.int8, device="cuda") * 2 - 1)
+            Kp = torch.empty(biq.biq_packed_bytes(m, n, q), dtype=torch.uint8, device="cuda")
+            for _ in range(3):
+                biq.biq_pack(Bd, Kp, m, n, q, 8)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            reps = 20
+            for _ in range(reps):
+                biq.biq_pack(Bd, Kp, m, n, q, 8)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / reps
+            nbytes = q * m * n + q * m * n // 8
+            packs.append({"m": m, "n": n, "q": q, "us_per_call": dt * 1e6, "algorithmic_bytes": nbytes,
+                          "achieved_GBps": nbytes / dt / 1e9, "hbm_frac": nbytes / dt / 1e9 / HBM_PEAK_GBPS})
+            log("pack %dx%d q=%d: %.1f us, %.0f GB/s (%.1f%% of HBM peak)" %
+                (m, n, q, dt * 1e6, nbytes / dt / 1e9, 100 * nbytes / dt / 1e9 / HBM_PEAK_GBPS))
+            del Bd, Kp
+            torch.cuda.empty_cache()
+        out["pack"] = packs
         # tables to device memory (biq_build_lut, the unfused a2 step): HBM write bound
         luts = []
         for (n, b, mu) in [(4096, 32, 8), (4096, 128, 8), (4096, 128, 4)]:
