@@ -154,6 +154,9 @@ def main() -> int:
                          "plain 512 MiB device copy, the calibration kernel for HBM byte counters")
     ap.add_argument("--workload", default=None,
                     help="time only this named configuration (for profiling), e.g. cfg4_sq4096_q3_b32")
+    ap.add_argument("--mu", type=int, default=0, help="with --workload: LUT-unit to use instead of the workload's")
+    ap.add_argument("--plan", choices=["default", "lut"], default="default",
+                    help="with --workload: the library's plan, or its choice among the lookup-table kernels only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -184,13 +187,17 @@ def main() -> int:
 
     if args.workload:
         w = CONFIGS[args.workload]
+        if args.mu:
+            w = w.with_mu(args.mu)
+        plan = biq.biq_plan_get_lut(w.m, w.n, w.q, w.batch, w.mu) if args.plan == "lut" else None
         copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
-        p = Problem(biq, torch, w, copies, real_first=False)
+        p = Problem(biq, torch, w, copies, real_first=False, plan=plan)
         steps = min(args.steps, 200 if w.lookups < 1e9 else 50)
         wall, ev = time_steps(torch, p, steps, 5)
         srow = summarize(w, wall / steps)
         srow["event_us_per_call"] = ev / steps * 1e6
-        srow["plan"] = biq.biq_plan_get(w.m, w.n, w.q, w.batch, w.mu).as_dict()
+        srow["plan"] = (plan or biq.biq_plan_get(w.m, w.n, w.q, w.batch, w.mu)).as_dict()
+        srow["kernel"] = biq.biq_kernel_name(srow["plan"]["kernel"])
         print(json.dumps(srow))
         return 0
 
