@@ -5,8 +5,9 @@
 // of an LDS half-wave all work on the SAME row, lane L on the L-th key unit (a run of whole
 // dwords holding UK whole keys, see biq_common.h), and the table entry of (key position s in the
 // unit, key k, input vector v, unit L) lives at byte
-//       ((s * 2^mu + k) * BT + v) * 128 + L * 4
-// so the bank is L whatever the keys are: every ds_read_b32 of a half-wave is conflict-free
+//       k * (UK/2 * BT * 256) + ((s >> 1) * BT + v) * 256 + (s & 1) * 128 + L * 4
+// (the key in the high bits: everything else of a lookup's address is a per-lane constant plus an
+// immediate offset of the read), so the bank is L whatever the keys are: every ds_read_b32 of a half-wave is conflict-free
 // (the arrangement idea of Fig. 8 with the lane's unit as the interleaving index).  A tile is
 // 32 units = 32*UK chunks and fills 128 KiB with BT = 2 (mu 4), 1 (mu 5, 6) or 4 (mu <= 3)
 // input vectors.  Per key: one bit-field extract, one shift-add for the address, BT reads.
@@ -28,23 +29,23 @@ template <int MU> struct WideGeom {
 
 template <int MU, int BT>
 __device__ __forceinline__ uint32_t wide_slot(int s, int key, int v, int L) {
-    return (uint32_t)((((s << MU) + key) * BT + v) * 128 + L * 4);
+    constexpr int KB = KeyUnit<MU>::UK / 2 * BT * 256;   // bytes per key value
+    return (uint32_t)(key * KB + ((s >> 1) * BT + v) * 256 + (s & 1) * 128 + L * 4);
 }
 
-// Lookups of key positions T .. UK-1 of one unit: acc[v] += table[s][key_s][v][L].
+// Lookups of key positions T .. UK-1 of one unit: acc[v] += table[s][key_s][v][L].  lane_even /
+// lane_odd = L * 4 (+ 128): the per-lane part of the address for even / odd key positions; the
+// rest, ((s >> 1) * BT + v) * 256, is an immediate offset of the read.
 template <int MU, int BT, int T>
-__device__ __forceinline__ void wide_lookup(const uint32_t (&w)[KeyUnit<MU>::UD], uint32_t lane_lo,
-                                            uint32_t lane_hi, float (&acc)[BT]) {
+__device__ __forceinline__ void wide_lookup(const uint32_t (&w)[KeyUnit<MU>::UD], uint32_t lane_even,
+                                            uint32_t lane_odd, float (&acc)[BT]) {
     if constexpr (T < KeyUnit<MU>::UK) {
-        constexpr uint32_t per_s = (uint32_t)((1 << MU) * BT * 128);   // bytes per key position
-        constexpr uint32_t off = (uint32_t)T * per_s;
+        constexpr uint32_t KB = (uint32_t)(KeyUnit<MU>::UK / 2 * BT * 256);
         const uint32_t key = unit_key<MU, T>(w);
-        // entries of positions below 64 KiB are reached with an immediate offset from lane_lo,
-        // the others from lane_hi = lane_lo + 65536
-        const uint32_t addr = key * (uint32_t)(BT * 128) + (off < 65536u ? lane_lo : lane_hi);
+        const uint32_t addr = key * KB + ((T & 1) ? lane_odd : lane_even);
 #pragma unroll
-        for (int v = 0; v < BT; ++v) acc[v] += lds_read_abs(addr + (off & 65535u) + v * 128);
-        wide_lookup<MU, BT, T + 1>(w, lane_lo, lane_hi, acc);
+        for (int v = 0; v < BT; ++v) acc[v] += lds_read_abs(addr + (uint32_t)(((T >> 1) * BT + v) * 256));
+        wide_lookup<MU, BT, T + 1>(w, lane_even, lane_odd, acc);
     }
 }
 
@@ -86,9 +87,10 @@ __global__ __launch_bounds__(1024) void query_wide_kernel(const QueryParams p) {
             float x[8], ent[16];
             load_chunk_x<MU>(p.X, p.n, p.batch, b0 + v, c0 + L * UK + s, x);
             table16(x, (uint32_t)h, ent);
+            constexpr int KB = UK / 2 * BT * 256;
             char* dst = lds_bytes + wide_slot<MU, BT>(s, h * 16, v, L);
 #pragma unroll
-            for (int l = 0; l < LN; ++l) *reinterpret_cast<float*>(dst + l * (BT * 128)) = ent[l];
+            for (int l = 0; l < LN; ++l) *reinterpret_cast<float*>(dst + l * KB) = ent[l];
         }
     } else {
         for (int i = tid; i < CT * E * BT; i += nthreads) {
@@ -112,8 +114,8 @@ __global__ __launch_bounds__(1024) void query_wide_kernel(const QueryParams p) {
     const int half = lane >> 5;
     const int wave = tid >> 6;
     const int nwaves = nthreads >> 6;
-    const uint32_t lane_lo = (uint32_t)(L * 4);
-    const uint32_t lane_hi = lane_lo + 65536u;
+    const uint32_t lane_even = (uint32_t)(L * 4);
+    const uint32_t lane_odd = lane_even + 128u;
     const int dw0 = tile * 32 * UD + L * UD;     // this lane's unit inside a packed row
     const int nrows = r1 - r0;
     const int nsteps = (nrows + 1) >> 1;         // steps of 2 rows per wave
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(1024) void query_wide_kernel(const QueryParams p) {
         float acc[BT];
 #pragma unroll
         for (int v = 0; v < BT; ++v) acc[v] = 0.0f;
-        wide_lookup<MU, BT, 0>(w, lane_lo, lane_hi, acc);
+        wide_lookup<MU, BT, 0>(w, lane_even, lane_odd, acc);
 #pragma unroll
         for (int v = 0; v < BT; ++v) y[v] = fmaf(al, acc[v], y[v]);
         if (nplane == 0) {
