@@ -833,34 +833,21 @@ biq_status biq_pack(const int8_t* B, uint8_t* K, int m, int n, int q, int mu, vo
 biq_status biq_quantize(const float* W, uint8_t* K, float* alpha, int m, int n, int q, void* stream) {
     if (!shape_ok(m, n, q, 1, 8) || !W || !K || !alpha) return BIQ_EINVAL;
     if (!aligned(K, 16) || !aligned(W, 4) || !aligned(alpha, 4)) return BIQ_EINVAL;
-    if (n > kQuantMaxN) return BIQ_EUNSUPPORTED;  // the row's residual is kept in LDS
+    if (n > kQuantMaxN) return BIQ_EUNSUPPORTED;  // a row's residual is kept in the registers of one workgroup
     const int stride_dw = (int)(biq_key_row_stride(n) / 4);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     uint32_t* Kd = reinterpret_cast<uint32_t*>(K);
-    if (n <= 8192) {
-        // one wave per row, the row in registers
-        const int rows_per_wg = kQuantThreads / 64;
-        const dim3 grid((m + rows_per_wg - 1) / rows_per_wg), block(kQuantThreads);
-#define BIQ_QUANT_CASE(EPT)                                                                        \
-    hipLaunchKernelGGL(quantize_wave_kernel<EPT>, grid, block, 0, s, W, Kd, alpha, m, n, q, stride_dw)
-        if (n <= 64 * 8) BIQ_QUANT_CASE(8);
-        else if (n <= 64 * 16) BIQ_QUANT_CASE(16);
-        else if (n <= 64 * 32) BIQ_QUANT_CASE(32);
-        else if (n <= 64 * 64) BIQ_QUANT_CASE(64);
-        else BIQ_QUANT_CASE(128);
+#define BIQ_QUANT_CASE(EPT, WPR)                                                                   \
+    hipLaunchKernelGGL((quantize_wave_kernel<EPT, WPR>), dim3((m + (4 / WPR) - 1) / (4 / WPR)),   \
+                       dim3(kQuantThreads), 0, s, W, Kd, alpha, m, n, q, stride_dw)
+    if (n <= 64 * 8) BIQ_QUANT_CASE(8, 1);
+    else if (n <= 64 * 16) BIQ_QUANT_CASE(16, 1);
+    else if (n <= 64 * 32) BIQ_QUANT_CASE(32, 1);
+    else if (n <= 64 * 64) BIQ_QUANT_CASE(64, 1);
+    else if (n <= 64 * 128) BIQ_QUANT_CASE(128, 1);
+    else if (n <= 64 * 64 * 4) BIQ_QUANT_CASE(64, 4);    // four waves per row
+    else BIQ_QUANT_CASE(128, 4);
 #undef BIQ_QUANT_CASE
-        return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
-    }
-    const int lds = (((n + 3) & ~3) + 4) * (int)sizeof(float);
-    static bool granted = false;
-    if (!granted) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(quantize_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu) != hipSuccess)
-            return BIQ_EHIP;
-        granted = true;
-    }
-    hipLaunchKernelGGL(quantize_kernel, dim3(m), dim3(kQuantThreads), lds, s, W, Kd, alpha, m, n, q,
-                       stride_dw);
     return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
 }
 

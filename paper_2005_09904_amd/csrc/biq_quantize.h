@@ -7,11 +7,11 @@
 // written straight in the packed key format (bit j of the row <-> element j, +1 <-> 1), the
 // scales as alpha[q][m]: the outputs feed biq_gemm without a pass over int8 signs.
 //
-// Two kernels.  Rows up to 8192 elements: one wave per row, the residual in registers (element
+// The residual lives in registers.  Rows up to 8192 elements: one wave per row (element
 // j = 64*t + lane, so one ballot per t is two key dwords), no barriers.  Longer rows (up to
-// 32768): one workgroup per row, the residual in LDS.  Sums are taken in a fixed order (per lane
-// over its strided elements, then a butterfly inside the wave, then over the waves), so the
-// result does not depend on timing.
+// 32768): the four waves of a workgroup share a row, one barrier per plane for the sum.  Sums
+// are taken in a fixed order (per lane over its strided elements, then a butterfly inside the
+// wave, then over the waves), so the result does not depend on timing.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -22,75 +22,32 @@ namespace biq {
 constexpr int kQuantThreads = 256;
 constexpr int kQuantMaxN = 32768;
 
-__global__ __launch_bounds__(kQuantThreads) void quantize_kernel(const float* __restrict__ W,
-                                                                 uint32_t* __restrict__ K,
-                                                                 float* __restrict__ alpha, int m, int n,
-                                                                 int q, int stride_dw) {
-    extern __shared__ __align__(16) float qlds[];   // [n] residual, then [4] wave sums
-    float* const wave_sums = qlds + ((n + 3) & ~3);
-    const int row = blockIdx.x;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const float* wrow = W + (size_t)row * n;
-
-    if ((n & 3) == 0 && (reinterpret_cast<uintptr_t>(W) & 15) == 0) {
-        for (int j = tid * 4; j < n; j += kQuantThreads * 4)
-            *reinterpret_cast<float4*>(qlds + j) = *reinterpret_cast<const float4*>(wrow + j);
-    } else {
-        for (int j = tid; j < n; j += kQuantThreads) qlds[j] = wrow[j];
-    }
-    __syncthreads();
-
-    const int stride_bits = stride_dw * 32;
-    for (int i = 0; i < q; ++i) {
-        float s = 0.0f;
-        for (int j = tid; j < n; j += kQuantThreads) s += fabsf(qlds[j]);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-        if (lane == 0) wave_sums[wave] = s;
-        __syncthreads();
-        const float a = (((wave_sums[0] + wave_sums[1]) + wave_sums[2]) + wave_sums[3]) / (float)n;
-        if (tid == 0) alpha[(size_t)i * m + row] = a;
-        uint32_t* krow = K + ((size_t)i * m + row) * stride_dw;
-        // 64 consecutive elements per wave and step: one ballot = two key dwords
-        for (int j0 = wave * 64; j0 < stride_bits; j0 += kQuantThreads) {
-            const int j = j0 + lane;
-            bool plus = false;
-            if (j < n) {
-                const float v = qlds[j];
-                plus = !(v < 0.0f);
-                qlds[j] = v - (plus ? a : -a);
-            }
-            const unsigned long long mask = __ballot(plus);
-            if (lane == 0) {
-                krow[j0 >> 5] = (uint32_t)mask;
-                krow[(j0 >> 5) + 1] = (uint32_t)(mask >> 32);
-            }
-        }
-        __syncthreads();
-    }
-}
-
-// One wave per row, EPT elements per lane (n <= 64 * EPT).
-template <int EPT>
+// WPR waves per row (1: four rows per workgroup; 4: one row per workgroup), EPT elements per
+// lane: n <= 64 * EPT * WPR.  Lane l of wave w (of the row's WPR waves) holds elements
+// j = (t * WPR + w) * 64 + l, t = 0 .. EPT-1: the ballot of step t is the 64-bit word t * WPR + w
+// of the packed row.
+template <int EPT, int WPR>
 __global__ __launch_bounds__(kQuantThreads) void quantize_wave_kernel(const float* __restrict__ W,
                                                                       uint32_t* __restrict__ K,
                                                                       float* __restrict__ alpha, int m,
                                                                       int n, int q, int stride_dw) {
+    __shared__ float wave_sums[2][4];   // WPR = 4: the waves' partial sums, double buffered over the planes
     const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * (kQuantThreads / 64) + (threadIdx.x >> 6);
-    if (row >= m) return;
+    const int wave = threadIdx.x >> 6;
+    const int wsub = wave % WPR;
+    const int row = blockIdx.x * (kQuantThreads / 64 / WPR) + wave / WPR;
+    if (row >= m) return;   // WPR = 4: whole workgroup
     const float* wrow = W + (size_t)row * n;
     // All loads are issued unconditionally (addresses clamped into the row) so that they are in
     // flight together; elements past n are then zeroed and stay zero.
     float r[EPT];
 #pragma unroll
-    for (int t = 0; t < EPT; ++t) r[t] = wrow[min(64 * t + lane, n - 1)];
+    for (int t = 0; t < EPT; ++t) r[t] = wrow[min((t * WPR + wsub) * 64 + lane, n - 1)];
 #pragma unroll
-    for (int t = 0; t < EPT; ++t) r[t] = (64 * t + lane < n) ? r[t] : 0.0f;
-    const int steps = stride_dw / 2;  // 64-bit groups of the packed row (stride is a multiple of 16 bytes)
-    int nvalid = (n - lane + 63) >> 6;  // this lane holds elements of steps 0 .. nvalid - 1
+    for (int t = 0; t < EPT; ++t) r[t] = ((t * WPR + wsub) * 64 + lane < n) ? r[t] : 0.0f;
+    const int words = stride_dw / 2;  // 64-bit words of the packed row (stride is a multiple of 16 bytes)
+    // this lane holds elements of steps 0 .. nvalid - 1
+    int nvalid = max(0, (n - lane - 64 * wsub + 64 * WPR - 1) / (64 * WPR));
     for (int i = 0; i < q; ++i) {
         // (keeps the EPT "step is valid" predicates from being hoisted out of this loop into
         // 2 * EPT scalar registers)
@@ -100,11 +57,16 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_wave_kernel(const floa
         for (int t = 0; t < EPT; ++t) s += fabsf(r[t]);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+        if constexpr (WPR > 1) {
+            if (lane == 0) wave_sums[i & 1][wave] = s;
+            __syncthreads();
+            s = ((wave_sums[i & 1][0] + wave_sums[i & 1][1]) + wave_sums[i & 1][2]) + wave_sums[i & 1][3];
+        }
         const float a = s / (float)n;
-        if (lane == 0) alpha[(size_t)i * m + row] = a;
+        if (lane == 0 && wsub == 0) alpha[(size_t)i * m + row] = a;
         uint32_t* krow = K + ((size_t)i * m + row) * stride_dw;
-        // lane t (and t - 64) keeps the 64 sign bits of step t: the row's keys leave in one or two
-        // coalesced stores instead of one small store per step
+        // lane t (and t - 64) keeps the 64 sign bits of step t: the row's keys leave in a few
+        // wide stores instead of one small store per step
         int keep_lo[(EPT + 63) / 64], keep_hi[(EPT + 63) / 64];
 #pragma unroll
         for (int u = 0; u < (EPT + 63) / 64; ++u) { keep_lo[u] = 0; keep_hi[u] = 0; }
@@ -124,8 +86,9 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_wave_kernel(const floa
 #pragma unroll
         for (int u = 0; u < (EPT + 63) / 64; ++u) {
             const int t = 64 * u + lane;
-            if (t < EPT && t < steps)
-                *reinterpret_cast<uint2*>(krow + 2 * t) = make_uint2((uint32_t)keep_lo[u], (uint32_t)keep_hi[u]);
+            const int word = t * WPR + wsub;
+            if (t < EPT && word < words)
+                *reinterpret_cast<uint2*>(krow + 2 * word) = make_uint2((uint32_t)keep_lo[u], (uint32_t)keep_hi[u]);
         }
     }
 }

@@ -48,7 +48,7 @@ def _signs_from_bitmap(Kh, q, m, n):
 
 
 SHAPES = [(1, 1, 1), (3, 7, 2), (37, 100, 3), (64, 128, 1), (130, 1000, 3), (20, 4100, 4), (257, 2056, 2),
-          (5, 32768, 2), (700, 513, 3), (6, 8192, 2), (6, 8200, 2), (3, 449, 1)]
+          (5, 32768, 2), (700, 513, 3), (6, 8192, 2), (6, 8200, 2), (3, 449, 1), (3, 16384, 2), (2, 20001, 3)]
 
 
 @pytest.mark.parametrize("m,n,q", SHAPES)
