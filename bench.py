@@ -298,7 +298,7 @@ def main() -> int:
                 torch.cuda.empty_cache()
         # quantiser front end (Eq. 1, greedy): fp32 W -> packed signs + scales, HBM bound
         quant = []
-        for (m, n, q) in [(4096, 4096, 3), (16384, 4096, 2)]:
+        for (m, n, q) in [(4096, 4096, 3), (16384, 4096, 2), (4096, 16384, 2)]:
             Wd = torch.randn((m, n), device="cuda")
             Kq = torch.empty(biq.biq_packed_bytes(m, n, q), dtype=torch.uint8, device="cuda")
             aq = torch.empty((q, m), device="cuda")
