@@ -105,6 +105,45 @@ __device__ __forceinline__ void table16(const float (&x)[8], uint32_t h, float (
     for (int l = 0; l < 16; ++l) out[l] = a.a[l & 3] + bh[l >> 2];
 }
 
+// The 32 entries of keys 32*hq + 16*hh + l (hh = 0, 1; l = 0..15) of one chunk, for the fused
+// mu = 8 kernels: the same association as table16 (so the results are the same bits), with the
+// chunk's pair sums shared by both groups of 16.
+__device__ __forceinline__ void table32(const float (&x)[8], uint32_t hq, float (&out)[32]) {
+    const PairSums a = pair_sums(x[0], x[1]);
+    const PairSums b = pair_sums(x[2], x[3]);
+    const PairSums c = pair_sums(x[4], x[5]);
+    const PairSums d = pair_sums(x[6], x[7]);
+    // h = 2*hq + hh: hi(h) = C[h & 3] + D[h >> 2], and h >> 2 = hq >> 1 for both hh
+    const float dd = pair_pick(d, hq >> 1);
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        const float hi = pair_pick(c, 2u * (hq & 1u) + (uint32_t)hh) + dd;
+        float bh[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bh[j] = b.a[j] + hi;
+#pragma unroll
+        for (int l = 0; l < 16; ++l) out[hh * 16 + l] = a.a[l & 3] + bh[l >> 2];
+    }
+}
+
+// x[0..8) = X[col][8*c ..] with two 128-bit loads when the row allows it (vec_ok: n % 4 == 0 and X
+// 16-byte aligned), else element by element with zeros past the row or the batch.
+__device__ __forceinline__ void load_chunk8(const float* __restrict__ X, int n, int batch, int col, int c,
+                                            bool vec_ok, float (&x)[8]) {
+    if (vec_ok && col < batch && 8 * c + 8 <= n) {
+        const float4* xv = reinterpret_cast<const float4*>(X + (size_t)col * n);
+        const float4 a0 = xv[2 * c], a1 = xv[2 * c + 1];
+        x[0] = a0.x; x[1] = a0.y; x[2] = a0.z; x[3] = a0.w;
+        x[4] = a1.x; x[5] = a1.y; x[6] = a1.z; x[7] = a1.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int e = 8 * c + j;
+            x[j] = (col < batch && e < n) ? X[(size_t)col * n + e] : 0.0f;
+        }
+    }
+}
+
 // x[j] = X[col][MU*c + j] for j < MU and inside the row, else 0
 template <int MU>
 __device__ __forceinline__ void load_chunk_x(const float* __restrict__ X, int n, int batch, int col,

@@ -26,33 +26,19 @@ __device__ __forceinline__ uint32_t gemm8x2h_slot_offset(int L, int td, int e, i
 }
 
 // Entries 0..127 of the tables of chunks [c0, c0 + 128) for input vectors b0, b0 + 1.
-// One job = (vector, pair of chunks adjacent in L, 16 keys): 2 x 4 x 4 x 4 x 8 = 1024 jobs.
+// One job = (vector, chunk, 32 keys): 2 x 128 x 4 = 1024 jobs; consecutive threads write
+// consecutive banks.
 __device__ __forceinline__ void gemm8x2h_build_tile(const QueryParams& p, char* lds_bytes, int c0,
                                                     int b0, int tid, int nthreads) {
     const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
     for (int job = tid; job < 1024; job += nthreads) {
-        const int Lp = job & 3, e = (job >> 2) & 3, td = (job >> 4) & 3, v = (job >> 6) & 1, h = job >> 7;
-        float xa[8], xb[8], ea[16], eb[16];
-        const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
-        const int cb = ca + 16;
-        const int col = b0 + v;
-        if (vec_ok && col < p.batch && 8 * cb + 8 <= p.n) {
-            const float4* xv = reinterpret_cast<const float4*>(p.X + (size_t)col * p.n);
-            const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], q0 = xv[2 * cb], q1 = xv[2 * cb + 1];
-            xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
-            xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
-            xb[0] = q0.x; xb[1] = q0.y; xb[2] = q0.z; xb[3] = q0.w;
-            xb[4] = q1.x; xb[5] = q1.y; xb[6] = q1.z; xb[7] = q1.w;
-        } else {
-            load_chunk_x<8>(p.X, p.n, p.batch, col, ca, xa);
-            load_chunk_x<8>(p.X, p.n, p.batch, col, cb, xb);
-        }
-        table16(xa, (uint32_t)h, ea);   // keys 16h .. 16h + 15, h < 8: the stored half
-        table16(xb, (uint32_t)h, eb);
-        char* dst = lds_bytes + gemm8x2h_slot_offset(2 * Lp, td, e, v) + (h * 16) * 256;
+        const int L = job & 7, e = (job >> 3) & 3, td = (job >> 5) & 3, v = (job >> 7) & 1, hq = job >> 8;
+        float x[8], ent[32];
+        load_chunk8(p.X, p.n, p.batch, b0 + v, c0 + 16 * L + 4 * td + e, vec_ok, x);
+        table32(x, (uint32_t)hq, ent);   // keys 32*hq .. 32*hq + 31, hq < 4: the stored half
+        char* dst = lds_bytes + gemm8x2h_slot_offset(L, td, e, v) + (hq * 32) * 256;
 #pragma unroll
-        for (int l = 0; l < 16; ++l)
-            *reinterpret_cast<float2*>(dst + l * 256) = make_float2(ea[l], eb[l]);
+        for (int l = 0; l < 32; ++l) *reinterpret_cast<float*>(dst + l * 256) = ent[l];
     }
 }
 

@@ -58,32 +58,19 @@ __device__ __forceinline__ uint32_t lds_address_of(const void* p) {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Tables of chunks [c0, c0 + 128) for one input vector, built from X straight into the LDS
-// layout above.  One job = (pair of chunks adjacent in L, 16 keys): 1024 jobs per tile.
+// layout above.  One job = (chunk, 32 keys): 128 x 8 = 1024 jobs; consecutive threads write
+// consecutive banks.
 __device__ __forceinline__ void gemv8_build_tile(const QueryParams& p, char* lds_bytes, int c0,
                                                  int tid, int nthreads) {
     const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
     for (int job = tid; job < 1024; job += nthreads) {
-        const int Lp = job & 3, e = (job >> 2) & 3, td = (job >> 4) & 3, h = job >> 6;
-        float xa[8], xb[8], ea[16], eb[16];
-        const int ca = c0 + 16 * (2 * Lp) + 4 * td + e;
-        const int cb = ca + 16;
-        if (vec_ok && 8 * cb + 8 <= p.n) {
-            const float4* xv = reinterpret_cast<const float4*>(p.X);
-            const float4 a0 = xv[2 * ca], a1 = xv[2 * ca + 1], b0 = xv[2 * cb], b1 = xv[2 * cb + 1];
-            xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w;
-            xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
-            xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w;
-            xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
-        } else {
-            load_chunk_x<8>(p.X, p.n, 1, 0, ca, xa);
-            load_chunk_x<8>(p.X, p.n, 1, 0, cb, xb);
-        }
-        table16(xa, (uint32_t)h, ea);
-        table16(xb, (uint32_t)h, eb);
-        char* dst = lds_bytes + gemv8_slot_offset(2 * Lp, td, e) + (h * 16) * 256;
+        const int L = job & 7, e = (job >> 3) & 3, td = (job >> 5) & 3, hq = job >> 7;
+        float x[8], ent[32];
+        load_chunk8(p.X, p.n, 1, 0, c0 + 16 * L + 4 * td + e, vec_ok, x);
+        table32(x, (uint32_t)hq, ent);
+        char* dst = lds_bytes + gemv8_slot_offset(L, td, e) + (hq * 32) * 256;
 #pragma unroll
-        for (int l = 0; l < 16; ++l)
-            *reinterpret_cast<float2*>(dst + l * 256) = make_float2(ea[l], eb[l]);
+        for (int l = 0; l < 32; ++l) *reinterpret_cast<float*>(dst + l * 256) = ent[l];
     }
 }
 
