@@ -323,15 +323,16 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
         // Narrow keys, rows at least half a tile wide: 32 lanes per row, conflict-free gathers.
         // (mu = 6 holds one input vector per pass only and re-reads the keys per vector: measured
         // faster than the generic kernel up to 4 input vectors, slower from 16 on.)
-        // One tile per workgroup (wider rows are split, partial sums through the workspace); two
-        // workgroups per CU, at least 32 rows (one step of the 16 waves) each.
+        // One tile per workgroup (wider rows are split, partial sums through the workspace); one
+        // workgroup per CU (the tables fill the LDS: a second round of workgroups would only
+        // build tables again), at least 32 rows (one step of the 16 waves) each.
         pl.kernel = KERNEL_WIDE;
         pl.threads = 1024;
         pl.chunks_per_tile = 32 * UK;
         pl.batch_tile = (128 * 1024) / (32 * UK * E * 4);
         pl.tiles_per_split = 1;
         const long long units = (long long)m * ceil_div(C, pl.chunks_per_tile) * ceil_div(batch, pl.batch_tile);
-        long long rows = ceil_div(ceil_div(units, 2 * kNumCu), 32) * 32ll;
+        long long rows = ceil_div(ceil_div(units, kNumCu), 32) * 32ll;
         if (rows < 32) rows = 32;
         if (rows > (1 << 20)) rows = 1 << 20;
         pl.rows_per_wg = (int)rows;

@@ -84,6 +84,7 @@ __global__ __launch_bounds__(1024) void query_wide_kernel(const QueryParams p) {
             const int s = r % UK; r /= UK;
             const int v = r % BT;
             const int h = r / BT;
+            if (b0 + v >= p.batch) continue;   // no such input vector: its entries are read but never used
             float x[8], ent[16];
             load_chunk_x<MU>(p.X, p.n, p.batch, b0 + v, c0 + L * UK + s, x);
             table16(x, (uint32_t)h, ent);
