@@ -390,20 +390,27 @@ size_t plan_workspace(const biq_plan& pl, int m, int batch) {
            (pl.chunk_splits > 1 ? (size_t)pl.chunk_splits * batch * m * sizeof(float) : 0);
 }
 
+// Opt-in to dynamic LDS above 48 KiB.  The attribute belongs to (function, device): `granted` is
+// the instantiation's bitmap of devices that already have it (devices >= 64 are set every time).
+// Concurrent first calls from several threads at worst set the attribute twice.
+inline hipError_t grant_large_lds(const void* kern, unsigned long long& granted) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && ((granted >> dev) & 1ull)) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+    if (e == hipSuccess && dev >= 0 && dev < 64) granted |= 1ull << dev;
+    return e;
+}
+
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 template <int MU, int BT, bool FUSED>
 hipError_t launch_query_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     auto kern = query_kernel<MU, BT, FUSED>;
     if (lds > 48 * 1024) {
-        // opt in to large dynamic LDS once per instantiation (attribute is per function)
-        static int granted = 0;
-        if (lds > granted) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
-            if (e != hipSuccess) return e;
-            granted = kLdsPerCu;
-        }
+        static unsigned long long granted = 0;
+        if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
     return hipGetLastError();
@@ -437,13 +444,8 @@ hipError_t launch_query_mu(int mu, int bt, const QueryParams& qp, int grid, int 
 template <int MU, bool FUSED>
 hipError_t launch_wide_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     auto kern = query_wide_kernel<MU, FUSED>;
-    static bool granted = false;
-    if (!granted) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
-        if (e != hipSuccess) return e;
-        granted = true;
-    }
+    static unsigned long long granted = 0;
+    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
     return hipGetLastError();
 }
@@ -465,13 +467,8 @@ template <int Q, bool FUSED, int MAXT>
 hipError_t launch_gemv8_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     auto kern = gemv8_kernel<Q, FUSED, MAXT>;
     if (threads > MAXT) return hipErrorInvalidValue;
-    static bool granted = false;
-    if (!granted) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
-        if (e != hipSuccess) return e;
-        granted = true;
-    }
+    static unsigned long long granted = 0;
+    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
     return hipGetLastError();
 }
@@ -492,13 +489,8 @@ hipError_t launch_gemv8(int q, const QueryParams& qp, int grid, int threads, int
 template <int Q, bool FUSED>
 hipError_t launch_gemv8h_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     auto kern = gemv8h_kernel<Q, FUSED>;
-    static bool granted = false;
-    if (!granted) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
-        if (e != hipSuccess) return e;
-        granted = true;
-    }
+    static unsigned long long granted = 0;
+    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
     return hipGetLastError();
 }
@@ -516,13 +508,8 @@ hipError_t launch_gemv8h(int q, const QueryParams& qp, int grid, int threads, in
 template <int Q, bool FUSED>
 hipError_t launch_gemm8x2h_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     auto kern = gemm8x2h_kernel<Q, FUSED>;
-    static bool granted = false;
-    if (!granted) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
-        if (e != hipSuccess) return e;
-        granted = true;
-    }
+    static unsigned long long granted = 0;
+    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
     return hipGetLastError();
 }
@@ -540,13 +527,8 @@ hipError_t launch_gemm8x2h(int q, const QueryParams& qp, int grid, int threads, 
 template <int Q, bool FUSED>
 hipError_t launch_gemm8x2_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     auto kern = gemm8x2_kernel<Q, FUSED>;
-    static bool granted = false;
-    if (!granted) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
-        if (e != hipSuccess) return e;
-        granted = true;
-    }
+    static unsigned long long granted = 0;
+    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
     return hipGetLastError();
 }
@@ -568,13 +550,8 @@ hipError_t launch_unpack_inst(const UnpackParams& up, int grid, int lds, hipStre
     } else {
         auto kern = unpack_mfma_kernel<Q, RPW, CT, WS>;
         if (lds != UnpackGeom<CT, WS>::LDS_BYTES) return hipErrorInvalidValue;
-        static bool granted = false;
-        if (!granted) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
-            if (e != hipSuccess) return e;
-            granted = true;
-        }
+        static unsigned long long granted = 0;
+        if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3(grid), dim3(kUnpackThreads), lds, s, up);
         return hipGetLastError();
     }
