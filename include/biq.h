@@ -114,7 +114,9 @@ typedef struct {
     int row_mode;        /* mu = 8 kernels: 0 = a wave works through blocks of 64 rows
                             (throughput), 1 = one step of rows per wave at a time, keys
                             requested before the tables are built (latency; needs
-                            tiles_per_split = 1)                                           */
+                            tiles_per_split = 1), 2 = gemv8_half only: one row per wave at a
+                            time, its 64 lanes on the row's 64 key dwords (few rows per
+                            workgroup)                                                     */
     int xcd_skew;        /* GEMV kernel, row_mode 0, no chunk split, row_blocks a multiple of 8:
                             workgroups on even XCDs take rows_per_wg + xcd_skew rows, those on
                             odd XCDs rows_per_wg - xcd_skew (odd XCDs stream slower)        */

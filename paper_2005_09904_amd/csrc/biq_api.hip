@@ -109,7 +109,7 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
         // workgroup, latency mode only
         if (mu != 8 || batch != 1 || q > 4) return false;
         if (pl.chunks_per_tile != kGemvHalfTileChunks || pl.batch_tile != 1) return false;
-        if (pl.row_mode != 1 || pl.tiles_per_split != 1) return false;
+        if ((pl.row_mode != 1 && pl.row_mode != 2) || pl.tiles_per_split != 1) return false;
     }
     if (pl.kernel == KERNEL_WIDE) {
         // mu <= 6; one tile of 32 key units per workgroup, batch tile fixed by mu (tables fill 128 KiB)
@@ -137,7 +137,8 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     if (pl.rows_per_wg < 1 || pl.tiles_per_split < 1) return false;
     const int tiles = ceil_div(C, pl.chunks_per_tile);
     if (pl.tiles_per_split > tiles) pl.tiles_per_split = tiles;
-    if (pl.row_mode != 0 && !(pl.row_mode == 1 && pl.kernel != KERNEL_GENERIC && pl.tiles_per_split == 1))
+    if (pl.row_mode != 0 && !(pl.row_mode == 1 && pl.kernel != KERNEL_GENERIC && pl.tiles_per_split == 1) &&
+        !(pl.row_mode == 2 && pl.kernel == KERNEL_GEMV8H))
         return false;
     if (pl.xcd_skew != 0) {
         // only the GEMV kernel's throughput mode, whole grid = 8 equal XCD shares, no chunk split
@@ -251,6 +252,8 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
             const int tiles_h = ceil_div(C, kGemvHalfTileChunks);
             int rows = ceil_div(ceil_div((long long)m * tiles_h, kNumCu), 4) * 4;
             pl.rows_per_wg = rows < 8 ? 8 : rows;
+            // up to one row per wave: 64 lanes per row instead of 16 (4 lookups per lane and plane)
+            if (pl.rows_per_wg <= 16) pl.row_mode = 2;
         } else if ((long long)m * tiles <= 4ll * 128 * kNumCu) {
             // small: latency mode, 8 rows per wave step, at most 4 steps per wave
             pl.tiles_per_split = 1;

@@ -63,8 +63,9 @@ __device__ __forceinline__ void gemv8h_copy_tile(const QueryParams& p, char* lds
     }
 }
 
-// One 256-chunk tile per workgroup, one step of 4 rows per wave at a time; the first step's
-// keys and scales are requested before the tables are built.
+// One 256-chunk tile per workgroup; one step of 4 rows per wave at a time (row_mode 1) or one
+// row per wave at a time (row_mode 2); the first step's keys and scales are requested before the
+// tables are built.
 template <int Q, bool FUSED>
 __global__ __launch_bounds__(1024) void gemv8h_kernel(const QueryParams p) {
     extern __shared__ __align__(16) float lds[];
@@ -124,6 +125,68 @@ __global__ __launch_bounds__(1024) void gemv8h_kernel(const QueryParams p) {
 
     const uint32_t stride_bytes = (uint32_t)p.stride_dw * 4u;
     const int nrows = r1 - r0;
+
+    if (p.row_mode == 2) {
+        // ---- one row per wave at a time: the 64 lanes hold the row's 64 key dwords (4 lookups
+        // per lane and plane instead of 16), for workgroups with so few rows that most waves
+        // would otherwise idle through the lookups.  Lane = 4*L1 + td1 holds dword td1 of the
+        // 16-byte group L1; at static step te it visits byte (te + td1) & 3, which leaves a 2-way
+        // bank conflict per half-wave (8 groups x 2 byte parities = 16 banks for 32 lanes).
+        const int L1 = lane >> 2, td1 = lane & 3;
+        uint32_t sel1[4], base1[4];
+#pragma unroll
+        for (int te = 0; te < 4; ++te) {
+            const int e = (te + td1) & 3;
+            sel1[te] = 0x0c020000u | ((uint32_t)(4 + e) << 8);
+            base1[te] = (uint32_t)((e >> 1) * 128 + (e & 1) * 64 + L1 * 4) | ((uint32_t)(td1 >> 1) << 16);
+        }
+        const uint32_t td_bit15 = (uint32_t)(td1 & 1) << 15;
+        const bool have = (uint32_t)(tile * 256 + lane * 4) < stride_bytes;
+        auto load_row = [&](int row, uint32_t (&kw)[Q], float (&a)[Q]) {
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                kw[i] = 0u;
+                a[i] = 0.0f;
+                if (have && row < nrows) {
+                    const size_t kr = (size_t)i * p.m + r0 + row;
+                    kw[i] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(p.K) +
+                                                               kr * stride_bytes + tile * 256 + lane * 4);
+                    a[i] = p.alpha[kr];
+                }
+            }
+        };
+        uint32_t kw[Q], kwn[Q];
+        float a1[Q], a1n[Q];
+        load_row(wave, kw, a1);
+        if constexpr (FUSED) gemv8h_build_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
+        else gemv8h_copy_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
+        __syncthreads();
+        for (int row = wave; row < nrows; row += nwaves) {
+            load_row(row + nwaves, kwn, a1n);
+            float y = 0.0f;
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int te = 0; te < 4; ++te) {
+                    const uint32_t t = __builtin_amdgcn_perm(kw[i], base1[te], sel1[te]);
+                    const int32_t neg = (int32_t)(t << 16) >> 31;
+                    const uint32_t addr = (t ^ ((uint32_t)neg & 0xff00u)) | td_bit15;
+                    const float v = lds_read_abs(addr);
+                    acc = fmaf(v, __uint_as_float(((uint32_t)neg & 0x80000000u) | 0x3f800000u), acc);
+                }
+                y = fmaf(a1[i], acc, y);
+            }
+            y = reduce16(y);
+            y += __shfl_xor(y, 16, 64);
+            y += __shfl_xor(y, 32, 64);
+            if (lane == 0) p.out[(size_t)sp * p.m + r0 + row] = y;
+#pragma unroll
+            for (int i = 0; i < Q; ++i) { kw[i] = kwn[i]; a1[i] = a1n[i]; }
+        }
+        return;
+    }
+
     const bool have_keys = (uint32_t)(tile * 256 + L * 16) < stride_bytes;
     const int nsteps = (nrows + 3) >> 2;
     auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q]) {

@@ -243,7 +243,10 @@ def test_explicit_plans_give_the_same_result(biq, oracle):
                  (1, 64, 128, 1, 1, 9, 1),
                  # half-table kernel: 256-chunk tiles, 4 rows per wave step
                  (4, 1024, 256, 1, 1, 64, 1), (4, 256, 256, 1, 1, 700, 1), (4, 64, 256, 1, 1, 5, 1),
-                 (4, 512, 256, 1, 1, 130, 1)]:
+                 (4, 512, 256, 1, 1, 130, 1),
+                 # ... one row per wave at a time
+                 (4, 1024, 256, 1, 1, 8, 2), (4, 256, 256, 1, 1, 700, 2), (4, 64, 256, 1, 1, 5, 2),
+                 (4, 1024, 256, 1, 1, 16, 2)]:
         _say("plan " + str(spec))
         Y = gpu_gemm(biq, K, ad, Xd, m, n, 3, mu, plan=_plan(biq, *spec)).cpu().numpy()
         assert_within_tolerance(Y, ref, alpha, X, "plan")
