@@ -167,7 +167,7 @@ def main() -> int:
     import torch
 
     import paper_2005_09904_amd as biq
-    from paper_2005_09904_amd.workloads import CONFIGS
+    from paper_2005_09904_amd.workloads import CONFIGS, Workload
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -296,6 +296,34 @@ def main() -> int:
                                                                    s["achieved_GBps"], s["effective_GOPS"]))
                 del p
                 torch.cuda.empty_cache()
+        # the paper's own GPU grid (Table IV: square matrices, one bit-plane, mu = 8), with the
+        # run times it prints for a V100 beside ours: another machine, context only
+        PAPER_V100_US = {(512, 1): 4, (512, 32): 11, (512, 128): 30, (512, 256): 58,
+                         (1024, 1): 4, (1024, 32): 20, (1024, 128): 70, (1024, 256): 135,
+                         (2048, 1): 5, (2048, 32): 47, (2048, 128): 175, (2048, 256): 330,
+                         (4096, 1): 7, (4096, 32): 130, (4096, 128): 528, (4096, 256): 1005}
+        grid = []
+        for (nn, bb), v100 in PAPER_V100_US.items():
+            w = Workload("table4_%d_b%d" % (nn, bb), nn, nn, 1, bb, 8, "uniform")
+            default = biq.biq_plan_get(nn, nn, 1, bb, 8)
+            lut = biq.biq_plan_get_lut(nn, nn, 1, bb, 8)
+            row = {"n": nn, "batch": bb, "paper_v100_us": v100}
+            for tag, plan in (("us", None), ("lut_us", lut if default.kernel != lut.kernel else None)):
+                if tag == "lut_us" and plan is None:
+                    continue
+                copies = max(2, min(64, (256 * 1024 * 1024) // w.key_bytes + 1))
+                p = Problem(biq, torch, w, copies, real_first=False, plan=plan)
+                steps = 200 if bb <= 32 else 50
+                wall, _ = time_steps(torch, p, steps, 5)
+                row[tag] = wall / steps * 1e6
+                row["kernel" if tag == "us" else "lut_kernel"] = biq.biq_kernel_name((plan or default).kernel)
+                del p
+                torch.cuda.empty_cache()
+            grid.append(row)
+            log("table IV %4d^2 b=%-3d: %7.2f us [%s]%s   (paper, V100: %d us)" %
+                (nn, bb, row["us"], row["kernel"],
+                 "  tables only: %.2f us" % row["lut_us"] if "lut_us" in row else "", v100))
+        out["paper_table4_grid"] = grid
         # quantiser front end (Eq. 1, greedy): fp32 W -> packed signs + scales, HBM bound
         quant = []
         for (m, n, q) in [(4096, 4096, 3), (16384, 4096, 2), (4096, 16384, 2)]:
