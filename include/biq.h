@@ -21,7 +21,7 @@
  *     All work is enqueued on it; calls return without synchronising.
  *   - Output buffers are overwritten, never accumulated into.  Buffers must
  *     not overlap.
- *   - 1 <= mu <= 8, q >= 1, m, n, batch >= 1; m*q and n below 2^31.  Any
+ *   - 1 <= mu <= 10, q >= 1, m, n, batch >= 1; m*q and n below 2^31.  Any
  *     m, n, batch is accepted: there is no "multiple of the tile" requirement.
  *   - Errors are returned as a negative biq_status; nothing aborts or throws
  *     across this boundary.  On an error no kernel has been launched unless
@@ -170,6 +170,9 @@ biq_status biq_quantize(const float* W, uint8_t* K, float* alpha, int m, int n, 
  * packed row (i, r).  For checking indices bit for bit against a reference.
  */
 biq_status biq_unpack_keys(const uint8_t* K, uint8_t* keys, int m, int n, int q, int mu, void* stream);
+/* The same with 16-bit indices, for every mu (biq_unpack_keys returns BIQ_EUNSUPPORTED for mu > 8:
+ * the key does not fit a byte).  keys device uint16 [q][m][C], 2-byte aligned. */
+biq_status biq_unpack_keys16(const uint8_t* K, uint16_t* keys, int m, int n, int q, int mu, void* stream);
 
 /*
  * Table construction (Sec. III-B, q_alpha^beta = M_mu . x_alpha^beta; Algorithm 1):

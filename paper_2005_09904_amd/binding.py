@@ -17,7 +17,7 @@ EXPORTS = [
     "biq_status_str", "biq_version", "biq_key_row_stride", "biq_packed_bytes", "biq_num_chunks",
     "biq_lut_bytes", "biq_workspace_bytes", "biq_plan_get", "biq_plan_get_lut", "biq_plan_check", "biq_plan_workspace_bytes",
     "biq_kernel_name", "biq_pack", "biq_unpack_keys", "biq_build_lut", "biq_query", "biq_gemm",
-    "biq_gemm_ex", "biq_quantize",
+    "biq_gemm_ex", "biq_quantize", "biq_unpack_keys16",
 ]
 
 
@@ -72,6 +72,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "biq_kernel_name": (ctypes.c_char_p, [I]),
         "biq_pack": (I, [P, P, I, I, I, I, P]),
         "biq_unpack_keys": (I, [P, P, I, I, I, I, P]),
+        "biq_unpack_keys16": (I, [P, P, I, I, I, I, P]),
         "biq_build_lut": (I, [P, P, I, I, I, P]),
         "biq_query": (I, [P, P, P, P, I, I, I, I, I, P, Z, P]),
         "biq_gemm": (I, [P, P, P, P, I, I, I, I, I, P, Z, P]),
@@ -162,6 +163,11 @@ def biq_kernel_name(kernel: int) -> str:
 
 def biq_pack(B, K, m: int, n: int, q: int, mu: int, stream=None) -> None:
     _check(load_library().biq_pack(_ptr(B), _ptr(K), m, n, q, mu, _stream(stream)), "biq_pack")
+
+
+def biq_unpack_keys16(K, keys, m: int, n: int, q: int, mu: int, stream=None) -> None:
+    _check(load_library().biq_unpack_keys16(_ptr(K), _ptr(keys), m, n, q, mu, _stream(stream)),
+           "biq_unpack_keys16")
 
 
 def biq_quantize(W, K, alpha, m: int, n: int, q: int, stream=None) -> None:

@@ -26,13 +26,14 @@ enum KernelId { KERNEL_GENERIC = 0, KERNEL_GEMV8 = 1, KERNEL_GEMM8X2 = 2, KERNEL
 
 inline bool shape_ok(int m, int n, int q, int batch, int mu) {
     if (m < 1 || n < 1 || q < 1 || batch < 1) return false;
-    if (mu < 1 || mu > 8) return false;
+    if (mu < 1 || mu > kMaxMu) return false;
     if ((long long)m * q >= (1ll << 31)) return false;
     return true;
 }
 
 inline int unit_keys(int mu) {
     switch (mu) {
+        case 10: return KeyUnit<10>::UK; case 9: return KeyUnit<9>::UK;
         case 8: return KeyUnit<8>::UK; case 7: return KeyUnit<7>::UK; case 6: return KeyUnit<6>::UK;
         case 5: return KeyUnit<5>::UK; case 4: return KeyUnit<4>::UK; case 3: return KeyUnit<3>::UK;
         case 2: return KeyUnit<2>::UK; default: return KeyUnit<1>::UK;
@@ -344,6 +345,8 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
     }
     pl.kernel = KERNEL_GENERIC;
     pl.batch_tile = batch >= 5 ? 8 : batch >= 3 ? 4 : batch;
+    // one key unit's tables must fit the LDS budget (mu = 9, 10: 64 KiB per unit and input vector)
+    while (pl.batch_tile > 1 && (long long)UK * E * pl.batch_tile * 4 > kLdsTableBudget) pl.batch_tile /= 2;
     // widest tile: G units, G a power of two, tables within the budget, no wider than the row
     int G = 1;
     while (G < 64 && (long long)(2 * G) * UK * E * pl.batch_tile * 4 <= kLdsTableBudget &&
@@ -440,7 +443,9 @@ hipError_t launch_query_mu(int mu, int bt, const QueryParams& qp, int grid, int 
         case 5: return launch_query_bt<5, FUSED>(bt, qp, grid, threads, lds, s);
         case 6: return launch_query_bt<6, FUSED>(bt, qp, grid, threads, lds, s);
         case 7: return launch_query_bt<7, FUSED>(bt, qp, grid, threads, lds, s);
-        default: return launch_query_bt<8, FUSED>(bt, qp, grid, threads, lds, s);
+        case 8: return launch_query_bt<8, FUSED>(bt, qp, grid, threads, lds, s);
+        case 9: return launch_query_bt<9, FUSED>(bt, qp, grid, threads, lds, s);
+        default: return launch_query_bt<10, FUSED>(bt, qp, grid, threads, lds, s);
     }
 }
 
@@ -713,6 +718,32 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     return BIQ_OK;
 }
 
+template <typename KEY>
+biq_status unpack_keys_any(const uint8_t* K, KEY* keys, int m, int n, int q, int mu, void* stream) {
+    if (!shape_ok(m, n, q, 1, mu) || !K || !keys) return BIQ_EINVAL;
+    if (!aligned(K, 16) || !aligned(keys, sizeof(KEY))) return BIQ_EINVAL;
+    if (mu > 8 * (int)sizeof(KEY)) return BIQ_EUNSUPPORTED;  // key does not fit the output type
+    const long long key_rows = (long long)q * m;
+    const int stride_dw = (int)(biq_key_row_stride(n) / 4);
+    const int C = ceil_div(n, mu);
+    const int units = ceil_div(C, unit_keys(mu));
+    const long long total = key_rows * units;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    const uint32_t* Kd = reinterpret_cast<const uint32_t*>(K);
+#define BIQ_UNPACK_CASE(MU)                                                                        \
+    case MU:                                                                                       \
+        hipLaunchKernelGGL((unpack_keys_kernel<MU, KEY>), dim3(grid), dim3(256), 0, s, Kd, keys,   \
+                           key_rows, C, stride_dw);                                                \
+        break;
+    switch (mu) {
+        BIQ_UNPACK_CASE(1) BIQ_UNPACK_CASE(2) BIQ_UNPACK_CASE(3) BIQ_UNPACK_CASE(4) BIQ_UNPACK_CASE(5)
+        BIQ_UNPACK_CASE(6) BIQ_UNPACK_CASE(7) BIQ_UNPACK_CASE(8) BIQ_UNPACK_CASE(9) BIQ_UNPACK_CASE(10)
+    }
+#undef BIQ_UNPACK_CASE
+    return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -738,12 +769,12 @@ size_t biq_packed_bytes(int m, int n, int q) {
 }
 
 size_t biq_num_chunks(int n, int mu) {
-    if (n < 1 || mu < 1 || mu > 8) return 0;
+    if (n < 1 || mu < 1 || mu > kMaxMu) return 0;
     return (size_t)((n + mu - 1) / mu);
 }
 
 size_t biq_lut_bytes(int n, int batch, int mu) {
-    if (n < 1 || batch < 1 || mu < 1 || mu > 8) return 0;
+    if (n < 1 || batch < 1 || mu < 1 || mu > kMaxMu) return 0;
     return biq_num_chunks(n, mu) * ((size_t)1 << mu) * batch * sizeof(float);
 }
 
@@ -833,27 +864,11 @@ biq_status biq_quantize(const float* W, uint8_t* K, float* alpha, int m, int n, 
 }
 
 biq_status biq_unpack_keys(const uint8_t* K, uint8_t* keys, int m, int n, int q, int mu, void* stream) {
-    if (!shape_ok(m, n, q, 1, mu) || !K || !keys) return BIQ_EINVAL;
-    if (!aligned(K, 16)) return BIQ_EINVAL;
-    const long long key_rows = (long long)q * m;
-    const int stride_dw = (int)(biq_key_row_stride(n) / 4);
-    const int C = ceil_div(n, mu);
-    const int units = ceil_div(C, unit_keys(mu));
-    const long long total = key_rows * units;
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    const unsigned grid = (unsigned)((total + 255) / 256);
-    const uint32_t* Kd = reinterpret_cast<const uint32_t*>(K);
-#define BIQ_UNPACK_CASE(MU)                                                                       \
-    case MU:                                                                                      \
-        hipLaunchKernelGGL(unpack_keys_kernel<MU>, dim3(grid), dim3(256), 0, s, Kd, keys, key_rows, \
-                           C, stride_dw);                                                         \
-        break;
-    switch (mu) {
-        BIQ_UNPACK_CASE(1) BIQ_UNPACK_CASE(2) BIQ_UNPACK_CASE(3) BIQ_UNPACK_CASE(4)
-        BIQ_UNPACK_CASE(5) BIQ_UNPACK_CASE(6) BIQ_UNPACK_CASE(7) BIQ_UNPACK_CASE(8)
-    }
-#undef BIQ_UNPACK_CASE
-    return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
+    return unpack_keys_any<uint8_t>(K, keys, m, n, q, mu, stream);
+}
+
+biq_status biq_unpack_keys16(const uint8_t* K, uint16_t* keys, int m, int n, int q, int mu, void* stream) {
+    return unpack_keys_any<uint16_t>(K, keys, m, n, q, mu, stream);
 }
 
 biq_status biq_build_lut(const float* X, float* LUT, int n, int batch, int mu, void* stream) {
@@ -875,8 +890,8 @@ biq_status biq_build_lut(const float* X, float* LUT, int n, int batch, int mu, v
                                batch, C);                                                          \
         break;
     switch (mu) {
-        BIQ_LUT_CASE(1) BIQ_LUT_CASE(2) BIQ_LUT_CASE(3) BIQ_LUT_CASE(4)
-        BIQ_LUT_CASE(5) BIQ_LUT_CASE(6) BIQ_LUT_CASE(7) BIQ_LUT_CASE(8)
+        BIQ_LUT_CASE(1) BIQ_LUT_CASE(2) BIQ_LUT_CASE(3) BIQ_LUT_CASE(4) BIQ_LUT_CASE(5)
+        BIQ_LUT_CASE(6) BIQ_LUT_CASE(7) BIQ_LUT_CASE(8) BIQ_LUT_CASE(9) BIQ_LUT_CASE(10)
     }
 #undef BIQ_LUT_CASE
     return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;

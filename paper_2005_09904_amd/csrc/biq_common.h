@@ -24,6 +24,10 @@ template <> struct KeyUnit<6> { static constexpr int UD = 3, UK = 16; };
 template <> struct KeyUnit<3> { static constexpr int UD = 3, UK = 32; };
 template <> struct KeyUnit<5> { static constexpr int UD = 5, UK = 32; };
 template <> struct KeyUnit<7> { static constexpr int UD = 7, UK = 32; };
+// keys wider than a byte (the sizes Eq. 6 favours for large m): 32 keys in 9 dwords, 16 in 5
+template <> struct KeyUnit<9> { static constexpr int UD = 9, UK = 32; };
+template <> struct KeyUnit<10> { static constexpr int UD = 5, UK = 16; };
+constexpr int kMaxMu = 10;
 
 // Key t (compile-time position) of a unit held in w[0..UD).
 template <int MU, int T, int UD>
@@ -148,10 +152,55 @@ __device__ __forceinline__ void load_chunk8(const float* __restrict__ X, int n, 
 template <int MU>
 __device__ __forceinline__ void load_chunk_x(const float* __restrict__ X, int n, int batch, int col,
                                              int c, float (&x)[8]) {
+    static_assert(MU <= 8, "chunks of more than 8 elements use load_chunk_x10");
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int e = MU * c + j;
         x[j] = (j < MU && col < batch && e < n) ? X[(size_t)col * n + e] : 0.0f;
+    }
+}
+
+// The same for chunks of 9 or 10 elements.
+template <int MU>
+__device__ __forceinline__ void load_chunk_x10(const float* __restrict__ X, int n, int batch, int col,
+                                               int c, float (&x)[10]) {
+#pragma unroll
+    for (int j = 0; j < 10; ++j) {
+        const long long e = (long long)MU * c + j;
+        x[j] = (j < MU && col < batch && e < n) ? X[(size_t)col * n + e] : 0.0f;
+    }
+}
+
+// mu = 9, 10: the 16 entries of keys 16*h + l, h = 0 .. 2^(mu-4) - 1.  One more pair sum on top of
+// table16's association: A[l&3] + (B[l>>2] + (C[h&3] + (D[(h>>2)&3] + E[h>>4]))), so entry(~k) =
+// -entry(k) still holds bit for bit.
+__device__ __forceinline__ void table16_wide(const float (&x)[10], uint32_t h, float (&out)[16]) {
+    const PairSums a = pair_sums(x[0], x[1]);
+    const PairSums b = pair_sums(x[2], x[3]);
+    const PairSums c = pair_sums(x[4], x[5]);
+    const PairSums d = pair_sums(x[6], x[7]);
+    const PairSums e = pair_sums(x[8], x[9]);
+    const float hi = pair_pick(c, h & 3u) + (pair_pick(d, (h >> 2) & 3u) + pair_pick(e, h >> 4));
+    float bh[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bh[j] = b.a[j] + hi;
+#pragma unroll
+    for (int l = 0; l < 16; ++l) out[l] = a.a[l & 3] + bh[l >> 2];
+}
+
+// Entries of one chunk for any MU (element 9 of a mu = 9 chunk is 0, so that the unused key bit
+// pairs with a zero; keys with that bit set are never looked up).
+template <int MU>
+__device__ __forceinline__ void chunk_table16(const float* __restrict__ X, int n, int batch, int col, int c,
+                                              uint32_t h, float (&out)[16]) {
+    if constexpr (MU <= 8) {
+        float x[8];
+        load_chunk_x<MU>(X, n, batch, col, c, x);
+        table16(x, h, out);
+    } else {
+        float x[10];
+        load_chunk_x10<MU>(X, n, batch, col, c, x);
+        table16_wide(x, h, out);
     }
 }
 

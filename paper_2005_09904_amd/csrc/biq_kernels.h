@@ -46,20 +46,20 @@ __global__ __launch_bounds__(256) void pack_kernel(const int8_t* __restrict__ B,
 
 // =====================================================================================
 // biq_unpack_keys: the table indices as the query kernels extract them.
-// One thread per (key row, unit); keys uint8 [q*m][C].
+// One thread per (key row, unit); keys uint8 or uint16 [q*m][C].
 // =====================================================================================
-template <int MU, int T>
-__device__ __forceinline__ void store_unit_keys(const uint32_t (&w)[KeyUnit<MU>::UD], uint8_t* dst,
+template <int MU, int T, typename KEY>
+__device__ __forceinline__ void store_unit_keys(const uint32_t (&w)[KeyUnit<MU>::UD], KEY* dst,
                                                 int c0, int C) {
     if constexpr (T < KeyUnit<MU>::UK) {
-        if (c0 + T < C) dst[c0 + T] = (uint8_t)unit_key<MU, T>(w);
-        store_unit_keys<MU, T + 1>(w, dst, c0, C);
+        if (c0 + T < C) dst[c0 + T] = (KEY)unit_key<MU, T>(w);
+        store_unit_keys<MU, T + 1, KEY>(w, dst, c0, C);
     }
 }
 
-template <int MU>
+template <int MU, typename KEY>
 __global__ __launch_bounds__(256) void unpack_keys_kernel(const uint32_t* __restrict__ K,
-                                                          uint8_t* __restrict__ keys,
+                                                          KEY* __restrict__ keys,
                                                           long long key_rows, int C, int stride_dw) {
     constexpr int UD = KeyUnit<MU>::UD, UK = KeyUnit<MU>::UK;
     const int units = (C + UK - 1) / UK;
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void unpack_keys_kernel(const uint32_t* __rest
     const int u = (int)(gid - kr * units);
     uint32_t w[UD];
     load_unit<UD>(K + kr * stride_dw, u * UD, stride_dw, w);
-    store_unit_keys<MU, 0>(w, keys + kr * C, u * UK, C);
+    store_unit_keys<MU, 0, KEY>(w, keys + kr * C, u * UK, C);
 }
 
 // =====================================================================================
@@ -94,11 +94,7 @@ __global__ __launch_bounds__(256) void build_lut_kernel(const float* __restrict_
     const int c = (int)(rest / HG);
     float ent[VEC][16];
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-        float x[8];
-        load_chunk_x<MU>(X, n, batch, a + v, c, x);
-        table16(x, (uint32_t)h, ent[v]);
-    }
+    for (int v = 0; v < VEC; ++v) chunk_table16<MU>(X, n, batch, a + v, c, (uint32_t)h, ent[v]);
     float* dst = LUT + ((size_t)c * E + (size_t)h * 16) * batch + a;
 #pragma unroll
     for (int l = 0; l < LN; ++l) {
@@ -212,9 +208,8 @@ __global__ __launch_bounds__(1024) void query_kernel(const QueryParams p) {
                 const int r2 = job / BT;
                 const int h = r2 % HG;
                 const int ct = r2 / HG;
-                float x[8], ent[16];
-                load_chunk_x<MU>(p.X, p.n, p.batch, b0 + col, c0 + ct, x);
-                table16(x, (uint32_t)h, ent);
+                float ent[16];
+                chunk_table16<MU>(p.X, p.n, p.batch, b0 + col, c0 + ct, (uint32_t)h, ent);
                 float* dst = tables + ((size_t)ct * E + h * 16) * BT + col;
                 if constexpr (BT == 1 && LN >= 4) {
 #pragma unroll

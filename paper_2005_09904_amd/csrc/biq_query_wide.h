@@ -85,9 +85,8 @@ __global__ __launch_bounds__(1024) void query_wide_kernel(const QueryParams p) {
             const int v = r % BT;
             const int h = r / BT;
             if (b0 + v >= p.batch) continue;   // no such input vector: its entries are read but never used
-            float x[8], ent[16];
-            load_chunk_x<MU>(p.X, p.n, p.batch, b0 + v, c0 + L * UK + s, x);
-            table16(x, (uint32_t)h, ent);
+            float ent[16];
+            chunk_table16<MU>(p.X, p.n, p.batch, b0 + v, c0 + L * UK + s, (uint32_t)h, ent);
             constexpr int KB = UK / 2 * BT * 256;
             char* dst = lds_bytes + wide_slot<MU, BT>(s, h * 16, v, L);
 #pragma unroll

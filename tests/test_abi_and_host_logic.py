@@ -61,7 +61,8 @@ def test_size_arithmetic(biq):
     # invalid arguments give 0, not garbage
     assert biq.biq_key_row_stride(0) == 0
     assert biq.biq_packed_bytes(0, 5, 1) == 0
-    assert biq.biq_num_chunks(10, 9) == 0
+    assert biq.biq_num_chunks(10, 9) == 2
+    assert biq.biq_num_chunks(10, 11) == 0
     assert biq.biq_lut_bytes(10, 1, 0) == 0
 
 
@@ -72,7 +73,7 @@ def test_status_strings(biq):
     assert "unknown" in biq.status_str(-99)
 
 
-@pytest.mark.parametrize("mu", range(1, 9))
+@pytest.mark.parametrize("mu", range(1, 11))
 def test_default_plans_are_consistent(biq, mu):
     for (m, n, q, b) in [(1, 1, 1, 1), (512, 512, 1, 1), (2048, 2048, 2, 1), (4096, 1024, 3, 8),
                          (4096, 4096, 3, 32), (16384, 4096, 2, 128), (4096, 16384, 2, 128),
@@ -115,7 +116,7 @@ def test_argument_errors_are_reported_before_any_launch(biq):
     fake = 0x1000  # never dereferenced: every call below fails its argument checks first
     assert lib.biq_pack(None, fake, 4, 4, 1, 8, None) == biq.BIQ_EINVAL
     assert lib.biq_pack(fake, fake, 0, 4, 1, 8, None) == biq.BIQ_EINVAL
-    assert lib.biq_pack(fake, fake, 4, 4, 1, 9, None) == biq.BIQ_EINVAL
+    assert lib.biq_pack(fake, fake, 4, 4, 1, 11, None) == biq.BIQ_EINVAL
     assert lib.biq_pack(fake, fake + 8, 4, 4, 1, 8, None) == biq.BIQ_EINVAL  # K not 16-byte aligned
     assert lib.biq_unpack_keys(None, fake, 4, 4, 1, 8, None) == biq.BIQ_EINVAL
     assert lib.biq_build_lut(fake, None, 4, 1, 8, None) == biq.BIQ_EINVAL
@@ -173,7 +174,7 @@ def test_default_plans_pass_their_own_check_on_random_shapes(biq):
         n = int(rng.choice([1, 5, 64, 127, 128, 1000, 1024, 2048, 2050, 4096, 16384, 32768, 100000]))
         q = int(rng.integers(1, 7))
         b = int(rng.choice([1, 2, 3, 8, 17, 32, 33, 64, 100, 128, 500]))
-        mu = int(rng.integers(1, 9))
+        mu = int(rng.integers(1, 11))
         if m * q >= 1 << 31:
             continue
         for get in (biq.biq_plan_get, biq.biq_plan_get_lut):

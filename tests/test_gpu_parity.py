@@ -62,7 +62,7 @@ def test_pack_bit_exact(biq, oracle, m, n, q, b):
     assert np.array_equal(K.cpu().numpy().reshape(ref.shape), ref)
 
 
-@pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 def test_table_indices_bit_exact(biq, oracle, mu):
     import torch
 
@@ -71,13 +71,23 @@ def test_table_indices_bit_exact(biq, oracle, mu):
         B, _, _ = _rand_inputs(m, n, q, 1, 2000 + mu + n)
         K = gpu_pack(biq, torch.from_numpy(B).cuda(), mu)
         C = biq.biq_num_chunks(n, mu)
-        keys = torch.full((q, m, C), 0xEE, dtype=torch.uint8, device="cuda")
-        biq.biq_unpack_keys(K, keys, m, n, q, mu)
+        ref = oracle.pack_keys(B, mu)
+        keys16 = torch.full((q, m, C), 0x7EEE, dtype=torch.int16, device="cuda")   # uint16 storage
+        biq.biq_unpack_keys16(K, keys16, m, n, q, mu)
         torch.cuda.synchronize()
-        assert np.array_equal(keys.cpu().numpy().astype(np.uint16), oracle.pack_keys(B, mu))
+        assert np.array_equal(keys16.cpu().numpy().view(np.uint16), ref)
+        keys = torch.full((q, m, C), 0xEE, dtype=torch.uint8, device="cuda")
+        if mu <= 8:
+            biq.biq_unpack_keys(K, keys, m, n, q, mu)
+            torch.cuda.synchronize()
+            assert np.array_equal(keys.cpu().numpy().astype(np.uint16), ref)
+        else:   # a key wider than a byte does not fit the 8-bit form
+            with pytest.raises(biq.BiqError) as e:
+                biq.biq_unpack_keys(K, keys, m, n, q, mu)
+            assert e.value.status == biq.BIQ_EUNSUPPORTED
 
 
-@pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 def test_build_lut_parity_and_antisymmetry(biq, oracle, mu):
     import torch
 
@@ -92,11 +102,11 @@ def test_build_lut_parity_and_antisymmetry(biq, oracle, mu):
         torch.cuda.synchronize()
         got = LUT.cpu().numpy()
         ref = oracle.build_lut(X, mu)
-        # fp32 pairwise tree of at most 8 terms: <= 3 roundings of partial sums
+        # fp32 pair sums and a chain over them: at most 4 roundings for mu <= 8, 5 for mu = 9, 10
         Xp = np.zeros((b, C * mu), dtype=np.float64)
         Xp[:, :n] = np.abs(X)
         l1 = Xp.reshape(b, C, mu).sum(axis=2).T  # [C][b]
-        assert np.all(np.abs(got - ref) <= 4 * 2.0 ** -24 * l1[:, None, :] + 1e-45)
+        assert np.all(np.abs(got - ref) <= (5 if mu > 8 else 4) * 2.0 ** -24 * l1[:, None, :] + 1e-45)
         # LUT[~k] = -LUT[k] exactly (Algorithm 1 builds the upper half by negation)
         assert np.array_equal(got[:, ::-1, :], -got)
 
@@ -158,7 +168,7 @@ def test_gemm_parity_large_configs_sampled_rows(biq, oracle, name, mus):
 
 
 @pytest.mark.parametrize("m,n,q,b", RAGGED_SHAPES)
-@pytest.mark.parametrize("mu", [8, 4, 6, 1, 2, 3, 5, 7])
+@pytest.mark.parametrize("mu", [8, 4, 6, 1, 2, 3, 5, 7, 9, 10])
 def test_gemm_parity_ragged_shapes(biq, oracle, m, n, q, b, mu):
     _say("gemm ragged m=%d n=%d q=%d b=%d mu=%d" % (m, n, q, b, mu))
     B, alpha, X = _rand_inputs(m, n, q, b, 4000 + m + n + mu)
@@ -168,7 +178,7 @@ def test_gemm_parity_ragged_shapes(biq, oracle, m, n, q, b, mu):
     assert_within_tolerance(Y, oracle.gemm_dense(B, alpha, X), alpha, X, "ragged")
 
 
-@pytest.mark.parametrize("mu", [8, 4, 6, 3])
+@pytest.mark.parametrize("mu", [8, 4, 6, 3, 9, 10])
 def test_gemm_bit_exact_on_exact_inputs(biq, oracle, mu):
     """Small-integer x and power-of-two alpha: every fp32 partial sum is exact, so any table
     width, tiling and reduction order must reproduce the oracle bit for bit."""
@@ -504,7 +514,7 @@ def test_random_shapes_default_plans(biq, oracle):
     rng = np.random.default_rng(777)
     seen = set()
     for case in range(70):
-        mu = int(rng.integers(1, 9))
+        mu = int(rng.integers(1, 11))
         q = int(rng.integers(1, 6))
         b = int(rng.choice([1, 1, 2, 3, 5, 8, 33, 70, 130]))
         n = int(rng.choice([int(rng.integers(1, 300)), int(rng.integers(300, 2200)), int(rng.integers(2200, 9000))]))
@@ -513,6 +523,10 @@ def test_random_shapes_default_plans(biq, oracle):
             m = max(1, m // 2)
         if case % 7 == 0:                      # make sure the wide small GEMV / batched cases occur
             mu, b, n = 8, int(rng.choice([1, 4])), int(rng.integers(1030, 2048))
+        if case % 10 == 6:                     # ... the full-table GEMV and batched kernels
+            mu, b, n = 8, 1, int(rng.integers(100, 1000))
+        if case % 10 == 8:
+            mu, b, n = 8, int(rng.choice([2, 5])), int(rng.integers(64, 500))
         if case % 10 == 3:                     # ... and the matrix-core path
             m, n, q, b = int(rng.integers(2000, 3000)), int(rng.integers(1500, 2500)), 2, 130
         kname = biq.biq_kernel_name(biq.biq_plan_get(m, n, q, b, mu).kernel)
