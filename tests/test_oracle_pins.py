@@ -27,7 +27,7 @@ def test_pack_printed_example(oracle):
 def test_pack_sign_and_bit_order_single_elements(oracle):
     # one +1 at position j in an otherwise -1 chunk must give key 2**j (Algorithm 1's
     # indexing 2^(i-1)+j <-> x_(i-1); Algorithm 3's (x >> i) & 1 <-> w_i)
-    for mu in range(1, 9):
+    for mu in range(1, 11):
         for j in range(mu):
             signs = -np.ones(mu, dtype=np.int8)
             signs[j] = 1
@@ -87,7 +87,7 @@ def test_keys_mu8_are_the_bitmap_bytes_and_mu4_nibbles(oracle):
     k4 = oracle.pack_keys(B, 4)
     assert np.array_equal(k8, bitmap[:, :, : n // 8].astype(np.uint16))
     assert np.array_equal(k8, k4[:, :, 0::2] | (k4[:, :, 1::2] << 4))
-    for mu in range(1, 9):
+    for mu in range(1, 11):
         assert np.array_equal(oracle.keys_from_bitmap(bitmap, n, mu), oracle.pack_keys(B, mu))
 
 
@@ -115,7 +115,7 @@ def _m_mu(mu: int) -> np.ndarray:
     return np.array([[1.0 if (k >> j) & 1 else -1.0 for j in range(mu)] for k in range(1 << mu)])
 
 
-@pytest.mark.parametrize("mu", range(1, 9))
+@pytest.mark.parametrize("mu", range(1, 11))
 def test_lut_is_M_mu_times_x(oracle, mu):
     rng = np.random.default_rng(100 + mu)
     x = rng.standard_normal(mu)
@@ -127,7 +127,7 @@ def test_lut_is_M_mu_times_x(oracle, mu):
         assert abs(table[k] - float(np.dot(signs, x))) < 1e-14
 
 
-@pytest.mark.parametrize("mu", range(1, 9))
+@pytest.mark.parametrize("mu", range(1, 11))
 def test_lut_closed_forms_and_invariants(oracle, mu):
     rng = np.random.default_rng(200 + mu)
     x = rng.standard_normal(mu)
@@ -212,7 +212,7 @@ def test_gemm_dense_matches_numpy_matmul(oracle, m, n, q, b):
 
 
 @pytest.mark.parametrize("m,n,q,b", SHAPES)
-@pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 def test_gemm_lut_matches_dense_definition(oracle, m, n, q, b, mu):
     rng = np.random.default_rng(m * 977 + n * 13 + mu)
     B = (rng.integers(0, 2, size=(q, m, n)) * 2 - 1).astype(np.int8)
