@@ -237,21 +237,36 @@ __global__ __launch_bounds__(1024) void query_kernel(const QueryParams p) {
 
         const int dw0 = (c0 / UK) * UD + L * UD;  // this lane's unit inside a packed row
         const float* tab = tables + (size_t)L * UK * E * BT;
+        // (row, plane) pairs are walked with the next pair's keys and scale already requested
+        auto load_pair = [&](int r, int i, uint32_t (&w)[UD], float& al) {
+#pragma unroll
+            for (int d = 0; d < UD; ++d) w[d] = 0u;
+            al = 0.0f;
+            if (r < r1) {
+                const size_t kr = (size_t)i * p.m + r;
+                load_unit<UD>(p.K + kr * p.stride_dw, dw0, p.stride_dw, w);
+                al = p.alpha[kr];
+            }
+        };
+        uint32_t wcur[UD], wnext[UD];
+        float alcur, alnext;
+        load_pair(r0 + grp, 0, wcur, alcur);
         for (int r = r0 + grp; r < r1; r += ngrp) {
             float y[BT];
 #pragma unroll
             for (int c = 0; c < BT; ++c) y[c] = 0.0f;
             for (int i = 0; i < p.q; ++i) {
-                const size_t kr = (size_t)i * p.m + r;
-                uint32_t w[UD];
-                load_unit<UD>(p.K + kr * p.stride_dw, dw0, p.stride_dw, w);
+                if (i + 1 < p.q) load_pair(r, i + 1, wnext, alnext);
+                else load_pair(r + ngrp, 0, wnext, alnext);
                 float acc[BT];
 #pragma unroll
                 for (int c = 0; c < BT; ++c) acc[c] = 0.0f;
-                lookup_unit<MU, BT, 0>(w, tab, acc);
-                const float al = p.alpha[kr];
+                lookup_unit<MU, BT, 0>(wcur, tab, acc);
 #pragma unroll
-                for (int c = 0; c < BT; ++c) y[c] = fmaf(al, acc[c], y[c]);
+                for (int c = 0; c < BT; ++c) y[c] = fmaf(alcur, acc[c], y[c]);
+#pragma unroll
+                for (int d = 0; d < UD; ++d) wcur[d] = wnext[d];
+                alcur = alnext;
             }
             // reduce over the G lanes of the row group (G is a power of two <= 64)
             for (int off = G >> 1; off > 0; off >>= 1) {
