@@ -409,6 +409,22 @@ inline hipError_t grant_large_lds(const void* kern, unsigned long long& granted)
     return e;
 }
 
+inline bool aligned(const void* p, size_t a);
+
+// Adds the `splits` partial results [splits][count] into Y.
+inline hipError_t launch_reduce_splits(const float* partial, float* Y, long long count, int splits,
+                                       hipStream_t s) {
+    const bool vec4 = (count % 4 == 0) && ((reinterpret_cast<uintptr_t>(partial) & 15) == 0) &&
+                      ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
+    if (vec4)
+        hipLaunchKernelGGL(reduce_splits_kernel<4>, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, s,
+                           partial, Y, count, splits);
+    else
+        hipLaunchKernelGGL(reduce_splits_kernel<1>, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s,
+                           partial, Y, count, splits);
+    return hipGetLastError();
+}
+
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 template <int MU, int BT, bool FUSED>
@@ -631,9 +647,7 @@ biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* al
     if (e != hipSuccess) return BIQ_EHIP;
     if (pl.chunk_splits > 1) {
         const long long count = (long long)batch * m;
-        hipLaunchKernelGGL(reduce_splits_kernel, dim3(ceil_div(count, 256)), dim3(256), 0, s, partial, Y,
-                           count, pl.chunk_splits);
-        if (hipGetLastError() != hipSuccess) return BIQ_EHIP;
+        if (launch_reduce_splits(partial, Y, count, pl.chunk_splits, s) != hipSuccess) return BIQ_EHIP;
     }
     return BIQ_OK;
 }
@@ -711,9 +725,9 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     if (e != hipSuccess) return BIQ_EHIP;
     if (pl.chunk_splits > 1) {
         const long long count = (long long)batch * m;
-        hipLaunchKernelGGL(reduce_splits_kernel, dim3(ceil_div(count, 256)), dim3(256), 0, s,
-                           reinterpret_cast<const float*>(workspace), Y, count, pl.chunk_splits);
-        if (hipGetLastError() != hipSuccess) return BIQ_EHIP;
+        if (launch_reduce_splits(reinterpret_cast<const float*>(workspace), Y, count, pl.chunk_splits, s) !=
+            hipSuccess)
+            return BIQ_EHIP;
     }
     return BIQ_OK;
 }

@@ -299,15 +299,26 @@ __global__ __launch_bounds__(1024) void query_kernel(const QueryParams p) {
     }
 }
 
-// Sum of the chunk-split partials in a fixed order: Y[i] = sum_s partial[s][i].
+// Sum of the chunk-split partials in a fixed order: Y[i] = sum_s partial[s][i].  VEC = 4: 16-byte
+// accesses (count a multiple of 4, both buffers 16-byte aligned).
+template <int VEC>
 __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ partial,
                                                             float* __restrict__ Y, long long count,
                                                             int splits) {
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long i = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
     if (i >= count) return;
-    float acc = partial[i];
-    for (int s = 1; s < splits; ++s) acc += partial[(size_t)s * count + i];
-    Y[i] = acc;
+    if constexpr (VEC == 4) {
+        float4 acc = *reinterpret_cast<const float4*>(partial + i);
+        for (int s = 1; s < splits; ++s) {
+            const float4 v = *reinterpret_cast<const float4*>(partial + (size_t)s * count + i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        *reinterpret_cast<float4*>(Y + i) = acc;
+    } else {
+        float acc = partial[i];
+        for (int s = 1; s < splits; ++s) acc += partial[(size_t)s * count + i];
+        Y[i] = acc;
+    }
 }
 
 }  // namespace biq
