@@ -409,6 +409,15 @@ inline hipError_t grant_large_lds(const void* kern, unsigned long long& granted)
     return e;
 }
 
+// Launch of a kernel that needs more than 48 KiB of dynamic LDS; one opt-in bitmap per kernel.
+template <auto Kern, typename Params>
+hipError_t launch_large_lds(const Params& params, int grid, int threads, int lds, hipStream_t s) {
+    static unsigned long long granted = 0;
+    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(Kern), granted); e != hipSuccess) return e;
+    hipLaunchKernelGGL(Kern, dim3(grid), dim3(threads), lds, s, params);
+    return hipGetLastError();
+}
+
 inline bool aligned(const void* p, size_t a);
 
 // Adds the `splits` partial results [splits][count] into Y.
@@ -429,12 +438,8 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 
 template <int MU, int BT, bool FUSED>
 hipError_t launch_query_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    auto kern = query_kernel<MU, BT, FUSED>;
-    if (lds > 48 * 1024) {
-        static unsigned long long granted = 0;
-        if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
+    if (lds > 48 * 1024) return launch_large_lds<query_kernel<MU, BT, FUSED>>(qp, grid, threads, lds, s);
+    hipLaunchKernelGGL((query_kernel<MU, BT, FUSED>), dim3(grid), dim3(threads), lds, s, qp);
     return hipGetLastError();
 }
 
@@ -467,11 +472,7 @@ hipError_t launch_query_mu(int mu, int bt, const QueryParams& qp, int grid, int 
 
 template <int MU, bool FUSED>
 hipError_t launch_wide_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    auto kern = query_wide_kernel<MU, FUSED>;
-    static unsigned long long granted = 0;
-    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
-    return hipGetLastError();
+    return launch_large_lds<query_wide_kernel<MU, FUSED>>(qp, grid, threads, lds, s);
 }
 
 template <bool FUSED>
@@ -489,12 +490,8 @@ hipError_t launch_wide(int mu, const QueryParams& qp, int grid, int threads, int
 
 template <int Q, bool FUSED, int MAXT>
 hipError_t launch_gemv8_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    auto kern = gemv8_kernel<Q, FUSED, MAXT>;
     if (threads > MAXT) return hipErrorInvalidValue;
-    static unsigned long long granted = 0;
-    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
-    return hipGetLastError();
+    return launch_large_lds<gemv8_kernel<Q, FUSED, MAXT>>(qp, grid, threads, lds, s);
 }
 
 template <bool FUSED>
@@ -512,11 +509,7 @@ hipError_t launch_gemv8(int q, const QueryParams& qp, int grid, int threads, int
 
 template <int Q, bool FUSED>
 hipError_t launch_gemv8h_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    auto kern = gemv8h_kernel<Q, FUSED>;
-    static unsigned long long granted = 0;
-    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
-    return hipGetLastError();
+    return launch_large_lds<gemv8h_kernel<Q, FUSED>>(qp, grid, threads, lds, s);
 }
 
 template <bool FUSED>
@@ -531,11 +524,7 @@ hipError_t launch_gemv8h(int q, const QueryParams& qp, int grid, int threads, in
 
 template <int Q, bool FUSED>
 hipError_t launch_gemm8x2h_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    auto kern = gemm8x2h_kernel<Q, FUSED>;
-    static unsigned long long granted = 0;
-    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
-    return hipGetLastError();
+    return launch_large_lds<gemm8x2h_kernel<Q, FUSED>>(qp, grid, threads, lds, s);
 }
 
 template <bool FUSED>
@@ -550,11 +539,7 @@ hipError_t launch_gemm8x2h(int q, const QueryParams& qp, int grid, int threads, 
 
 template <int Q, bool FUSED>
 hipError_t launch_gemm8x2_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    auto kern = gemm8x2_kernel<Q, FUSED>;
-    static unsigned long long granted = 0;
-    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qp);
-    return hipGetLastError();
+    return launch_large_lds<gemm8x2_kernel<Q, FUSED>>(qp, grid, threads, lds, s);
 }
 
 template <bool FUSED>
@@ -572,12 +557,8 @@ hipError_t launch_unpack_inst(const UnpackParams& up, int grid, int lds, hipStre
     if constexpr (WS == 4 && Q * RPW * CT == 8) {
         return hipErrorInvalidValue;  // not built (register file, LDS): plan_finish_unpack rejects it
     } else {
-        auto kern = unpack_mfma_kernel<Q, RPW, CT, WS>;
         if (lds != UnpackGeom<CT, WS>::LDS_BYTES) return hipErrorInvalidValue;
-        static unsigned long long granted = 0;
-        if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(kern), granted); e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kUnpackThreads), lds, s, up);
-        return hipGetLastError();
+        return launch_large_lds<unpack_mfma_kernel<Q, RPW, CT, WS>>(up, grid, kUnpackThreads, lds, s);
     }
 }
 
