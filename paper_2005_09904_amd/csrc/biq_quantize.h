@@ -79,9 +79,11 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_wave_kernel(const floa
             r[t] = valid ? rn : 0.0f;
             // v_writelane_b32: the (wave-uniform) mask halves go into lane t of the keep registers.
             // The mask comes from a VALU compare; the assembler text is not seen by the compiler's
-            // hazard recogniser, hence the explicit wait states before the first read.
-            asm("s_nop 4\n\tv_writelane_b32 %0, %1, %2" : "+v"(keep_lo[t >> 6]) : "s"((uint32_t)mask), "n"(t & 63));
-            asm("v_writelane_b32 %0, %1, %2" : "+v"(keep_hi[t >> 6]) : "s"((uint32_t)(mask >> 32)), "n"(t & 63));
+            // hazard recogniser, hence the explicit wait states before the first read (one statement for
+            // both halves, so that neither can be scheduled ahead of the wait).
+            asm("s_nop 4\n\tv_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+                : "+v"(keep_lo[t >> 6]), "+v"(keep_hi[t >> 6])
+                : "s"((uint32_t)mask), "s"((uint32_t)(mask >> 32)), "n"(t & 63));
         }
 #pragma unroll
         for (int u = 0; u < (EPT + 63) / 64; ++u) {
