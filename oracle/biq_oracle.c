@@ -136,17 +136,26 @@ void biqo_lut_enum(const double* x, int mu, double* table) {
  * performed, which Eq. 6 states as 2^mu + mu - 1 per table.
  */
 long biqo_lut_dp(const double* x, int mu, double* r) {
+    const long half = 1L << (mu - 1);
+    const long last = (1L << mu) - 1;
     long ops = 0;
-    /* entry of key 0: every sign is -1 (mu operations: mu-1 adds, 1 negation) */
-    double s = x[0];
-    for (int i = 1; i < mu; ++i) { s += x[i]; ++ops; }
-    r[0] = -s; ++ops;
-    /* lower half: setting bit (i-1) of key j < 2^(i-1) flips x_(i-1) from - to + */
-    long k = 1;
-    for (int i = 1; i <= mu - 1; ++i)
-        for (long j = 0; j < (1L << (i - 1)); ++j) { r[k++] = r[j] + 2.0 * x[i - 1]; ++ops; }
-    /* upper half: the complement of a key has the negated sum */
-    for (long i = 1; i <= (1L << (mu - 1)); ++i) { r[(1L << mu) - i] = -r[i - 1]; ++ops; }
+    /* Key 0 has every sign negative: -(x_0 + ... + x_(mu-1)), mu operations. */
+    double total = 0.0;
+    for (int j = 0; j < mu; ++j) total += x[j];
+    ops += mu - 1;             /* the first term of a sum is a move, not an addition */
+    r[0] = -total; ++ops;
+    /* Every other key of the lower half (top bit clear) is an already known key plus one more
+     * set bit: with t the highest set bit of k, the key k - 2^t has the same signs except
+     * for x_t, which flips from - to +, i.e. the sum grows by 2 x_t.  Keys in increasing
+     * order, so k - 2^t < k is always there already.  One operation each. */
+    int t = 0;
+    for (long k = 1; k < half; ++k) {
+        if (k == (2L << t)) ++t;                 /* k reached the next power of two */
+        r[k] = r[k - (1L << t)] + 2.0 * x[t];
+        ++ops;
+    }
+    /* The upper half needs no arithmetic on x: complementing a key negates every sign. */
+    for (long k = half; k <= last; ++k) { r[k] = -r[last - k]; ++ops; }
     return ops;
 }
 

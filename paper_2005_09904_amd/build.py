@@ -1,34 +1,29 @@
-"""Builds libbiq.so (the HIP kernels and their C ABI) for gfx950 with hipcc, in-tree."""
+"""Builds libbiq.so (the HIP kernels and their C ABI) for gfx950 with hipcc, in-tree.
+
+One translation unit per kernel family (csrc/*.hip), compiled side by side and linked into one
+shared library; objects go to paper_2005_09904_amd/_build/ (not tracked)."""
 from __future__ import annotations
 
+import glob
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
+OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libbiq.so")
-SOURCES = [os.path.join(CSRC, "biq_api.hip")]
-HEADERS = [
-    os.path.join(CSRC, "biq_common.h"),
-    os.path.join(CSRC, "biq_kernels.h"),
-    os.path.join(CSRC, "biq_gemv8.h"),
-    os.path.join(CSRC, "biq_gemm8x2.h"),
-    os.path.join(CSRC, "biq_gemv8h.h"),
-    os.path.join(CSRC, "biq_gemm8x2h.h"),
-    os.path.join(CSRC, "biq_query_wide.h"),
-    os.path.join(CSRC, "biq_unpack_mfma.h"),
-    os.path.join(CSRC, "biq_quantize.h"),
-    os.path.join(ROOT, "include", "biq.h"),
-]
+SOURCES = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+HEADERS = sorted(glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(CSRC, "*.inc"))) + [
+    os.path.join(ROOT, "include", "biq.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
     "-O3",
     "-std=c++17",
     "-fPIC",
-    "-shared",
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
@@ -41,23 +36,37 @@ def is_stale() -> bool:
     return any(os.path.getmtime(p) > built for p in SOURCES + HEADERS)
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compiles every HIP source into libbiq.so (always recompiles). Returns the library path."""
-    hipcc = os.environ.get("HIPCC", "hipcc")
-    tmp = LIB_PATH + ".tmp.%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I" + os.path.join(ROOT, "include"), "-I" + CSRC] + SOURCES + ["-o", tmp]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass warns that it does not know the packed-fp32 feature; that is expected
     out = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
     if proc.returncode != 0:
-        if os.path.exists(tmp):
-            os.remove(tmp)
-        raise RuntimeError("hipcc failed:\n" + out)
+        raise RuntimeError("hipcc failed: %s\n%s" % (" ".join(cmd), out))
     if verbose and out.strip():
         print(out)
-    os.replace(tmp, LIB_PATH)
+
+
+def build_library(verbose: bool = False, jobs: int | None = None) -> str:
+    """Compiles every HIP source and links libbiq.so (always recompiles). Returns the library path."""
+    hipcc = os.environ.get("HIPCC", "hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    inc = ["-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+    tag = ".%d" % os.getpid()
+    objs = [os.path.join(OBJ_DIR, os.path.basename(s)[:-4] + tag + ".o") for s in SOURCES]
+    jobs = jobs or min(len(SOURCES), int(os.environ.get("MAX_JOBS", "0")) or os.cpu_count() or 1, 16)
+    try:
+        with ThreadPoolExecutor(max_workers=jobs) as pool:
+            list(pool.map(lambda so: _run([hipcc] + HIPCC_FLAGS + inc + ["-c", so[0], "-o", so[1]], verbose),
+                          zip(SOURCES, objs)))
+        tmp = LIB_PATH + ".tmp" + tag
+        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", tmp], verbose)
+        os.replace(tmp, LIB_PATH)
+    finally:
+        for o in objs:
+            if os.path.exists(o):
+                os.remove(o)
     return LIB_PATH
 
 

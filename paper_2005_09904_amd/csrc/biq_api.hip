@@ -3,13 +3,13 @@
 
 #include <hip/hip_runtime.h>
 
-#include "biq_kernels.h"
+#include "biq_launch.h"
+// kernel headers: only their geometry constants are used here (no kernel is instantiated in this file)
 #include "biq_gemv8.h"
 #include "biq_gemm8x2.h"
 #include "biq_gemv8h.h"
 #include "biq_gemm8x2h.h"
 #include "biq_query_wide.h"
-#include "biq_unpack_mfma.h"
 #include "biq_quantize.h"
 
 namespace {
@@ -17,7 +17,6 @@ namespace {
 using namespace biq;
 
 // gfx950 (MI355X) limits the planner is written for.
-constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kLdsTableBudget = 128 * 1024;  // tables of one tile (leaves room for 1 WG/CU extras)
 constexpr int kNumCu = 256;
 constexpr int kNumXcd = 8;
@@ -40,7 +39,17 @@ inline int unit_keys(int mu) {
     }
 }
 
-inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+inline int ceil_div(int a, int b) { return (int)(((long long)a + b - 1) / b); }
+inline long long ceil_div_ll(long long a, long long b) { return (a + b - 1) / b; }
+// rows per workgroup from a 64-bit estimate: rounded up to a multiple of `step`, at least `lo`, and
+// never beyond what the 32-bit plan field holds (more rows than m are pointless anyway)
+inline int rows_from(long long want, int step, int lo, int m) {
+    long long r = ceil_div_ll(want, step) * step;
+    const long long cap = ceil_div_ll(m, step) * step;
+    if (r > cap) r = cap;
+    if (r < lo) r = lo;
+    return (int)r;
+}
 inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
 
 // 16-byte pieces of prepared input per key group (16 MFMA steps): column tiles x 3 bf16 terms x 64 lanes
@@ -182,7 +191,9 @@ bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
 //  - chunk splits: bounded so that the partial sums written stay below about twice the
 //    bytes the method has to move anyway
 //  - rows per workgroup: enough workgroups to fill the 256 CUs several times over
-void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tables_given = false) {
+bool plan_generic(biq_plan& pl, int m, int n, int q, int batch, int mu);
+
+bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tables_given) {
     const int UK = unit_keys(mu);
     const int C = ceil_div(n, mu);
     const int E = 1 << mu;
@@ -218,8 +229,7 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
                 break;
             }
         }
-        plan_finish(pl, m, n, q, batch, mu);
-        return;
+        return plan_finish(pl, m, n, q, batch, mu);
     }
     if (mu == 8 && batch == 1 && q <= 4) {
         // GEMV: workgroups of 1024 threads, 128-chunk tiles, one workgroup per CU when the
@@ -251,25 +261,22 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
             pl.tiles_per_split = 1;
             pl.row_mode = 1;
             const int tiles_h = ceil_div(C, kGemvHalfTileChunks);
-            int rows = ceil_div(ceil_div((long long)m * tiles_h, kNumCu), 4) * 4;
-            pl.rows_per_wg = rows < 8 ? 8 : rows;
+            pl.rows_per_wg = rows_from(ceil_div_ll((long long)m * tiles_h, kNumCu), 4, 8, m);
             // up to one row per wave: 64 lanes per row instead of 16 (4 lookups per lane and plane)
             if (pl.rows_per_wg <= 16) pl.row_mode = 2;
         } else if ((long long)m * tiles <= 4ll * 128 * kNumCu) {
             // small: latency mode, 8 rows per wave step, at most 4 steps per wave
             pl.tiles_per_split = 1;
             pl.row_mode = 1;
-            int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 8) * 8;
-            pl.rows_per_wg = rows < 8 ? 8 : rows;
+            pl.rows_per_wg = rows_from(ceil_div_ll((long long)m * tiles, kNumCu), 8, 8, m);
         } else {
             pl.tiles_per_split = 1;
-            int rows = ceil_div(ceil_div((long long)m * tiles, kNumCu), 64) * 64;
+            const int rows = rows_from(ceil_div_ll((long long)m * tiles, kNumCu), 64, 64, m);
             pl.rows_per_wg = rows > 8192 ? 8192 : rows;
         }
         // 4 planes in the streaming modes: 512 threads (the 1024-thread kernel spills registers)
         if (q == 4 && pl.kernel == KERNEL_GEMV8 && pl.row_mode == 0) pl.threads = 512;
-        plan_finish(pl, m, n, q, batch, mu);
-        return;
+        return plan_finish(pl, m, n, q, batch, mu);
     }
     if (mu == 8 && batch >= 2 && q <= 4 && C > kGemmTileChunks &&
         (long long)m * ceil_div(C, kGemmHalfTileChunks) * ceil_div(batch, 2) <= 512ll * kNumCu) {
@@ -284,10 +291,8 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
         pl.tiles_per_split = 1;
         pl.row_mode = 1;
         const long long units = (long long)m * ceil_div(C, kGemmHalfTileChunks) * ceil_div(batch, 2);
-        int rows = ceil_div(ceil_div(units, kNumCu), 8) * 8;
-        pl.rows_per_wg = rows < 8 ? 8 : rows;
-        plan_finish(pl, m, n, q, batch, mu);
-        return;
+        pl.rows_per_wg = rows_from(ceil_div_ll(units, kNumCu), 8, 8, m);
+        return plan_finish(pl, m, n, q, batch, mu);
     }
     if (mu == 8 && batch >= 2 && q <= 4) {
         // Batched: workgroups of 1024 threads over (row block, chunk split, pair of input
@@ -305,13 +310,13 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
         const long long RT = (long long)ceil_div(m, rows) * T;
         int S = 1;
         if (RT < kNumCu) {
-            S = ceil_div(kNumCu, RT);
+            S = (int)ceil_div_ll(kNumCu, RT);
             if (S > tiles) S = tiles;
         }
         pl.tiles_per_split = ceil_div(tiles, S);
         S = ceil_div(tiles, pl.tiles_per_split);
         if (RT * S < kNumCu) {
-            int r2 = ceil_div(ceil_div((long long)m * T * S, kNumCu), 64) * 64;
+            const int r2 = rows_from(ceil_div_ll((long long)m * T * S, kNumCu), 64, 64, m);
             if (r2 < rows) rows = r2;
         }
         if (pl.tiles_per_split == 1 && rows <= 4 * 256) {
@@ -320,8 +325,7 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
             rows = ceil_div(rows, 256) * 256;
         }
         pl.rows_per_wg = rows;
-        plan_finish(pl, m, n, q, batch, mu);
-        return;
+        return plan_finish(pl, m, n, q, batch, mu);
     }
     if ((mu <= 5 || (mu == 6 && batch <= 4)) && 2 * C >= 32 * UK) {
         // Narrow keys, rows at least half a tile wide: 32 lanes per row, conflict-free gathers.
@@ -336,13 +340,19 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
         pl.batch_tile = (128 * 1024) / (32 * UK * E * 4);
         pl.tiles_per_split = 1;
         const long long units = (long long)m * ceil_div(C, pl.chunks_per_tile) * ceil_div(batch, pl.batch_tile);
-        long long rows = ceil_div(ceil_div(units, kNumCu), 32) * 32ll;
-        if (rows < 32) rows = 32;
-        if (rows > (1 << 20)) rows = 1 << 20;
-        pl.rows_per_wg = (int)rows;
-        plan_finish(pl, m, n, q, batch, mu);
-        return;
+        const int rows = rows_from(ceil_div_ll(units, kNumCu), 32, 32, m);
+        pl.rows_per_wg = rows > (1 << 20) ? (1 << 20) : rows;
+        return plan_finish(pl, m, n, q, batch, mu);
     }
+    return plan_generic(pl, m, n, q, batch, mu);
+}
+
+// The generic kernel: any mu, any q.
+bool plan_generic(biq_plan& pl, int m, int n, int q, int batch, int mu) {
+    const int UK = unit_keys(mu);
+    const int C = ceil_div(n, mu);
+    const int E = 1 << mu;
+    pl = biq_plan{};
     pl.kernel = KERNEL_GENERIC;
     pl.batch_tile = batch >= 5 ? 8 : batch >= 3 ? 4 : batch;
     // one key unit's tables must fit the LDS budget (mu = 9, 10: 64 KiB per unit and input vector)
@@ -380,7 +390,15 @@ void plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
         if (k > fit) k = fit < 1 ? 1 : fit;
     }
     pl.rows_per_wg = (int)(k * groups);
-    plan_finish(pl, m, n, q, batch, mu);
+    return plan_finish(pl, m, n, q, batch, mu);
+}
+
+// The library's plan for a shape.  Should the tuned choice not pass plan_finish (a shape outside
+// what its kernel's 32-bit offsets cover), the generic kernel takes the call; false if that
+// fails too (the caller reports BIQ_EUNSUPPORTED, sizes read as 0).
+bool plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tables_given = false) {
+    if (plan_tuned(pl, m, n, q, batch, mu, tables_given)) return true;
+    return plan_generic(pl, m, n, q, batch, mu);
 }
 
 // Bytes of the prepared-input area at the start of the workspace (unpack-MFMA plans only).
@@ -396,198 +414,7 @@ size_t plan_workspace(const biq_plan& pl, int m, int batch) {
            (pl.chunk_splits > 1 ? (size_t)pl.chunk_splits * batch * m * sizeof(float) : 0);
 }
 
-// Opt-in to dynamic LDS above 48 KiB.  The attribute belongs to (function, device): `granted` is
-// the instantiation's bitmap of devices that already have it (devices >= 64 are set every time).
-// Concurrent first calls from several threads at worst set the attribute twice.
-inline hipError_t grant_large_lds(const void* kern, unsigned long long& granted) {
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < 64 && ((granted >> dev) & 1ull)) return hipSuccess;
-    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
-    if (e == hipSuccess && dev >= 0 && dev < 64) granted |= 1ull << dev;
-    return e;
-}
-
-// Launch of a kernel that needs more than 48 KiB of dynamic LDS; one opt-in bitmap per kernel.
-template <auto Kern, typename Params>
-hipError_t launch_large_lds(const Params& params, int grid, int threads, int lds, hipStream_t s) {
-    static unsigned long long granted = 0;
-    if (hipError_t e = grant_large_lds(reinterpret_cast<const void*>(Kern), granted); e != hipSuccess) return e;
-    hipLaunchKernelGGL(Kern, dim3(grid), dim3(threads), lds, s, params);
-    return hipGetLastError();
-}
-
-inline bool aligned(const void* p, size_t a);
-
-// Adds the `splits` partial results [splits][count] into Y.
-inline hipError_t launch_reduce_splits(const float* partial, float* Y, long long count, int splits,
-                                       hipStream_t s) {
-    const bool vec4 = (count % 4 == 0) && ((reinterpret_cast<uintptr_t>(partial) & 15) == 0) &&
-                      ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
-    if (vec4)
-        hipLaunchKernelGGL(reduce_splits_kernel<4>, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, s,
-                           partial, Y, count, splits);
-    else
-        hipLaunchKernelGGL(reduce_splits_kernel<1>, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s,
-                           partial, Y, count, splits);
-    return hipGetLastError();
-}
-
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
-
-template <int MU, int BT, bool FUSED>
-hipError_t launch_query_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    if (lds > 48 * 1024) return launch_large_lds<query_kernel<MU, BT, FUSED>>(qp, grid, threads, lds, s);
-    hipLaunchKernelGGL((query_kernel<MU, BT, FUSED>), dim3(grid), dim3(threads), lds, s, qp);
-    return hipGetLastError();
-}
-
-template <int MU, bool FUSED>
-hipError_t launch_query_bt(int bt, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    switch (bt) {
-        case 1: return launch_query_inst<MU, 1, FUSED>(qp, grid, threads, lds, s);
-        case 2: return launch_query_inst<MU, 2, FUSED>(qp, grid, threads, lds, s);
-        case 4: return launch_query_inst<MU, 4, FUSED>(qp, grid, threads, lds, s);
-        default: return launch_query_inst<MU, 8, FUSED>(qp, grid, threads, lds, s);
-    }
-}
-
-template <bool FUSED>
-hipError_t launch_query_mu(int mu, int bt, const QueryParams& qp, int grid, int threads, int lds,
-                           hipStream_t s) {
-    switch (mu) {
-        case 1: return launch_query_bt<1, FUSED>(bt, qp, grid, threads, lds, s);
-        case 2: return launch_query_bt<2, FUSED>(bt, qp, grid, threads, lds, s);
-        case 3: return launch_query_bt<3, FUSED>(bt, qp, grid, threads, lds, s);
-        case 4: return launch_query_bt<4, FUSED>(bt, qp, grid, threads, lds, s);
-        case 5: return launch_query_bt<5, FUSED>(bt, qp, grid, threads, lds, s);
-        case 6: return launch_query_bt<6, FUSED>(bt, qp, grid, threads, lds, s);
-        case 7: return launch_query_bt<7, FUSED>(bt, qp, grid, threads, lds, s);
-        case 8: return launch_query_bt<8, FUSED>(bt, qp, grid, threads, lds, s);
-        case 9: return launch_query_bt<9, FUSED>(bt, qp, grid, threads, lds, s);
-        default: return launch_query_bt<10, FUSED>(bt, qp, grid, threads, lds, s);
-    }
-}
-
-template <int MU, bool FUSED>
-hipError_t launch_wide_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    return launch_large_lds<query_wide_kernel<MU, FUSED>>(qp, grid, threads, lds, s);
-}
-
-template <bool FUSED>
-hipError_t launch_wide(int mu, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    switch (mu) {
-        case 1: return launch_wide_inst<1, FUSED>(qp, grid, threads, lds, s);
-        case 2: return launch_wide_inst<2, FUSED>(qp, grid, threads, lds, s);
-        case 3: return launch_wide_inst<3, FUSED>(qp, grid, threads, lds, s);
-        case 4: return launch_wide_inst<4, FUSED>(qp, grid, threads, lds, s);
-        case 5: return launch_wide_inst<5, FUSED>(qp, grid, threads, lds, s);
-        case 6: return launch_wide_inst<6, FUSED>(qp, grid, threads, lds, s);
-    }
-    return hipErrorInvalidValue;
-}
-
-template <int Q, bool FUSED, int MAXT>
-hipError_t launch_gemv8_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    if (threads > MAXT) return hipErrorInvalidValue;
-    return launch_large_lds<gemv8_kernel<Q, FUSED, MAXT>>(qp, grid, threads, lds, s);
-}
-
-template <bool FUSED>
-hipError_t launch_gemv8(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    switch (q) {
-        case 1: return launch_gemv8_inst<1, FUSED, 1024>(qp, grid, threads, lds, s);
-        case 2: return launch_gemv8_inst<2, FUSED, 1024>(qp, grid, threads, lds, s);
-        case 3: return launch_gemv8_inst<3, FUSED, 1024>(qp, grid, threads, lds, s);
-        default:
-            // 4 planes: up to 512 threads run the instantiation with the larger register budget
-            return threads <= 512 ? launch_gemv8_inst<4, FUSED, 512>(qp, grid, threads, lds, s)
-                                  : launch_gemv8_inst<4, FUSED, 1024>(qp, grid, threads, lds, s);
-    }
-}
-
-template <int Q, bool FUSED>
-hipError_t launch_gemv8h_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    return launch_large_lds<gemv8h_kernel<Q, FUSED>>(qp, grid, threads, lds, s);
-}
-
-template <bool FUSED>
-hipError_t launch_gemv8h(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    switch (q) {
-        case 1: return launch_gemv8h_inst<1, FUSED>(qp, grid, threads, lds, s);
-        case 2: return launch_gemv8h_inst<2, FUSED>(qp, grid, threads, lds, s);
-        case 3: return launch_gemv8h_inst<3, FUSED>(qp, grid, threads, lds, s);
-        default: return launch_gemv8h_inst<4, FUSED>(qp, grid, threads, lds, s);
-    }
-}
-
-template <int Q, bool FUSED>
-hipError_t launch_gemm8x2h_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    return launch_large_lds<gemm8x2h_kernel<Q, FUSED>>(qp, grid, threads, lds, s);
-}
-
-template <bool FUSED>
-hipError_t launch_gemm8x2h(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    switch (q) {
-        case 1: return launch_gemm8x2h_inst<1, FUSED>(qp, grid, threads, lds, s);
-        case 2: return launch_gemm8x2h_inst<2, FUSED>(qp, grid, threads, lds, s);
-        case 3: return launch_gemm8x2h_inst<3, FUSED>(qp, grid, threads, lds, s);
-        default: return launch_gemm8x2h_inst<4, FUSED>(qp, grid, threads, lds, s);
-    }
-}
-
-template <int Q, bool FUSED>
-hipError_t launch_gemm8x2_inst(const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    return launch_large_lds<gemm8x2_kernel<Q, FUSED>>(qp, grid, threads, lds, s);
-}
-
-template <bool FUSED>
-hipError_t launch_gemm8x2(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
-    switch (q) {
-        case 1: return launch_gemm8x2_inst<1, FUSED>(qp, grid, threads, lds, s);
-        case 2: return launch_gemm8x2_inst<2, FUSED>(qp, grid, threads, lds, s);
-        case 3: return launch_gemm8x2_inst<3, FUSED>(qp, grid, threads, lds, s);
-        default: return launch_gemm8x2_inst<4, FUSED>(qp, grid, threads, lds, s);
-    }
-}
-
-template <int Q, int RPW, int CT, int WS>
-hipError_t launch_unpack_inst(const UnpackParams& up, int grid, int lds, hipStream_t s) {
-    if constexpr (WS == 4 && Q * RPW * CT == 8) {
-        return hipErrorInvalidValue;  // not built (register file, LDS): plan_finish_unpack rejects it
-    } else {
-        if (lds != UnpackGeom<CT, WS>::LDS_BYTES) return hipErrorInvalidValue;
-        return launch_large_lds<unpack_mfma_kernel<Q, RPW, CT, WS>>(up, grid, kUnpackThreads, lds, s);
-    }
-}
-
-template <int CT, int WS>
-hipError_t launch_unpack_qr(int q, int rpw, const UnpackParams& up, int grid, int lds, hipStream_t s) {
-    switch (q * 8 + rpw) {
-        case 1 * 8 + 1: return launch_unpack_inst<1, 1, CT, WS>(up, grid, lds, s);
-        case 1 * 8 + 2: return launch_unpack_inst<1, 2, CT, WS>(up, grid, lds, s);
-        case 1 * 8 + 4: return launch_unpack_inst<1, 4, CT, WS>(up, grid, lds, s);
-        case 2 * 8 + 1: return launch_unpack_inst<2, 1, CT, WS>(up, grid, lds, s);
-        case 2 * 8 + 2: return launch_unpack_inst<2, 2, CT, WS>(up, grid, lds, s);
-        case 3 * 8 + 1: return launch_unpack_inst<3, 1, CT, WS>(up, grid, lds, s);
-        case 4 * 8 + 1: return launch_unpack_inst<4, 1, CT, WS>(up, grid, lds, s);
-    }
-    return hipErrorInvalidValue;  // plan_finish_unpack admits no other combination
-}
-
-hipError_t launch_unpack(int q, int rpw, int ct, int ws, const UnpackParams& up, int grid, int lds,
-                         hipStream_t s) {
-    switch (ct * 8 + ws) {
-        case 1 * 8 + 1: return launch_unpack_qr<1, 1>(q, rpw, up, grid, lds, s);
-        case 1 * 8 + 2: return launch_unpack_qr<1, 2>(q, rpw, up, grid, lds, s);
-        case 1 * 8 + 4: return launch_unpack_qr<1, 4>(q, rpw, up, grid, lds, s);
-        case 2 * 8 + 1: return launch_unpack_qr<2, 1>(q, rpw, up, grid, lds, s);
-        case 2 * 8 + 2: return launch_unpack_qr<2, 2>(q, rpw, up, grid, lds, s);
-        case 2 * 8 + 4: return launch_unpack_qr<2, 4>(q, rpw, up, grid, lds, s);
-    }
-    return hipErrorInvalidValue;
-}
 
 // Large-batch path: split X into bf16 terms in MFMA operand order (workspace), contract, and
 // sum the partial results when the key groups were split over workgroups.
@@ -600,12 +427,7 @@ biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* al
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + plan_xf_bytes(pl));
 
     const long long total = (long long)pl.batch_tiles * steps * CT * 64;
-    const unsigned sgrid = (unsigned)((total + 255) / 256);
-    if (CT == 2)
-        hipLaunchKernelGGL(xsplit_kernel<2>, dim3(sgrid), dim3(256), 0, s, X, Xf, n, batch, steps, total);
-    else
-        hipLaunchKernelGGL(xsplit_kernel<1>, dim3(sgrid), dim3(256), 0, s, X, Xf, n, batch, steps, total);
-    if (hipGetLastError() != hipSuccess) return BIQ_EHIP;
+    if (launch_xsplit(CT, X, Xf, n, batch, steps, total, s) != hipSuccess) return BIQ_EHIP;
 
     UnpackParams up{};
     up.K = K;
@@ -646,9 +468,7 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
         pl = *user_plan;
         if (!plan_finish(pl, m, n, q, batch, mu)) return BIQ_EINVAL;
     } else {
-        plan_default(pl, m, n, q, batch, mu, !fused);
-        biq_plan checked = pl;
-        if (!plan_finish(checked, m, n, q, batch, mu)) return BIQ_EUNSUPPORTED;  // planner defect: never launch it
+        if (!plan_default(pl, m, n, q, batch, mu, !fused)) return BIQ_EUNSUPPORTED;
     }
     if (pl.kernel == KERNEL_UNPACK_MFMA && !fused) return BIQ_EINVAL;  // that kernel reads X, not tables
     const size_t need = plan_workspace(pl, m, batch);
@@ -685,24 +505,12 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     const int grid = qp.tasks_per_xcd * kNumXcd;
 
     hipError_t e;
-    if (pl.kernel == KERNEL_GEMV8)
-        e = fused ? launch_gemv8<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
-                  : launch_gemv8<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
-    else if (pl.kernel == KERNEL_GEMV8H)
-        e = fused ? launch_gemv8h<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
-                  : launch_gemv8h<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
-    else if (pl.kernel == KERNEL_WIDE)
-        e = fused ? launch_wide<true>(mu, qp, grid, pl.threads, pl.lds_bytes, s)
-                  : launch_wide<false>(mu, qp, grid, pl.threads, pl.lds_bytes, s);
-    else if (pl.kernel == KERNEL_GEMM8X2H)
-        e = fused ? launch_gemm8x2h<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
-                  : launch_gemm8x2h<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
-    else if (pl.kernel == KERNEL_GEMM8X2)
-        e = fused ? launch_gemm8x2<true>(q, qp, grid, pl.threads, pl.lds_bytes, s)
-                  : launch_gemm8x2<false>(q, qp, grid, pl.threads, pl.lds_bytes, s);
-    else
-        e = fused ? launch_query_mu<true>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s)
-                  : launch_query_mu<false>(mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s);
+    if (pl.kernel == KERNEL_GEMV8) e = launch_gemv8(fused, q, qp, grid, pl.threads, pl.lds_bytes, s);
+    else if (pl.kernel == KERNEL_GEMV8H) e = launch_gemv8h(fused, q, qp, grid, pl.threads, pl.lds_bytes, s);
+    else if (pl.kernel == KERNEL_WIDE) e = launch_wide(fused, mu, qp, grid, pl.threads, pl.lds_bytes, s);
+    else if (pl.kernel == KERNEL_GEMM8X2H) e = launch_gemm8x2h(fused, q, qp, grid, pl.threads, pl.lds_bytes, s);
+    else if (pl.kernel == KERNEL_GEMM8X2) e = launch_gemm8x2(fused, q, qp, grid, pl.threads, pl.lds_bytes, s);
+    else e = launch_query_generic(fused, mu, pl.batch_tile, qp, grid, pl.threads, pl.lds_bytes, s);
     if (e != hipSuccess) return BIQ_EHIP;
     if (pl.chunk_splits > 1) {
         const long long count = (long long)batch * m;
@@ -721,22 +529,9 @@ biq_status unpack_keys_any(const uint8_t* K, KEY* keys, int m, int n, int q, int
     const long long key_rows = (long long)q * m;
     const int stride_dw = (int)(biq_key_row_stride(n) / 4);
     const int C = ceil_div(n, mu);
-    const int units = ceil_div(C, unit_keys(mu));
-    const long long total = key_rows * units;
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    const unsigned grid = (unsigned)((total + 255) / 256);
-    const uint32_t* Kd = reinterpret_cast<const uint32_t*>(K);
-#define BIQ_UNPACK_CASE(MU)                                                                        \
-    case MU:                                                                                       \
-        hipLaunchKernelGGL((unpack_keys_kernel<MU, KEY>), dim3(grid), dim3(256), 0, s, Kd, keys,   \
-                           key_rows, C, stride_dw);                                                \
-        break;
-    switch (mu) {
-        BIQ_UNPACK_CASE(1) BIQ_UNPACK_CASE(2) BIQ_UNPACK_CASE(3) BIQ_UNPACK_CASE(4) BIQ_UNPACK_CASE(5)
-        BIQ_UNPACK_CASE(6) BIQ_UNPACK_CASE(7) BIQ_UNPACK_CASE(8) BIQ_UNPACK_CASE(9) BIQ_UNPACK_CASE(10)
-    }
-#undef BIQ_UNPACK_CASE
-    return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
+    const hipError_t e = launch_unpack_keys(mu, sizeof(KEY) == 2, reinterpret_cast<const uint32_t*>(K), keys,
+                                            key_rows, C, stride_dw, reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? BIQ_OK : BIQ_EHIP;
 }
 
 }  // namespace
@@ -775,14 +570,12 @@ size_t biq_lut_bytes(int n, int batch, int mu) {
 
 biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan) {
     if (!plan || !shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
-    plan_default(*plan, m, n, q, batch, mu);
-    return BIQ_OK;
+    return plan_default(*plan, m, n, q, batch, mu) ? BIQ_OK : BIQ_EUNSUPPORTED;
 }
 
 biq_status biq_plan_get_lut(int m, int n, int q, int batch, int mu, biq_plan* plan) {
     if (!plan || !shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
-    plan_default(*plan, m, n, q, batch, mu, true);
-    return BIQ_OK;
+    return plan_default(*plan, m, n, q, batch, mu, true) ? BIQ_OK : BIQ_EUNSUPPORTED;
 }
 
 biq_status biq_plan_check(int m, int n, int q, int batch, int mu, biq_plan* plan) {
@@ -799,9 +592,9 @@ size_t biq_workspace_bytes(int m, int n, int q, int batch, int mu) {
     if (!shape_ok(m, n, q, batch, mu)) return 0;
     // the larger of what biq_gemm's and biq_query's default plans need
     biq_plan pl;
-    plan_default(pl, m, n, q, batch, mu, false);
+    if (!plan_default(pl, m, n, q, batch, mu, false)) return 0;
     const size_t a = plan_workspace(pl, m, batch);
-    plan_default(pl, m, n, q, batch, mu, true);
+    if (!plan_default(pl, m, n, q, batch, mu, true)) return 0;
     const size_t b = plan_workspace(pl, m, batch);
     return a > b ? a : b;
 }
@@ -826,15 +619,9 @@ biq_status biq_pack(const int8_t* B, uint8_t* K, int m, int n, int q, int mu, vo
     const int stride_dw = (int)(biq_key_row_stride(n) / 4);
     const long long total = key_rows * stride_dw;
     if (total > (1ll << 38)) return BIQ_EUNSUPPORTED;
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    const unsigned grid = (unsigned)((total + 255) / 256);
-    if (n % 16 == 0 && aligned(B, 16))
-        hipLaunchKernelGGL(pack_kernel<true>, dim3(grid), dim3(256), 0, s, B,
-                           reinterpret_cast<uint32_t*>(K), key_rows, n, stride_dw);
-    else
-        hipLaunchKernelGGL(pack_kernel<false>, dim3(grid), dim3(256), 0, s, B,
-                           reinterpret_cast<uint32_t*>(K), key_rows, n, stride_dw);
-    return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
+    const hipError_t e = launch_pack(B, reinterpret_cast<uint32_t*>(K), key_rows, n, stride_dw,
+                                     reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? BIQ_OK : BIQ_EHIP;
 }
 
 biq_status biq_quantize(const float* W, uint8_t* K, float* alpha, int m, int n, int q, void* stream) {
@@ -842,20 +629,9 @@ biq_status biq_quantize(const float* W, uint8_t* K, float* alpha, int m, int n, 
     if (!aligned(K, 16) || !aligned(W, 4) || !aligned(alpha, 4)) return BIQ_EINVAL;
     if (n > kQuantMaxN) return BIQ_EUNSUPPORTED;  // a row's residual is kept in the registers of one workgroup
     const int stride_dw = (int)(biq_key_row_stride(n) / 4);
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    uint32_t* Kd = reinterpret_cast<uint32_t*>(K);
-#define BIQ_QUANT_CASE(EPT, WPR)                                                                   \
-    hipLaunchKernelGGL((quantize_wave_kernel<EPT, WPR>), dim3((m + (4 / WPR) - 1) / (4 / WPR)),   \
-                       dim3(kQuantThreads), 0, s, W, Kd, alpha, m, n, q, stride_dw)
-    if (n <= 64 * 8) BIQ_QUANT_CASE(8, 1);
-    else if (n <= 64 * 16) BIQ_QUANT_CASE(16, 1);
-    else if (n <= 64 * 32) BIQ_QUANT_CASE(32, 1);
-    else if (n <= 64 * 64) BIQ_QUANT_CASE(64, 1);
-    else if (n <= 64 * 128) BIQ_QUANT_CASE(128, 1);
-    else if (n <= 64 * 64 * 4) BIQ_QUANT_CASE(64, 4);    // four waves per row
-    else BIQ_QUANT_CASE(128, 4);
-#undef BIQ_QUANT_CASE
-    return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
+    const hipError_t e = launch_quantize(W, reinterpret_cast<uint32_t*>(K), alpha, m, n, q, stride_dw,
+                                         reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? BIQ_OK : BIQ_EHIP;
 }
 
 biq_status biq_unpack_keys(const uint8_t* K, uint8_t* keys, int m, int n, int q, int mu, void* stream) {
@@ -869,27 +645,9 @@ biq_status biq_unpack_keys16(const uint8_t* K, uint16_t* keys, int m, int n, int
 biq_status biq_build_lut(const float* X, float* LUT, int n, int batch, int mu, void* stream) {
     if (!shape_ok(1, n, 1, batch, mu) || !X || !LUT) return BIQ_EINVAL;
     if (!aligned(X, 4) || !aligned(LUT, 4)) return BIQ_EINVAL;
-    const int C = ceil_div(n, mu);
-    const int HG = mu > 4 ? (1 << (mu - 4)) : 1;
-    const bool vec4 = (batch % 4 == 0) && aligned(LUT, 16);
-    const long long total = (long long)C * HG * (vec4 ? batch / 4 : batch);
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    const unsigned grid = (unsigned)((total + 255) / 256);
-#define BIQ_LUT_CASE(MU)                                                                           \
-    case MU:                                                                                       \
-        if (vec4)                                                                                  \
-            hipLaunchKernelGGL((build_lut_kernel<MU, 4>), dim3(grid), dim3(256), 0, s, X, LUT, n,  \
-                               batch, C);                                                          \
-        else                                                                                       \
-            hipLaunchKernelGGL((build_lut_kernel<MU, 1>), dim3(grid), dim3(256), 0, s, X, LUT, n,  \
-                               batch, C);                                                          \
-        break;
-    switch (mu) {
-        BIQ_LUT_CASE(1) BIQ_LUT_CASE(2) BIQ_LUT_CASE(3) BIQ_LUT_CASE(4) BIQ_LUT_CASE(5)
-        BIQ_LUT_CASE(6) BIQ_LUT_CASE(7) BIQ_LUT_CASE(8) BIQ_LUT_CASE(9) BIQ_LUT_CASE(10)
-    }
-#undef BIQ_LUT_CASE
-    return hipGetLastError() == hipSuccess ? BIQ_OK : BIQ_EHIP;
+    const hipError_t e = launch_build_lut(mu, X, LUT, n, batch, ceil_div(n, mu),
+                                          reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? BIQ_OK : BIQ_EHIP;
 }
 
 biq_status biq_query(const uint8_t* K, const float* alpha, const float* LUT, float* Y, int m, int n,

@@ -73,17 +73,19 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_wave_kernel(const floa
 #pragma unroll
         for (int t = 0; t < EPT; ++t) {
             const bool valid = t < nvalid;
-            const unsigned long long mask = __ballot(valid && !(r[t] < 0.0f));
-            // r -= copysign(a, r), with sign(0) = +1: -0.0 never occurs (x - x = +0.0)
-            const float rn = r[t] - __uint_as_float((__float_as_uint(r[t]) & 0x80000000u) | __float_as_uint(a));
+            // one predicate decides the code and the residual update: b = -1 iff r < 0, so that
+            // r = +0.0 and r = -0.0 (a weight may be -0.0) both take b = +1 and r - alpha (Eq. 1
+            // with sign(0) = +1)
+            const bool neg = r[t] < 0.0f;
+            const unsigned long long mask = __ballot(valid && !neg);
+            const float rn = neg ? r[t] + a : r[t] - a;
             r[t] = valid ? rn : 0.0f;
-            // v_writelane_b32: the (wave-uniform) mask halves go into lane t of the keep registers.
-            // The mask comes from a VALU compare; the assembler text is not seen by the compiler's
-            // hazard recogniser, hence the explicit wait states before the first read (one statement for
-            // both halves, so that neither can be scheduled ahead of the wait).
-            asm("s_nop 4\n\tv_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
-                : "+v"(keep_lo[t >> 6]), "+v"(keep_hi[t >> 6])
-                : "s"((uint32_t)mask), "s"((uint32_t)(mask >> 32)), "n"(t & 63));
+            // the (wave-uniform) mask halves go into lane t of the keep registers: a compare and two
+            // selects, all visible to the compiler's hazard handling (this toolchain has no builtin
+            // for v_writelane_b32)
+            const bool mine = lane == (t & 63);
+            keep_lo[t >> 6] = mine ? (int)(uint32_t)mask : keep_lo[t >> 6];
+            keep_hi[t >> 6] = mine ? (int)(uint32_t)(mask >> 32) : keep_hi[t >> 6];
         }
 #pragma unroll
         for (int u = 0; u < (EPT + 63) / 64; ++u) {

@@ -14,7 +14,7 @@
 // One tile per workgroup; a row wider than a tile is split over workgroups (partial sums).
 #pragma once
 
-#include "biq_gemv8.h"
+#include "biq_gemv8h.h"
 
 namespace biq {
 

@@ -136,8 +136,11 @@ LARGE = [("cfg4_sq4096_q3_b32", [8]), ("cfg5_ffn_up_q2_b128", [4, 6, 8]), ("cfg5
 
 
 @pytest.mark.parametrize("name,mus", LARGE)
-def test_gemm_parity_large_configs_sampled_rows(biq, oracle, name, mus):
-    """Full-size launches; the oracle computes a sample of output rows one by one."""
+def test_gemm_parity_large_configs_every_element(biq, oracle, name, mus):
+    """Full-size launches of the three large configurations, every element of Y and of K against
+    the oracle (Eq. 2 with W reconstructed, all rows: seconds to tens of seconds on one core,
+    computed once per configuration), for the library's default plan and for the lookup-table
+    kernels, for every mu of the sweep, in the launch configuration bench.py times."""
     import torch
     from paper_2005_09904_amd.workloads import CONFIGS, make_inputs
 
@@ -146,24 +149,17 @@ def test_gemm_parity_large_configs_sampled_rows(biq, oracle, name, mus):
     Bd, ad, Xd = device_inputs(B, alpha, X)
     K = gpu_pack(biq, Bd, w.mu)
     del Bd
-    rows = np.unique(np.concatenate([
-        np.array([0, 1, w.m - 1, w.m // 2]),
-        np.random.default_rng(w.seed).integers(0, w.m, size=96)])).astype(np.int64)
-    ref = oracle.gemm_dense(B, alpha, X, rows=rows)
-    bitmap_rows = oracle.pack_bitmap(B[:, rows, :])
-    Kh = K.cpu().numpy().reshape(w.q, w.m, -1)
-    assert np.array_equal(Kh[:, rows, :], bitmap_rows)
+    _say("oracle gemm_dense %s, all %d rows" % (name, w.m))
+    ref = oracle.gemm_dense(B, alpha, X)
+    assert np.array_equal(K.cpu().numpy().reshape(w.q, w.m, -1), oracle.pack_bitmap(B))
     for mu in mus:
-        # the default plan (for these sizes: keys unpacked into the matrix cores) and the
-        # lookup-table kernels, both in the launch configuration bench.py times
         default = biq.biq_plan_get(w.m, w.n, w.q, w.batch, mu)
         lut = biq.biq_plan_get_lut(w.m, w.n, w.q, w.batch, mu)
         for plan in ([None, lut] if default.kernel != lut.kernel else [None]):
             kname = biq.biq_kernel_name((plan or default).kernel)
-            _say("gemm %s mu=%d %s (sampled rows)" % (name, mu, kname))
+            _say("gemm %s mu=%d %s (every element)" % (name, mu, kname))
             Y = gpu_gemm(biq, K, ad, Xd, w.m, w.n, w.q, mu, plan=plan).cpu().numpy()
-            assert np.all(np.isfinite(Y))
-            assert_within_tolerance(Y[:, rows], ref, alpha[:, rows], X, "%s mu=%d %s" % (name, mu, kname))
+            assert_within_tolerance(Y, ref, alpha, X, "%s mu=%d %s" % (name, mu, kname))
     torch.cuda.empty_cache()
 
 
@@ -423,19 +419,18 @@ def test_unpack_mfma_does_not_depend_on_mu_and_default_plan_picks_it(biq, oracle
     B, alpha, X = _rand_inputs(m, n, q, b, seed=99)
     B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
     K = gpu_pack(biq, B_dev)
-    rows = np.unique(np.random.default_rng(5).integers(0, m, size=200)).astype(np.int64)
-    ref = oracle.gemm_dense(B, alpha, X, rows=rows)
+    ref = oracle.gemm_dense(B, alpha, X)
     first = None
     for mu in (8, 6, 4, 1):
         assert biq.biq_kernel_name(biq.biq_plan_get(m, n, q, b, mu).kernel) == "unpack_mfma"
         assert biq.biq_kernel_name(biq.biq_plan_get_lut(m, n, q, b, mu).kernel) != "unpack_mfma"
         Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, mu)
-        assert_within_tolerance(Y.cpu().numpy()[:, rows], ref, alpha[:, rows], X, what="unpack_mfma mu=%d" % mu)
+        assert_within_tolerance(Y.cpu().numpy(), ref, alpha, X, what="unpack_mfma mu=%d" % mu)
         first = Y if first is None else first
         assert torch_equal(first, Y)
     # the table kernels on the same inputs, through an explicit plan
     Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=biq.biq_plan_get_lut(m, n, q, b, 8))
-    assert_within_tolerance(Y.cpu().numpy()[:, rows], ref, alpha[:, rows], X, what="lut plan")
+    assert_within_tolerance(Y.cpu().numpy(), ref, alpha, X, what="lut plan")
 
 
 def torch_equal(a, b):

@@ -104,6 +104,19 @@ def test_exactly_representable_rows_are_recovered(oracle):
     assert np.all(R[2] == 0.0)
 
 
+def test_zero_of_either_sign_takes_plus_one(oracle):
+    """Eq. 1 with sign(0) = +1: a weight that is +0.0 or -0.0 (a pruned weight computed as
+    negative * 0) gets b = +1, and its residual continues as 0 - alpha.  Hand-worked row
+    w = (-0, +0, 4, -4): alpha_1 = 2, b_1 = (+,+,+,-), r = (-2,-2,2,-2), alpha_2 = 2, b_2 = (-,-,+,-)."""
+    w = np.array([[-0.0, 0.0, 4.0, -4.0]], dtype=np.float32)
+    assert np.signbit(w[0, 0]) and not np.signbit(w[0, 1])
+    B, alpha, R = oracle.quantize_greedy(w, 2, with_residuals=True)
+    assert alpha[:, 0].tolist() == [2.0, 2.0]
+    assert B[0, 0].tolist() == [1, 1, 1, -1]
+    assert R[1, 0].tolist() == [-2.0, -2.0, 2.0, -2.0]
+    assert B[1, 0].tolist() == [-1, -1, 1, -1]
+
+
 def test_argument_errors(oracle):
     with pytest.raises(oracle.OracleError):
         oracle.quantize_greedy(np.zeros((2, 3), np.float32), 0)
