@@ -214,6 +214,28 @@ biq_status biq_gemm_ex(const uint8_t* K, const float* alpha, const float* X, flo
                        int m, int n, int q, int batch, int mu, const biq_plan* plan,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * biq_gemm for callers that cannot allocate or hand over device memory for a workspace: code
+ * whose launches are being captured into a HIP graph, serving loops with a fixed memory plan,
+ * harnesses that forbid hipMalloc.  Same arguments, plan, kernels and results (bit for bit) as
+ * biq_gemm, but the workspace is a fixed buffer of biq_noalloc_scratch_bytes() = 32 MiB of device
+ * memory inside the library's own code object (one copy per GPU, held until the process ends).
+ * Nothing is allocated or freed, by the library or by the runtime on its behalf.
+ *   - BIQ_EWORKSPACE if biq_workspace_bytes(m, n, q, batch, mu) exceeds that size (no kernel is
+ *     launched; all five benchmark configurations fit): use biq_gemm with a caller workspace.
+ *   - Every call on one GPU uses that GPU's single buffer: calls that may overlap in time on one
+ *     GPU (different streams, different host threads) race on it and must be serialised by the
+ *     caller.  Calls on different GPUs are independent.  The buffer's contents after a call are
+ *     undefined; no call relies on what an earlier one left there.
+ *   - biq_init() looks the buffer's device address up for the current device (once per device;
+ *     no allocation).  Calling it is optional - biq_gemm_noalloc does the same on its first call
+ *     on a device - but a caller about to start a graph capture should call it beforehand.
+ */
+biq_status biq_init(void);
+size_t biq_noalloc_scratch_bytes(void);
+biq_status biq_gemm_noalloc(const uint8_t* K, const float* alpha, const float* X, float* Y,
+                            int m, int n, int q, int batch, int mu, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

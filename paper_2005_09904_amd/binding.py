@@ -17,7 +17,8 @@ EXPORTS = [
     "biq_status_str", "biq_version", "biq_key_row_stride", "biq_packed_bytes", "biq_num_chunks",
     "biq_lut_bytes", "biq_workspace_bytes", "biq_plan_get", "biq_plan_get_lut", "biq_plan_check", "biq_plan_workspace_bytes",
     "biq_kernel_name", "biq_pack", "biq_unpack_keys", "biq_build_lut", "biq_query", "biq_gemm",
-    "biq_gemm_ex", "biq_quantize", "biq_unpack_keys16",
+    "biq_gemm_ex", "biq_quantize", "biq_unpack_keys16", "biq_init", "biq_noalloc_scratch_bytes",
+    "biq_gemm_noalloc",
 ]
 
 
@@ -78,6 +79,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "biq_gemm": (I, [P, P, P, P, I, I, I, I, I, P, Z, P]),
         "biq_gemm_ex": (I, [P, P, P, P, I, I, I, I, I, PL, P, Z, P]),
         "biq_quantize": (I, [P, P, P, I, I, I, P]),
+        "biq_init": (I, []),
+        "biq_noalloc_scratch_bytes": (Z, []),
+        "biq_gemm_noalloc": (I, [P, P, P, P, I, I, I, I, I, P]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -195,6 +199,19 @@ def biq_gemm(K, alpha, X, Y, m: int, n: int, q: int, batch: int, mu: int, worksp
              stream=None) -> None:
     _check(load_library().biq_gemm(_ptr(K), _ptr(alpha), _ptr(X), _ptr(Y), m, n, q, batch, mu,
                                    _ptr(workspace), _nbytes(workspace), _stream(stream)), "biq_gemm")
+
+
+def biq_init() -> None:
+    _check(load_library().biq_init(), "biq_init")
+
+
+def biq_noalloc_scratch_bytes() -> int:
+    return load_library().biq_noalloc_scratch_bytes()
+
+
+def biq_gemm_noalloc(K, alpha, X, Y, m: int, n: int, q: int, batch: int, mu: int, stream=None) -> None:
+    _check(load_library().biq_gemm_noalloc(_ptr(K), _ptr(alpha), _ptr(X), _ptr(Y), m, n, q, batch, mu,
+                                           _stream(stream)), "biq_gemm_noalloc")
 
 
 class PreparedGemm:

@@ -534,6 +534,33 @@ biq_status unpack_keys_any(const uint8_t* K, KEY* keys, int m, int n, int q, int
     return e == hipSuccess ? BIQ_OK : BIQ_EHIP;
 }
 
+// ---- the allocation-free entry point's scratch buffer -------------------------------------
+// Workspace of biq_gemm_noalloc: device memory that belongs to the library's code object, one
+// copy per GPU, held until the process ends.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; the device address is looked up once per device and kept.
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_addr[kMaxDevices];  // device address of `scratch` on each device, 0 = not looked up yet
+
+// Device address of the current device's copy of `scratch`.
+hipError_t scratch_address(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* p = __atomic_load_n(&g_scratch_addr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        __atomic_store_n(&g_scratch_addr[dev], p, __ATOMIC_RELEASE);  // racing first calls store the same value
+    }
+    *out = p;
+    return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -668,6 +695,28 @@ biq_status biq_gemm_ex(const uint8_t* K, const float* alpha, const float* X, flo
     if (!plan) return BIQ_EINVAL;
     return run_query(true, K, alpha, X, nullptr, Y, m, n, q, batch, mu, plan, workspace,
                      workspace_bytes, stream);
+}
+
+biq_status biq_init(void) {
+    void* p = nullptr;
+    return scratch_address(&p) == hipSuccess ? BIQ_OK : BIQ_EHIP;
+}
+
+size_t biq_noalloc_scratch_bytes(void) { return kScratchBytes; }
+
+biq_status biq_gemm_noalloc(const uint8_t* K, const float* alpha, const float* X, float* Y, int m, int n,
+                            int q, int batch, int mu, void* stream) {
+    if (!shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
+    biq_plan pl;
+    if (!plan_default(pl, m, n, q, batch, mu, false)) return BIQ_EUNSUPPORTED;
+    const size_t need = plan_workspace(pl, m, batch);
+    if (need > kScratchBytes) return BIQ_EWORKSPACE;  // beyond the fixed buffer: use biq_gemm with a workspace
+    void* ws = nullptr;
+    if (need > 0 && scratch_address(&ws) != hipSuccess) return BIQ_EHIP;
+    // Every kernel writes the part of the workspace it later reads (split input, partial sums) in
+    // full before reading it, so what an earlier call left there does not matter and nothing is
+    // cleared.
+    return run_query(true, K, alpha, X, nullptr, Y, m, n, q, batch, mu, &pl, ws, need, stream);
 }
 
 }  // extern "C"
