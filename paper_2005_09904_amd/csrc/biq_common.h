@@ -148,6 +148,24 @@ __device__ __forceinline__ void load_chunk8(const float* __restrict__ X, int n, 
     }
 }
 
+// The same for input vector 0 in two halves, for rows that allow 128-bit loads (n % 4 == 0, X
+// 16-byte aligned), without branches: load_chunk8_raw issues both loads unconditionally from
+// addresses clamped into the row (so the loads of a prefetch stay in flight together and the
+// compiler can count them: s_waitcnt vmcnt(N) instead of a full drain), chunk8_zero_tail later
+// zeroes the elements that lie past the row.  n >= 4.
+__device__ __forceinline__ void load_chunk8_raw(const float* __restrict__ X, int n, int c, float (&x)[8]) {
+    const float4* xv = reinterpret_cast<const float4*>(X);
+    const int q4 = n >> 2;  // float4 pieces of the row, >= 1
+    const float4 a0 = xv[min(2 * c, q4 - 1)], a1 = xv[min(2 * c + 1, q4 - 1)];
+    x[0] = a0.x; x[1] = a0.y; x[2] = a0.z; x[3] = a0.w;
+    x[4] = a1.x; x[5] = a1.y; x[6] = a1.z; x[7] = a1.w;
+}
+
+__device__ __forceinline__ void chunk8_zero_tail(int n, int c, float (&x)[8]) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = (8 * c + j < n) ? x[j] : 0.0f;
+}
+
 // x[j] = X[col][MU*c + j] for j < MU and inside the row, else 0
 template <int MU>
 __device__ __forceinline__ void load_chunk_x(const float* __restrict__ X, int n, int batch, int col,

@@ -57,20 +57,42 @@ __device__ __forceinline__ uint32_t lds_address_of(const void* p) {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Tables of chunks [c0, c0 + 128) for one input vector, built from X straight into the LDS
-// layout above.  One job = (chunk, 32 keys): 128 x 8 = 1024 jobs; consecutive threads write
-// consecutive banks.
+// Table build of a 128-chunk tile for one input vector, from X straight into the LDS layout
+// above.  One job = (chunk, 32 keys): 128 x 8 = 1024 jobs; consecutive jobs write consecutive
+// banks.  gemv8_job_x fetches the job's 8 inputs, gemv8_job_build turns them into 32 entries.
+__device__ __forceinline__ int gemv8_job_chunk(int job) {
+    const int L = job & 7, e = (job >> 3) & 3, td = (job >> 5) & 3;
+    return 16 * L + 4 * td + e;
+}
+
+// The job's 8 inputs, requested ahead of time (rows that allow 128-bit loads only).  Raw: elements
+// past the row still hold clamped reads; gemv8_job_build zeroes them.
+__device__ __forceinline__ void gemv8_job_x_ahead(const QueryParams& p, int c0, int job, float (&x)[8]) {
+    load_chunk8_raw(p.X, p.n, c0 + gemv8_job_chunk(job), x);
+}
+
+__device__ __forceinline__ void gemv8_job_build(const QueryParams& p, char* lds_bytes, int c0, int job,
+                                                float (&x)[8]) {
+    const int L = job & 7, e = (job >> 3) & 3, td = (job >> 5) & 3, hq = job >> 7;
+    chunk8_zero_tail(p.n, c0 + gemv8_job_chunk(job), x);
+    float ent[32];
+    table32(x, (uint32_t)hq, ent);
+    char* dst = lds_bytes + gemv8_slot_offset(L, td, e) + (hq * 32) * 256;
+#pragma unroll
+    for (int l = 0; l < 32; ++l) *reinterpret_cast<float*>(dst + l * 256) = ent[l];
+}
+
+__device__ __forceinline__ bool x_rows_vectorizable(const QueryParams& p) {
+    return ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+}
+
 __device__ __forceinline__ void gemv8_build_tile(const QueryParams& p, char* lds_bytes, int c0,
                                                  int tid, int nthreads) {
-    const bool vec_ok = ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+    const bool vec_ok = x_rows_vectorizable(p);
     for (int job = tid; job < 1024; job += nthreads) {
-        const int L = job & 7, e = (job >> 3) & 3, td = (job >> 5) & 3, hq = job >> 7;
-        float x[8], ent[32];
-        load_chunk8(p.X, p.n, 1, 0, c0 + 16 * L + 4 * td + e, vec_ok, x);
-        table32(x, (uint32_t)hq, ent);
-        char* dst = lds_bytes + gemv8_slot_offset(L, td, e) + (hq * 32) * 256;
-#pragma unroll
-        for (int l = 0; l < 32; ++l) *reinterpret_cast<float*>(dst + l * 256) = ent[l];
+        float x[8];
+        load_chunk8(p.X, p.n, 1, 0, c0 + gemv8_job_chunk(job), vec_ok, x);
+        gemv8_job_build(p, lds_bytes, c0, job, x);
     }
 }
 
@@ -162,6 +184,7 @@ __global__ __launch_bounds__(MAXT) void gemv8_kernel(const QueryParams p) {
 
     const uint32_t stride_bytes = (uint32_t)p.stride_dw * 4u;
     const int nrows = r1 - r0;
+    if (nrows <= 0) return;  // (uneven XCD shares can leave the last workgroups without rows)
 
     if (p.row_mode == 1) {
         // ---- latency mode: one tile per workgroup, one step of 8 rows per wave at a time.  The
@@ -207,65 +230,98 @@ __global__ __launch_bounds__(MAXT) void gemv8_kernel(const QueryParams p) {
     // ---- throughput mode.  Rows are handled in blocks of 64: in step t (0..7) row group g of
     // the wave reads row 8*g + t of the block, and the lane with L == t keeps the row's sum, so
     // that after the 8 steps lane j holds row j of the block: alpha and Y are accessed coalesced.
+    // Block b of a tile goes to wave b mod nwaves; every wave runs the same number of block
+    // iterations per tile (blocks that do not exist are skipped, their loads read one cache line).
+    // All loads are issued unconditionally, from addresses clamped into the row block: with loads
+    // behind per-lane conditions the compiler cannot count the requests in flight and drains them
+    // (s_waitcnt vmcnt(0)) where it should wait for the oldest only.  So the ring of PD steps per
+    // wave really stays in flight, runs on across tile boundaries, and the next tile's inputs are
+    // fetched a tile ahead.
     const int nblk = (nrows + 63) >> 6;
-    // ring of PD steps in flight per wave (PD * Q KiB); fewer for many planes to stay inside
-    // 128 VGPRs
+    const int iters = (nblk + nwaves - 1) / nwaves;  // block iterations per wave and tile, >= 1
+    // PD * Q KiB in flight per wave; fewer for many planes to stay inside 128 VGPRs
     constexpr int PD = (Q <= 2 || MAXT <= 512) ? 4 : (Q == 3 ? 2 : 1);
-    for (int tile = tile0; tile < tile1; ++tile) {
-        const bool have_keys = (uint32_t)(tile * 128 + L * 16) < stride_bytes;
-        const char* kbase[Q];
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const char* kbase[Q];
+    const char* abase[Q];
+#pragma unroll
+    for (int i = 0; i < Q; ++i) {
+        kbase[i] = reinterpret_cast<const char*>(p.K) + ((size_t)i * p.m + r0) * stride_bytes;
+        abase[i] = reinterpret_cast<const char*>(p.alpha + (size_t)i * p.m + r0);
+    }
+    float* const obase = p.out + (size_t)sp * p.m + r0;
+    const uint32_t last_row = (uint32_t)(nrows - 1);
+    auto load_iter = [&](int tile, int bk, int t, u32x4 (&k)[Q]) {
+        const bool there = bk < nblk && tile < tile1;  // the same for the whole wave
+        const uint32_t row = min((uint32_t)(64 * bk + 8 * rsub + t), last_row);
+        const uint32_t seg = min((uint32_t)(tile * 128 + L * 16), stride_bytes - 16u);
+        const uint32_t voff = there ? row * stride_bytes + seg : 0u;
 #pragma unroll
         for (int i = 0; i < Q; ++i)
-            kbase[i] = reinterpret_cast<const char*>(p.K) +
-                       ((size_t)i * p.m + r0) * stride_bytes + (size_t)tile * 128;
+            k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kbase[i] + voff));
+    };
+    const bool x_ahead = FUSED && nthreads == 1024 && x_rows_vectorizable(p);
+    float xa[8];
+    if (x_ahead) gemv8_job_x_ahead(p, tile0 * kGemvTileChunks, tid, xa);
+    auto build = [&](int tile) {
+        if constexpr (FUSED) {
+            if (x_ahead) gemv8_job_build(p, lds_bytes, tile * kGemvTileChunks, tid, xa);
+            else gemv8_build_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
+            if (x_ahead && tile + 1 < tile1) gemv8_job_x_ahead(p, (tile + 1) * kGemvTileChunks, tid, xa);
+        } else {
+            gemv8_copy_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
+        }
+    };
 
-        auto load_iter = [&](int bk, int t, u32x4 (&k)[Q]) {
-            const uint32_t row = (uint32_t)(64 * bk + 8 * rsub + t);  // relative to r0
-            const bool ok = have_keys && bk < nblk && (int)row < nrows;
-            const uint32_t voff = row * stride_bytes + (uint32_t)(16 * L);
+    // Start-up: one step of keys per wave and the first tile's inputs are requested, the tables
+    // are built, then the rest of the ring is requested.  (A CU's address unit takes about 20 clocks
+    // per 128-bit wave load: the whole ring first would put the table build 2 us behind it.)
+    u32x4 buf[PD][Q];
+    load_iter(tile0, wave_u, 0, buf[0]);
+    build(tile0);
+    __syncthreads();
 #pragma unroll
-            for (int i = 0; i < Q; ++i) {
-                k[i] = (u32x4){0u, 0u, 0u, 0u};
-                if (ok) k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kbase[i] + voff));
-            }
-        };
+    for (int s = 1; s < PD; ++s) load_iter(tile0, wave_u, s, buf[s]);
 
-        // the first steps' keys are requested before the tables are (re)built
-        u32x4 buf[PD][Q];
-        int bk = wave;
-#pragma unroll
-        for (int s = 0; s < PD; ++s) load_iter(bk, s, buf[s]);
-
-        if (tile != tile0) __syncthreads();  // every wave is done with the previous tables
-        if constexpr (FUSED) gemv8_build_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
-        else gemv8_copy_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
-        __syncthreads();
-
-        for (; bk < nblk; bk += nwaves) {
+    for (int tile = tile0; tile < tile1; ++tile) {
+        int it = 0;
+        do {
+            const int bk = wave_u + it * nwaves;
+            const bool last = it + 1 >= iters;
+            const int next_bk = last ? wave_u : bk + nwaves;
+            const int next_tile = last ? tile + 1 : tile;
             const int row_l = 64 * bk + lane;  // the row this lane finishes, relative to r0
-            const bool row_ok = row_l < nrows;
             float al[Q], keep[Q];
 #pragma unroll
             for (int i = 0; i < Q; ++i) {
-                al[i] = row_ok ? p.alpha[(size_t)i * p.m + r0 + row_l] : 0.0f;
+                al[i] = *reinterpret_cast<const float*>(abase[i] + 4u * min((uint32_t)row_l, last_row));
                 keep[i] = 0.0f;
             }
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
+                if (bk < nblk) {  // the same for the whole wave
 #pragma unroll
-                for (int i = 0; i < Q; ++i) {
-                    const float s = reduce8(lookup16(buf[t % PD][i]));
-                    keep[i] = (L == t) ? s : keep[i];
+                    for (int i = 0; i < Q; ++i) {
+                        const float sum = reduce8(lookup16(buf[t % PD][i]));
+                        keep[i] = (L == t) ? sum : keep[i];
+                    }
                 }
-                if (t + PD < 8) load_iter(bk, t + PD, buf[t % PD]);
-                else load_iter(bk + nwaves, t + PD - 8, buf[t % PD]);
+                if (t + PD < 8) load_iter(tile, bk, t + PD, buf[t % PD]);
+                else load_iter(next_tile, next_bk, t + PD - 8, buf[t % PD]);
             }
-            float y = 0.0f;
+            if (bk < nblk) {
+                float y = 0.0f;
 #pragma unroll
-            for (int i = 0; i < Q; ++i) y = fmaf(al[i], keep[i], y);
-            if (tile != tile0) y += yacc[row_l];
-            if (tile + 1 < tile1) yacc[row_l] = y;
-            else if (row_ok) p.out[(size_t)sp * p.m + r0 + row_l] = y;
+                for (int i = 0; i < Q; ++i) y = fmaf(al[i], keep[i], y);
+                if (tile != tile0) y += yacc[row_l];
+                if (tile + 1 < tile1) yacc[row_l] = y;
+                else if (row_l < nrows) obase[row_l] = y;
+            }
+        } while (++it < iters);
+        if (tile + 1 < tile1) {
+            __syncthreads();  // every wave is done with these tables
+            build(tile + 1);
+            __syncthreads();
         }
     }
 }

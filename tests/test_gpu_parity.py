@@ -252,10 +252,25 @@ def test_explicit_plans_give_the_same_result(biq, oracle):
                  (4, 512, 256, 1, 1, 130, 1),
                  # ... one row per wave at a time
                  (4, 1024, 256, 1, 1, 8, 2), (4, 256, 256, 1, 1, 700, 2), (4, 64, 256, 1, 1, 5, 2),
-                 (4, 1024, 256, 1, 1, 16, 2)]:
+                 (4, 1024, 256, 1, 1, 16, 2),
+                 # throughput mode, several tiles per workgroup, ragged block counts per wave
+                 (1, 1024, 128, 1, 3, 700, 0), (1, 1024, 128, 1, 3, 64, 0), (1, 1024, 128, 1, 2, 1000, 0),
+                 (1, 256, 128, 1, 3, 333, 0), (1, 64, 128, 1, 3, 9, 0)]:
         _say("plan " + str(spec))
         Y = gpu_gemm(biq, K, ad, Xd, m, n, 3, mu, plan=_plan(biq, *spec)).cpu().numpy()
         assert_within_tolerance(Y, ref, alpha, X, "plan")
+    # throughput mode for every plane count (4 planes: both register budgets), several tiles per
+    # workgroup, inputs fetched a tile ahead (1024 threads, n a multiple of 4) and not (n = 5001)
+    for q, n2 in ((1, 5000), (2, 5001), (4, 5000)):
+        B, alpha, X = _rand_inputs(2000, n2, q, 1, 7002 + q)
+        Bd, ad, Xd = device_inputs(B, alpha, X)
+        K = gpu_pack(biq, Bd, mu)
+        ref = oracle.gemm_dense(B, alpha, X)
+        for spec in [(1, 1024, 128, 1, 5, 8, 0), (1, 512, 128, 1, 5, 72, 0), (1, 1024, 128, 1, 2, 520, 0),
+                     (1, 1024, 128, 1, 5, 2000, 0)]:
+            _say("plan q=%d n=%d " % (q, n2) + str(spec))
+            Y = gpu_gemm(biq, K, ad, Xd, 2000, n2, q, mu, plan=_plan(biq, *spec)).cpu().numpy()
+            assert_within_tolerance(Y, ref, alpha, X, "plan")
 
 
 @pytest.mark.parametrize("q", [1, 2, 3, 4, 5])
