@@ -73,56 +73,122 @@ class Problem:
         self.prepared[self.calls % self.copies]()
         self.calls += 1
 
+    def touch_all(self, torch):
+        """One untimed call on every key matrix of the rotation (first use of a buffer is not what
+        a step is meant to measure), then back to the start of the rotation."""
+        for call in self.prepared:
+            call()
+        torch.cuda.synchronize()
+        self.calls = 0
 
-def time_steps(torch, prob: Problem, steps: int, warmup: int):
-    """Returns (wall seconds, HIP-event seconds) for exactly `steps` calls after `warmup` calls.
-    The events are recorded on the stream the kernels are launched on (torch's current one)."""
+
+class Timing:
+    """Per-call times over the timed regions of one workload: every region is exactly `steps`
+    calls between two HIP events on the stream the kernels run on, with a synchronisation on both
+    sides.  median / min / mean are over the regions' (event time / steps); `wall` is the host
+    clock around the first region / steps (it includes the cost of the synchronisation itself)."""
+
+    def __init__(self, per_region, wall):
+        self.regions = len(per_region)
+        self.median = float(sorted(per_region)[len(per_region) // 2])
+        self.min = float(min(per_region))
+        self.mean = float(sum(per_region) / len(per_region))
+        self.wall = wall
+
+    def as_dict(self):
+        return {"median_us": self.median * 1e6, "min_us": self.min * 1e6, "mean_us": self.mean * 1e6,
+                "wall_us_first_region": self.wall * 1e6, "regions": self.regions}
+
+
+def time_steps(torch, prob: Problem, steps: int, warmup: int, regions: int = 9) -> Timing:
+    """`warmup` untimed calls, then `regions` timed regions of exactly `steps` calls each.  One
+    region is what the command line asks for; the repetitions give the median and the minimum."""
     for _ in range(warmup):
         prob.step()
     torch.cuda.synchronize()
-    ev0 = torch.cuda.Event(enable_timing=True)
-    ev1 = torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(steps):
-        prob.step()
-    ev1.record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    return t1 - t0, ev0.elapsed_time(ev1) * 1e-3
+    per_region = []
+    wall = None
+    for _ in range(regions):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            prob.step()
+        e1.record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        if wall is None:
+            wall = (t1 - t0) / steps
+        per_region.append(e0.elapsed_time(e1) * 1e-3 / steps)
+    return Timing(per_region, wall)
 
 
-def summarize(w, seconds_per_call: float):
-    return {
+def summarize(w, t: Timing):
+    """Rates of one workload from the median per-call time (min and mean beside it)."""
+    sec = t.median
+    row = {
         "workload": w.name,
         "m": w.m, "n": w.n, "q": w.q, "batch": w.batch, "mu": w.mu,
-        "us_per_call": seconds_per_call * 1e6,
+        "us_per_call": sec * 1e6,
+        "min_us_per_call": t.min * 1e6,
+        "mean_us_per_call": t.mean * 1e6,
+        "wall_us_per_call_first_region": t.wall * 1e6,
+        "timed_regions": t.regions,
         "algorithmic_bytes": w.algorithmic_bytes,
-        "achieved_GBps": w.algorithmic_bytes / seconds_per_call / 1e9,
-        "hbm_frac": w.algorithmic_bytes / seconds_per_call / 1e9 / HBM_PEAK_GBPS,
-        "weight_GBps": w.key_bytes / seconds_per_call / 1e9,
-        "effective_GOPS": w.dense_equiv_ops / seconds_per_call / 1e9,
-        "lookups_per_s": w.lookups / seconds_per_call,
+        "achieved_GBps": w.algorithmic_bytes / sec / 1e9,
+        "hbm_frac": w.algorithmic_bytes / sec / 1e9 / HBM_PEAK_GBPS,
+        "weight_GBps": w.key_bytes / sec / 1e9,
+        "effective_GOPS": w.dense_equiv_ops / sec / 1e9,
+        "lookups_per_s": w.lookups / sec,
     }
+    return row
 
 
-def cpu_baseline(w, host_inputs, budget_s: float = 10.0):
-    """The oracle's LUT path (Algorithm 2, single thread, fp64) timed on this host."""
+def read_profiled_traffic(algorithmic_bytes: int):
+    """HBM bytes per launch of the roofline kernel from the committed counter summary
+    (profiles/gemv8_q2_hbm_regime_counters.md: two rocprofv3 --pmc runs, scaled by a copy of known
+    size), with the commit it was profiled at.  None if the summary is missing or is for another
+    workload: the figure is a profile's, not something this run measures."""
+    import re
+
+    path = os.path.join(ROOT, "profiles", "gemv8_q2_hbm_regime_counters.md")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None, None
+    m_traffic = re.search(r"traffic_bytes_per_launch:\s*(\d+)", text)
+    m_algo = re.search(r"algorithmic_bytes_per_launch:\s*(\d+)", text)
+    m_commit = re.search(r"profiled_at_commit:\s*([0-9a-f]{7,40})", text)
+    if not (m_traffic and m_algo) or int(m_algo.group(1)) != algorithmic_bytes:
+        return None, None
+    return float(m_traffic.group(1)), (m_commit.group(1) if m_commit else None)
+
+
+def cpu_baseline(w, host_inputs, budget_s: float = 8.0):
+    """The oracle as it stands, single thread, fp64, timed on this host on the whole headline
+    workload: its lookup-table path (Algorithm 2) and its dense definition (Eq. 2)."""
     import numpy as np
     import oracle
 
     B, alpha, X = host_inputs
     keys = oracle.pack_keys(B, w.mu)
-    t0 = time.perf_counter()
-    oracle.gemm_lut(keys, alpha, X, w.mu)
-    first = time.perf_counter() - t0
-    reps = int(max(3, min(200, budget_s / max(first, 1e-6))))
-    times = []
-    for _ in range(reps):
+
+    def median_time(fn):
         t0 = time.perf_counter()
-        oracle.gemm_lut(keys, alpha, X, w.mu)
-        times.append(time.perf_counter() - t0)
-    med = float(np.median(times))
+        fn()
+        first = time.perf_counter() - t0
+        reps = int(max(3, min(200, budget_s / max(first, 1e-6))))
+        times = []
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            fn()
+            times.append(time.perf_counter() - t0)
+        return float(np.median(times)), reps
+
+    lut_s, lut_reps = median_time(lambda: oracle.gemm_lut(keys, alpha, X, w.mu))
+    dense_s, dense_reps = median_time(lambda: oracle.gemm_dense(B, alpha, X))
     cpu_model = "unknown"
     try:
         with open("/proc/cpuinfo") as f:
@@ -133,12 +199,16 @@ def cpu_baseline(w, host_inputs, budget_s: float = 10.0):
     except OSError:
         pass
     return {
-        "value": w.algorithmic_bytes / med / 1e9,
+        "value": w.algorithmic_bytes / lut_s / 1e9,
         "unit": "GB/s",
         "cores": 1,
         "kind": "oracle",
-        "sample": "whole %s workload, oracle gemm_lut (Algorithm 2, fp64), median of %d calls" % (w.name, reps),
-        "us_per_call": med * 1e6,
+        "sample": "whole %s workload: oracle gemm_lut (Algorithm 2, fp64), median of %d calls; "
+                  "oracle gemm_dense (Eq. 2, fp64) beside it, median of %d calls" % (w.name, lut_reps, dense_reps),
+        "us_per_call": lut_s * 1e6,
+        "gemm_lut_us_per_call": lut_s * 1e6,
+        "gemm_dense_us_per_call": dense_s * 1e6,
+        "gemm_dense_GBps": w.algorithmic_bytes / dense_s / 1e9,
         "host_cpu": cpu_model,
         "host_cores_total": os.cpu_count(),
     }
@@ -167,6 +237,8 @@ def main() -> int:
     import torch
 
     import paper_2005_09904_amd as biq
+    from dataclasses import replace
+
     from paper_2005_09904_amd.workloads import CONFIGS, Workload
 
     if not torch.cuda.is_available():
@@ -193,9 +265,8 @@ def main() -> int:
         copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
         p = Problem(biq, torch, w, copies, real_first=False, plan=plan)
         steps = min(args.steps, 200 if w.lookups < 1e9 else 50)
-        wall, ev = time_steps(torch, p, steps, 5)
-        srow = summarize(w, wall / steps)
-        srow["event_us_per_call"] = ev / steps * 1e6
+        p.touch_all(torch)
+        srow = summarize(w, time_steps(torch, p, steps, 5))
         srow["plan"] = (plan or biq.biq_plan_get(w.m, w.n, w.q, w.batch, w.mu)).as_dict()
         srow["kernel"] = biq.biq_kernel_name(srow["plan"]["kernel"])
         print(json.dumps(srow))
@@ -211,15 +282,18 @@ def main() -> int:
     if args.only in ("all", "headline"):
         copies = (512 * 1024 * 1024) // head.key_bytes + 1
         prob = Problem(biq, torch, head, copies)
-        wall, ev = time_steps(torch, prob, args.steps, args.warmup)
-        head_sum = summarize(head, wall / args.steps)
-        head_sum["event_us_per_call"] = ev / args.steps * 1e6
-        log("headline %s: %.2f us/call wall, %.2f us/call events" %
-            (head.name, head_sum["us_per_call"], head_sum["event_us_per_call"]))
+        prob.touch_all(torch)
+        cold = time_steps(torch, prob, args.steps, args.warmup)
+        head_sum = summarize(head, cold)
+        head_sum["keys"] = "cold: %d packed matrices in rotation, each used once before the warm-up" % copies
+        log("headline %s (cold keys): median %.2f us/call, min %.2f, mean %.2f over %d regions of %d calls; "
+            "host clock of the first region %.2f" %
+            (head.name, cold.median * 1e6, cold.min * 1e6, cold.mean * 1e6, cold.regions, args.steps, cold.wall * 1e6))
         # same buffers every call: keys served from cache
         warm = Problem(biq, torch, head, 1)
-        wwall, _ = time_steps(torch, warm, args.steps, args.warmup)
-        head_sum["warm_us_per_call"] = wwall / args.steps * 1e6
+        wt = time_steps(torch, warm, args.steps, args.warmup)
+        head_sum["warm_keys"] = wt.as_dict()
+        log("headline %s (warm keys): median %.2f us/call, min %.2f" % (head.name, wt.median * 1e6, wt.min * 1e6))
         del warm
 
     # ---- roofline: same kernel, m scaled until keys are 512 MiB per call ----------------------
@@ -228,22 +302,27 @@ def main() -> int:
         big = head.scaled_m(head.m * 512, "cfg2_shape_m1048576_hbm_regime")
         pb = Problem(biq, torch, big, 2, real_first=False)
         rsteps = max(20, min(200, args.steps // 10))
-        rwall, rev = time_steps(torch, pb, rsteps, 5)
-        launch_s = rev / rsteps
+        pb.touch_all(torch)
+        rt = time_steps(torch, pb, rsteps, 5)
+        launch_s = rt.median
         plan = biq.biq_plan_get(big.m, big.n, big.q, big.batch, big.mu)
+        traffic, traffic_commit = read_profiled_traffic(big.algorithmic_bytes)
         roof = {
             "bound": "hbm",
             "achieved": big.algorithmic_bytes / launch_s / 1e9,
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": big.algorithmic_bytes / launch_s / 1e9 / HBM_PEAK_GBPS,
-            # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a 512 MiB device copy),
-            # bytes per launch of this workload: see profiles/gemv8_q2_hbm_regime_counters.md
-            "traffic": 551.6e6 if big.algorithmic_bytes == 549462016 else None,
+            # from profiles/gemv8_q2_hbm_regime_counters.md (rocprofv3 FETCH_SIZE / WRITE_SIZE scaled
+            # by a copy of known size), not measured in this run
+            "traffic": traffic,
+            "traffic_source": ("profiles/gemv8_q2_hbm_regime_counters.md @ %s" % traffic_commit) if traffic else None,
             "kernel": biq.biq_kernel_name(plan.kernel),
             "workload": big.name,
             "algorithmic_bytes_per_launch": big.algorithmic_bytes,
             "launch_us": launch_s * 1e6,
+            "launch_us_min": rt.min * 1e6,
+            "launch_us_mean": rt.mean * 1e6,
             "launches_timed": rsteps,
         }
         log("roofline %s: %.1f us/launch, %.0f GB/s (%.1f%% of HBM peak)" %
@@ -255,7 +334,7 @@ def main() -> int:
                 "workload": head.name,
                 "achieved": head_sum["achieved_GBps"],
                 "frac": head_sum["hbm_frac"],
-                "launch_us": head_sum["event_us_per_call"],
+                "launch_us": head_sum["us_per_call"],
                 "note": "1 MiB of keys per call: bounded by launch latency, not by HBM",
             }
 
@@ -276,8 +355,9 @@ def main() -> int:
                 copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
                 p = Problem(biq, torch, w, copies, real_first=False, plan=plan)
                 steps = 200 if w.lookups < 1e9 else 20
-                wall, _ = time_steps(torch, p, steps, 5)
-                s = summarize(w, wall / steps)
+                p.touch_all(torch)
+                t = time_steps(torch, p, steps, 5)
+                s = summarize(w, t)
                 s["key_copies_in_rotation"] = copies
                 s["kernel"] = kname
                 s["default_plan"] = plan is None
@@ -285,11 +365,11 @@ def main() -> int:
                     # dense contraction: 2 flop per weight and input vector, times the three bf16
                     # terms of x, on columns padded to the 32-wide MFMA tile
                     padded = -(-w.batch // 32) * 32
-                    s["mfma_TFLOPs"] = 6.0 * w.q * w.m * w.n * padded / (wall / steps) / 1e12
+                    s["mfma_TFLOPs"] = 6.0 * w.q * w.m * w.n * padded / t.median / 1e12
                     s["mfma_frac"] = s["mfma_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
                 elif w.batch > 1:
                     # batched table lookups are bounded by gathers from LDS (4 bytes per lookup)
-                    s["lds_gather_GBps"] = 4.0 * w.lookups / (wall / steps) / 1e9
+                    s["lds_gather_GBps"] = 4.0 * w.lookups / t.median / 1e9
                     s["lds_frac"] = s["lds_gather_GBps"] / LDS_PEAK_GBPS
                 extra.append(s)
                 log("%s [%s]: %.2f us/call, %.1f GB/s, %.0f GOPS" % (w.name, kname, s["us_per_call"],
@@ -314,8 +394,8 @@ def main() -> int:
                 copies = max(2, min(64, (256 * 1024 * 1024) // w.key_bytes + 1))
                 p = Problem(biq, torch, w, copies, real_first=False, plan=plan)
                 steps = 200 if bb <= 32 else 50
-                wall, _ = time_steps(torch, p, steps, 5)
-                row[tag] = wall / steps * 1e6
+                p.touch_all(torch)
+                row[tag] = time_steps(torch, p, steps, 5).median * 1e6
                 row["kernel" if tag == "us" else "lut_kernel"] = biq.biq_kernel_name((plan or default).kernel)
                 del p
                 torch.cuda.empty_cache()
@@ -391,17 +471,27 @@ def main() -> int:
             del Xd, Ld
             torch.cuda.empty_cache()
         out["build_lut"] = luts
-        # the batch-1 family: m scaled by powers of two, to show the launch-latency knee
+        # the batch-1 bandwidth family: cfg 2's shape with m scaled by powers of two (the launch-latency
+        # knee), and the FFN matrices of cfg 5 with one input vector; cold keys, median per call
         fam = []
-        for k in range(0, 10):
-            w = head.scaled_m(head.m << k)
+        family = [head.scaled_m(head.m << k) for k in range(0, 10)]
+        family += [replace(CONFIGS["cfg5_ffn_up_q2_b128"], batch=1, name="cfg5_ffn_up_q2_b1"),
+                   replace(CONFIGS["cfg5_ffn_down_q2_b128"], batch=1, name="cfg5_ffn_down_q2_b1")]
+        for w in family:
             copies = max(2, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
             p = Problem(biq, torch, w, copies, real_first=False)
-            steps = 200 if k < 6 else 30
-            wall, _ = time_steps(torch, p, steps, 5)
-            s = summarize(w, wall / steps)
-            fam.append({"m": w.m, "key_bytes": w.key_bytes, "us_per_call": s["us_per_call"],
-                        "achieved_GBps": s["achieved_GBps"], "hbm_frac": s["hbm_frac"]})
+            steps = 200 if w.key_bytes < (64 << 20) else 30
+            p.touch_all(torch)
+            t = time_steps(torch, p, steps, 5)
+            s = summarize(w, t)
+            plan = biq.biq_plan_get(w.m, w.n, w.q, w.batch, w.mu)
+            fam.append({"workload": w.name, "m": w.m, "n": w.n, "key_bytes": w.key_bytes, "us_per_call": s["us_per_call"],
+                        "min_us_per_call": s["min_us_per_call"], "achieved_GBps": s["achieved_GBps"],
+                        "hbm_frac": s["hbm_frac"], "kernel": biq.biq_kernel_name(plan.kernel),
+                        "dispatches": 2 if plan.chunk_splits > 1 else 1})
+            log("family %s: %.2f us/call (min %.2f), %.0f GB/s = %.1f%% of HBM peak [%s]" %
+                (w.name, s["us_per_call"], s["min_us_per_call"], s["achieved_GBps"], 100 * s["hbm_frac"],
+                 fam[-1]["kernel"]))
             del p
             torch.cuda.empty_cache()
         out["gemv_b1_family"] = fam
@@ -409,12 +499,13 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline and prob is not None and prob.host is not None:
         cpu = cpu_baseline(head, prob.host)
-        log("cpu oracle: %.0f us/call on 1 core (%s)" % (cpu["us_per_call"], cpu["host_cpu"]))
+        log("cpu oracle on 1 core (%s): gemm_lut %.0f us/call, gemm_dense %.0f us/call" %
+            (cpu["host_cpu"], cpu["gemm_lut_us_per_call"], cpu["gemm_dense_us_per_call"]))
 
     value = head_sum["achieved_GBps"] if head_sum else (roof["achieved"] if roof else None)
     ms_per_step = head_sum["us_per_call"] / 1e3 if head_sum else (roof["launch_us"] / 1e3 if roof else None)
     line = {
-        "metric": "biq_gemm achieved HBM GB/s (algorithmic bytes / time), GEMV b=1",
+        "metric": "biq_gemm achieved HBM GB/s (algorithmic bytes / median time per call), GEMV b=1",
         "value": value,
         "unit": "GB/s",
         "n_gpus": 1,
@@ -430,6 +521,9 @@ def main() -> int:
             "workload": head.name,
             "m": head.m, "n": head.n, "q": head.q, "batch": head.batch, "mu": head.mu,
             "keys": "cold: %d packed matrices in rotation" % (prob.copies if prob else 0),
+            "timing": "9 regions of exactly `steps` calls each, every region between two HIP events and two "
+                      "synchronisations; ms_per_step and value are the median over the regions, min / mean / "
+                      "host clock of the first region are in `headline`",
         },
         "headline": head_sum,
         "roofline": roof,

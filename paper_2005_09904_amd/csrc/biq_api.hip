@@ -234,15 +234,15 @@ bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool table
     if (mu == 8 && batch == 1 && q <= 4) {
         // GEMV: workgroups of 1024 threads, 128-chunk tiles, one workgroup per CU when the
         // rows allow it (every further round of workgroups pays the table build again).  With
-        // >= 1024 rows per CU a workgroup walks all tiles of its rows (no partial sums);
-        // otherwise the tiles are split over workgroups as well and the partials are summed by
-        // a second small kernel.
+        // >= 512 rows per CU a workgroup walks all tiles of its rows (no partial sums: measured
+        // equal to or faster than a split from there on); otherwise the tiles are split over
+        // workgroups as well and the partials are summed by a second small kernel.
         pl.kernel = KERNEL_GEMV8;
         pl.threads = 1024;
         pl.chunks_per_tile = kGemvTileChunks;
         pl.batch_tile = 1;
         const int tiles = ceil_div(C, kGemvTileChunks);
-        if (ceil_div(m, 1024) >= kNumCu) {
+        if (ceil_div(m, 512) >= kNumCu) {
             pl.tiles_per_split = tiles;
             int rows = ceil_div(ceil_div(m, kNumCu), 64) * 64;
             pl.rows_per_wg = rows > 8192 ? 8192 : rows;
@@ -274,8 +274,6 @@ bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool table
             const int rows = rows_from(ceil_div_ll((long long)m * tiles, kNumCu), 64, 64, m);
             pl.rows_per_wg = rows > 8192 ? 8192 : rows;
         }
-        // 4 planes in the streaming modes: 512 threads (the 1024-thread kernel spills registers)
-        if (q == 4 && pl.kernel == KERNEL_GEMV8 && pl.row_mode == 0) pl.threads = 512;
         return plan_finish(pl, m, n, q, batch, mu);
     }
     if (mu == 8 && batch >= 2 && q <= 4 && C > kGemmTileChunks &&

@@ -108,9 +108,8 @@ __device__ __forceinline__ void gemv8_copy_tile(const QueryParams& p, char* lds_
     }
 }
 
-// MAXT = largest workgroup the instantiation may be launched with: 1024 threads leave 128
-// VGPRs per lane, which 4 planes with their key ring do not fit into (they spill); the 512
-// instantiation has 256.
+// MAXT = largest workgroup the instantiation may be launched with: 1024 threads leave 128 VGPRs
+// per lane (4 planes then keep 2 steps of keys in flight per wave instead of 4), 512 leave 256.
 template <int Q, bool FUSED, int MAXT = 1024>
 __global__ __launch_bounds__(MAXT) void gemv8_kernel(const QueryParams p) {
     extern __shared__ __align__(16) float lds[];
@@ -240,7 +239,7 @@ __global__ __launch_bounds__(MAXT) void gemv8_kernel(const QueryParams p) {
     const int nblk = (nrows + 63) >> 6;
     const int iters = (nblk + nwaves - 1) / nwaves;  // block iterations per wave and tile, >= 1
     // PD * Q KiB in flight per wave; fewer for many planes to stay inside 128 VGPRs
-    constexpr int PD = (Q <= 2 || MAXT <= 512) ? 4 : (Q == 3 ? 2 : 1);
+    constexpr int PD = (Q <= 3 || MAXT <= 512) ? 4 : 2;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const char* kbase[Q];
     const char* abase[Q];

@@ -32,6 +32,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_wave_kernel(const floa
                                                                       float* __restrict__ alpha, int m,
                                                                       int n, int q, int stride_dw) {
     __shared__ float wave_sums[2][4];   // WPR = 4: the waves' partial sums, double buffered over the planes
+    __shared__ uint2 mask_strip[kQuantThreads / 64][EPT];  // per wave: the sign bits of each step of a plane
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wsub = wave % WPR;
@@ -44,7 +45,10 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_wave_kernel(const floa
 #pragma unroll
     for (int t = 0; t < EPT; ++t) r[t] = wrow[min((t * WPR + wsub) * 64 + lane, n - 1)];
 #pragma unroll
-    for (int t = 0; t < EPT; ++t) r[t] = ((t * WPR + wsub) * 64 + lane < n) ? r[t] : 0.0f;
+    for (int t = 0; t < EPT; ++t) r[t] = ((t * WPR + wsub) * 64 + lane < n) ? r[t] + 0.0f : 0.0f;
+    // (+ 0.0f turns a weight of -0.0 into +0.0 and changes nothing else; a residual is never -0.0
+    // afterwards (x - x = +0.0 under round-to-nearest), so the sign bit of r is exactly "r < 0" and
+    // sign(0) = +1 as in Eq. 1's reading: the code and the residual update below agree)
     const int words = stride_dw / 2;  // 64-bit words of the packed row (stride is a multiple of 16 bytes)
     // this lane holds elements of steps 0 .. nvalid - 1
     int nvalid = max(0, (n - lane - 64 * wsub + 64 * WPR - 1) / (64 * WPR));
@@ -65,34 +69,25 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_wave_kernel(const floa
         const float a = s / (float)n;
         if (lane == 0 && wsub == 0) alpha[(size_t)i * m + row] = a;
         uint32_t* krow = K + ((size_t)i * m + row) * stride_dw;
-        // lane t (and t - 64) keeps the 64 sign bits of step t: the row's keys leave in a few
-        // wide stores instead of one small store per step
-        int keep_lo[(EPT + 63) / 64], keep_hi[(EPT + 63) / 64];
-#pragma unroll
-        for (int u = 0; u < (EPT + 63) / 64; ++u) { keep_lo[u] = 0; keep_hi[u] = 0; }
+        // The 64 sign bits of step t are wave-uniform (a ballot); they go through a per-wave LDS
+        // strip, word t, so that afterwards lane t (and t - 64) holds step t's bits and the row's
+        // keys leave in a few wide stores instead of one small store per step.  A wave only reads
+        // what it wrote itself: LDS operations of one wave complete in order, no barrier needed.
+        uint2* const strip = mask_strip[wave];
 #pragma unroll
         for (int t = 0; t < EPT; ++t) {
             const bool valid = t < nvalid;
-            // one predicate decides the code and the residual update: b = -1 iff r < 0, so that
-            // r = +0.0 and r = -0.0 (a weight may be -0.0) both take b = +1 and r - alpha (Eq. 1
-            // with sign(0) = +1)
-            const bool neg = r[t] < 0.0f;
-            const unsigned long long mask = __ballot(valid && !neg);
-            const float rn = neg ? r[t] + a : r[t] - a;
+            const unsigned long long mask = __ballot(valid && !(r[t] < 0.0f));
+            // r -= copysign(a, r)
+            const float rn = r[t] - __uint_as_float((__float_as_uint(r[t]) & 0x80000000u) | __float_as_uint(a));
             r[t] = valid ? rn : 0.0f;
-            // the (wave-uniform) mask halves go into lane t of the keep registers: a compare and two
-            // selects, all visible to the compiler's hazard handling (this toolchain has no builtin
-            // for v_writelane_b32)
-            const bool mine = lane == (t & 63);
-            keep_lo[t >> 6] = mine ? (int)(uint32_t)mask : keep_lo[t >> 6];
-            keep_hi[t >> 6] = mine ? (int)(uint32_t)(mask >> 32) : keep_hi[t >> 6];
+            if (lane == 0) strip[t] = make_uint2((uint32_t)mask, (uint32_t)(mask >> 32));
         }
 #pragma unroll
         for (int u = 0; u < (EPT + 63) / 64; ++u) {
             const int t = 64 * u + lane;
             const int word = t * WPR + wsub;
-            if (t < EPT && word < words)
-                *reinterpret_cast<uint2*>(krow + 2 * word) = make_uint2((uint32_t)keep_lo[u], (uint32_t)keep_hi[u]);
+            if (t < EPT && word < words) *reinterpret_cast<uint2*>(krow + 2 * word) = strip[t];
         }
     }
 }

@@ -20,7 +20,7 @@ hipError_t launch_gemv8_q(int q, const QueryParams& qp, int grid, int threads, i
         case 2: return launch_gemv8_inst<2, FUSED, 1024>(qp, grid, threads, lds, s);
         case 3: return launch_gemv8_inst<3, FUSED, 1024>(qp, grid, threads, lds, s);
         case 4:
-            // 4 planes: up to 512 threads run the instantiation with the larger register budget
+            // 4 planes: up to 512 threads run an instantiation with a deeper key ring (more registers)
             return threads <= 512 ? launch_gemv8_inst<4, FUSED, 512>(qp, grid, threads, lds, s)
                                   : launch_gemv8_inst<4, FUSED, 1024>(qp, grid, threads, lds, s);
     }
