@@ -225,6 +225,9 @@ def main() -> int:
     ap.add_argument("--workload", default=None,
                     help="time only this named configuration (for profiling), e.g. cfg4_sq4096_q3_b32")
     ap.add_argument("--mu", type=int, default=0, help="with --workload: LUT-unit to use instead of the workload's")
+    ap.add_argument("--m", type=int, default=0, help="with --workload: number of output rows instead of the workload's "
+                                                     "(the batch-1 bandwidth family scales m)")
+    ap.add_argument("--batch", type=int, default=0, help="with --workload: number of input vectors instead of the workload's")
     ap.add_argument("--plan", choices=["default", "lut"], default="default",
                     help="with --workload: the library's plan, or its choice among the lookup-table kernels only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -261,6 +264,10 @@ def main() -> int:
         w = CONFIGS[args.workload]
         if args.mu:
             w = w.with_mu(args.mu)
+        if args.m:
+            w = w.scaled_m(args.m)
+        if args.batch:
+            w = replace(w, batch=args.batch, name="%s_b%d" % (w.name, args.batch))
         plan = biq.biq_plan_get_lut(w.m, w.n, w.q, w.batch, w.mu) if args.plan == "lut" else None
         copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
         p = Problem(biq, torch, w, copies, real_first=False, plan=plan)

@@ -29,7 +29,7 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, no intrinsics, no OpenMP). Returns the library path."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-o", tmp, _SRC])
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -58,6 +58,7 @@ def _load():
         lib.biqo_gemm_dense.argtypes = [P, P, P, L, L, I, L, P]
         lib.biqo_gemm_lut.argtypes = [P, P, P, L, L, I, L, I, P]
         lib.biqo_quantize_greedy.argtypes = [P, L, L, I, P, P, P]
+        lib.biqo_lstm_cell.argtypes = [P, P, P, P, P, L, L, I, L, P, P]
         _lib = lib
     return _lib
 
@@ -196,3 +197,25 @@ def quantize_greedy(W, q: int, with_residuals: bool = False):
     _check(_load().biqo_quantize_greedy(_ptr(W), m, n, q, _ptr(B), _ptr(alpha),
                                         _ptr(R) if R is not None else None), "quantize_greedy")
     return (B, alpha, R) if with_residuals else (B, alpha)
+
+
+def lstm_cell(B, alpha, bias, X, C_prev):
+    """One LSTM cell step on stacked quantised gate matrices (gates i, f, g, o): B int8 [q][4H][n],
+    alpha [q][4H], bias [4H], X [b][n] = [x_t ; h_(t-1)], C_prev [b][H].  Returns (h, c) float64 [b][H]."""
+    B = _arr(B, np.int8, 3)
+    q, m, n = B.shape
+    if m % 4:
+        raise OracleError("4H rows expected")
+    H = m // 4
+    alpha = _arr(alpha, np.float32, 2)
+    bias = _arr(bias, np.float32, 1)
+    X = _arr(X, np.float32, 2)
+    C_prev = _arr(C_prev, np.float32, 2)
+    b = X.shape[0]
+    if alpha.shape != (q, m) or bias.shape != (m,) or X.shape[1] != n or C_prev.shape != (b, H):
+        raise OracleError("shape mismatch")
+    h = np.zeros((b, H), dtype=np.float64)
+    c = np.zeros((b, H), dtype=np.float64)
+    _check(_load().biqo_lstm_cell(_ptr(B), _ptr(alpha), _ptr(bias), _ptr(X), _ptr(C_prev), H, n, q, b,
+                                  _ptr(h), _ptr(c)), "lstm_cell")
+    return h, c

@@ -29,6 +29,7 @@
  *
  * Every function returns 0 on success, a negative number on invalid input.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -285,5 +286,42 @@ int biqo_quantize_greedy(const float* W, long m, long n, int q, int8_t* B, doubl
         }
     }
     free(r);
+    return BIQO_OK;
+}
+
+/*
+ * One step of an LSTM cell whose four gate matrices are binary-coding quantised and stacked into
+ * one weight matrix of 4H rows (Sec. II-C names LSTM layers as a target of the method and gives
+ * their shapes; the cell itself is the textbook one, gates in the order input, forget, cell
+ * candidate, output: rows [0,H), [H,2H), [2H,3H), [3H,4H)).  The layer's input is the
+ * concatenation [x_t ; h_(t-1)] of length n, given as X [b][n]; the recurrent and the input
+ * matrix are the column blocks of the stacked matrix.
+ *     z = W [x ; h] + bias          (W = sum_i alpha_i B_i, Eq. 2; z has 4H entries)
+ *     i = sigma(z_i), f = sigma(z_f), g = tanh(z_g), o = sigma(z_o)
+ *     c' = f * c + i * g,   h' = o * tanh(c')
+ * B int8 [q][4H][n], alpha float [q][4H], bias float [4H], X float [b][n], C_prev float [b][H];
+ * H_out, C_out double [b][H].  fp64 throughout.
+ */
+static double biqo_sigmoid(double z) { return 1.0 / (1.0 + exp(-z)); }
+
+int biqo_lstm_cell(const int8_t* B, const float* alpha, const float* bias, const float* X,
+                   const float* C_prev, long H, long n, int q, long b, double* H_out, double* C_out) {
+    if (!B || !alpha || !bias || !X || !C_prev || !H_out || !C_out || H < 1) return BIQO_EINVAL;
+    long m = 4 * H;
+    double* Z = (double*)malloc((size_t)b * m * sizeof(double));
+    if (!Z) return BIQO_ENOMEM;
+    int rc = biqo_gemm_dense(B, alpha, X, m, n, q, b, Z); /* Z [b][4H] */
+    if (rc) { free(Z); return rc; }
+    for (long a = 0; a < b; ++a)
+        for (long j = 0; j < H; ++j) {
+            double zi = Z[a * m + j] + (double)bias[j];
+            double zf = Z[a * m + H + j] + (double)bias[H + j];
+            double zg = Z[a * m + 2 * H + j] + (double)bias[2 * H + j];
+            double zo = Z[a * m + 3 * H + j] + (double)bias[3 * H + j];
+            double c = biqo_sigmoid(zf) * (double)C_prev[a * H + j] + biqo_sigmoid(zi) * tanh(zg);
+            C_out[a * H + j] = c;
+            H_out[a * H + j] = biqo_sigmoid(zo) * tanh(c);
+        }
+    free(Z);
     return BIQO_OK;
 }
