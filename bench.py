@@ -478,6 +478,47 @@ def main() -> int:
             del Xd, Ld
             torch.cuda.empty_cache()
         out["build_lut"] = luts
+        # small layers that do not depend on each other, L = 8 per dispatch (grouped launch) against the
+        # same 8 as separate calls; and the LSTM cell step with its update fused (cfg 3's shape)
+        class Calls:
+            def __init__(self, fns):
+                self.fns = fns
+
+            def step(self):
+                for fn in self.fns:
+                    fn()
+
+        grouped = []
+        for name in ["cfg1_fc512_b1", "cfg2_gemv2048_q2_b1", "cfg3_lstm4096x1024_q3_b8"]:
+            w = CONFIGS[name]
+            L = 8
+            probs = [Problem(biq, torch, replace(w, seed=w.seed + 1000 * i), 1, real_first=False) for i in range(L)]
+            group = biq.PreparedGroup([(p.K[0], p.alpha, p.X, p.Y, w.m, w.n, w.q, w.batch) for p in probs], w.mu)
+            tg = time_steps(torch, Calls([group]), 200, 20)
+            ts = time_steps(torch, Calls([p.prepared[0] for p in probs]), 200, 20)
+            grouped.append({"workload": w.name, "layers_per_dispatch": L,
+                            "grouped_us_per_layer": tg.median * 1e6 / L, "grouped_us_per_call": tg.median * 1e6,
+                            "separate_us_per_layer": ts.median * 1e6 / L})
+            log("grouped %s x %d: %.2f us per layer in one dispatch, %.2f us per layer as separate calls" %
+                (w.name, L, tg.median * 1e6 / L, ts.median * 1e6 / L))
+            del probs, group
+            torch.cuda.empty_cache()
+        out["grouped_launch"] = grouped
+        w = CONFIGS["cfg3_lstm4096x1024_q3_b8"]
+        hid = w.m // 4
+        pl = Problem(biq, torch, w, 1, real_first=False)
+        bias = torch.zeros(w.m, device="cuda")
+        cprev = torch.randn((w.batch, hid), device="cuda")
+        hout, cout = torch.empty_like(cprev), torch.empty_like(cprev)
+        tl = time_steps(torch, Calls([biq.PreparedLstmCell(pl.K[0], pl.alpha, bias, pl.X, cprev, hout, cout, hid,
+                                                           w.n, w.q, w.batch, w.mu)]), 200, 20)
+        tgm = time_steps(torch, pl, 200, 20)
+        out["lstm_cell"] = {"hidden": hid, "n": w.n, "q": w.q, "batch": w.batch,
+                            "fused_cell_us_per_step": tl.median * 1e6, "biq_gemm_alone_us": tgm.median * 1e6}
+        log("lstm cell step (hidden %d, n %d, q %d, batch %d): %.2f us fused; biq_gemm alone %.2f us" %
+            (hid, w.n, w.q, w.batch, tl.median * 1e6, tgm.median * 1e6))
+        del pl
+        torch.cuda.empty_cache()
         # the batch-1 bandwidth family: cfg 2's shape with m scaled by powers of two (the launch-latency
         # knee), and the FFN matrices of cfg 5 with one input vector; cold keys, median per call
         fam = []

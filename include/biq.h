@@ -215,6 +215,46 @@ biq_status biq_gemm_ex(const uint8_t* K, const float* alpha, const float* X, flo
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Several independent small multiplies in one dispatch.  A small layer costs one dependent
+ * dispatch plus one table build whatever its size (Table IV's batch-1 column is flat from 512^2
+ * to 4096^2 for the same reason); layers that do not depend on each other - the sub-layers of a
+ * Transformer block, the gate or direction matrices of LSTM layers (Sec. II-C) - share that cost
+ * here.  problems: HOST array of `count` descriptors (read during the call only) holding device
+ * pointers with the layouts and alignments of biq_gemm; shapes, plane counts and batch sizes may
+ * differ.  Consecutive problems that map to the same kernel family and plane count go into one
+ * dispatch (at most 16 per dispatch), so a list of equal layers is exactly one dispatch.
+ * No workspace, no allocation.  Each result equals biq_gemm's on the same problem up to the order of
+ * the additions (same tolerance; bit-identical when the plans agree).
+ * Served: mu = 8, q <= 4 and rows no wider than one tile of tables (batch 1: n <= 2048, batch >= 2:
+ * n <= 1024); BIQ_EUNSUPPORTED otherwise, and then nothing has been launched.
+ */
+typedef struct {
+    const uint8_t* K;    /* [q][m][stride] */
+    const float* alpha;  /* [q][m] */
+    const float* X;      /* [batch][n] */
+    float* Y;            /* [batch][m] */
+    int m, n, q, batch;
+} biq_problem;
+biq_status biq_gemm_grouped(const biq_problem* problems, int count, int mu, void* stream);
+
+/*
+ * One step of an LSTM cell whose four gate matrices are binary-coding quantised (Sec. II-C: LSTM
+ * layers are among the method's targets) and stacked into one matrix of m = 4 * hidden rows, gates in
+ * the order input, forget, cell candidate, output.  One dispatch: the lookup-table multiply of
+ * biq_gemm with the cell update as its epilogue,
+ *     z = W [x_t ; h_(t-1)] + bias,  c' = sigma(z_f) c + sigma(z_i) tanh(z_g),  h' = sigma(z_o) tanh(c').
+ * K, alpha as for biq_gemm with m = 4 * hidden; bias device float [4 * hidden]; X device float [batch][n]
+ * holds [x_t ; h_(t-1)] per input vector (n = input size + hidden: the input and the recurrent matrix
+ * are the column blocks of the stacked matrix); C_prev, H_out, C_out device float [batch][hidden].
+ * fp32 throughout (expf / tanhf of the device library).  Served: mu = 8, q <= 4, batch 1 with
+ * n <= 2048 or batch >= 2 with n <= 1024; BIQ_EUNSUPPORTED otherwise (use biq_gemm and apply the
+ * cell update separately).
+ */
+biq_status biq_lstm_cell(const uint8_t* K, const float* alpha, const float* bias, const float* X,
+                         const float* C_prev, float* H_out, float* C_out, int hidden, int n, int q, int batch,
+                         int mu, void* stream);
+
+/*
  * biq_gemm for callers that cannot allocate or hand over device memory for a workspace: code
  * whose launches are being captured into a HIP graph, serving loops with a fixed memory plan,
  * harnesses that forbid hipMalloc.  Same arguments, plan, kernels and results (bit for bit) as

@@ -18,7 +18,7 @@ EXPORTS = [
     "biq_lut_bytes", "biq_workspace_bytes", "biq_plan_get", "biq_plan_get_lut", "biq_plan_check", "biq_plan_workspace_bytes",
     "biq_kernel_name", "biq_pack", "biq_unpack_keys", "biq_build_lut", "biq_query", "biq_gemm",
     "biq_gemm_ex", "biq_quantize", "biq_unpack_keys16", "biq_init", "biq_noalloc_scratch_bytes",
-    "biq_gemm_noalloc",
+    "biq_gemm_noalloc", "biq_gemm_grouped", "biq_lstm_cell",
 ]
 
 
@@ -34,6 +34,13 @@ class BiqPlan(ctypes.Structure):
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+
+
+class BiqProblem(ctypes.Structure):
+    """Mirror of biq_problem in include/biq.h."""
+
+    _fields_ = [("K", ctypes.c_void_p), ("alpha", ctypes.c_void_p), ("X", ctypes.c_void_p), ("Y", ctypes.c_void_p),
+                ("m", ctypes.c_int), ("n", ctypes.c_int), ("q", ctypes.c_int), ("batch", ctypes.c_int)]
 
 
 class BiqError(RuntimeError):
@@ -82,6 +89,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "biq_init": (I, []),
         "biq_noalloc_scratch_bytes": (Z, []),
         "biq_gemm_noalloc": (I, [P, P, P, P, I, I, I, I, I, P]),
+        "biq_gemm_grouped": (I, [ctypes.POINTER(BiqProblem), I, I, P]),
+        "biq_lstm_cell": (I, [P, P, P, P, P, P, P, I, I, I, I, I, P]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -212,6 +221,50 @@ def biq_noalloc_scratch_bytes() -> int:
 def biq_gemm_noalloc(K, alpha, X, Y, m: int, n: int, q: int, batch: int, mu: int, stream=None) -> None:
     _check(load_library().biq_gemm_noalloc(_ptr(K), _ptr(alpha), _ptr(X), _ptr(Y), m, n, q, batch, mu,
                                            _stream(stream)), "biq_gemm_noalloc")
+
+
+class PreparedGroup:
+    """A biq_gemm_grouped call with its descriptor array built once.  problems: list of
+    (K, alpha, X, Y, m, n, q, batch); the tensors must stay alive and in place."""
+
+    def __init__(self, problems, mu, stream=None):
+        self._keep = problems
+        self._array = (BiqProblem * len(problems))()
+        for d, (K, alpha, X, Y, m, n, q, batch) in zip(self._array, problems):
+            d.K, d.alpha, d.X, d.Y = _ptr(K), _ptr(alpha), _ptr(X), _ptr(Y)
+            d.m, d.n, d.q, d.batch = m, n, q, batch
+        self._args = (self._array, len(problems), mu, _stream(stream))
+        self._fn = load_library().biq_gemm_grouped
+
+    def __call__(self) -> None:
+        status = self._fn(*self._args)
+        if status != BIQ_OK:
+            raise BiqError(status, "biq_gemm_grouped")
+
+
+def biq_gemm_grouped(problems, mu: int, stream=None) -> None:
+    PreparedGroup(problems, mu, stream)()
+
+
+def biq_lstm_cell(K, alpha, bias, X, C_prev, H_out, C_out, hidden: int, n: int, q: int, batch: int, mu: int,
+                  stream=None) -> None:
+    _check(load_library().biq_lstm_cell(_ptr(K), _ptr(alpha), _ptr(bias), _ptr(X), _ptr(C_prev), _ptr(H_out),
+                                        _ptr(C_out), hidden, n, q, batch, mu, _stream(stream)), "biq_lstm_cell")
+
+
+class PreparedLstmCell:
+    """A biq_lstm_cell call with its arguments marshalled once (see PreparedGemm)."""
+
+    def __init__(self, K, alpha, bias, X, C_prev, H_out, C_out, hidden, n, q, batch, mu, stream=None):
+        self._keep = (K, alpha, bias, X, C_prev, H_out, C_out)
+        self._fn = load_library().biq_lstm_cell
+        self._args = (_ptr(K), _ptr(alpha), _ptr(bias), _ptr(X), _ptr(C_prev), _ptr(H_out), _ptr(C_out), hidden, n, q,
+                      batch, mu, _stream(stream))
+
+    def __call__(self) -> None:
+        status = self._fn(*self._args)
+        if status != BIQ_OK:
+            raise BiqError(status, "biq_lstm_cell")
 
 
 class PreparedGemm:

@@ -11,6 +11,7 @@
 #include "biq_gemm8x2h.h"
 #include "biq_query_wide.h"
 #include "biq_quantize.h"
+#include "biq_grouped.h"
 
 namespace {
 
@@ -414,6 +415,66 @@ size_t plan_workspace(const biq_plan& pl, int m, int batch) {
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// Kernel parameters of a lookup-table plan.
+void fill_query_params(QueryParams& qp, const biq_plan& pl, const uint8_t* K, const float* alpha, const float* X,
+                       const float* LUT, float* out, int m, int n, int q, int batch, int mu) {
+    qp.K = reinterpret_cast<const uint32_t*>(K);
+    qp.alpha = alpha;
+    qp.X = X;
+    qp.LUT = LUT;
+    qp.out = out;
+    qp.m = m; qp.n = n; qp.q = q; qp.batch = batch;
+    qp.stride_dw = (int)(biq_key_row_stride(n) / 4);
+    qp.C = ceil_div(n, mu);
+    qp.CT = pl.chunks_per_tile;
+    qp.G = pl.chunks_per_tile / unit_keys(mu);
+    qp.log2G = ilog2(qp.G);
+    qp.tiles = ceil_div(qp.C, qp.CT);
+    qp.tps = pl.tiles_per_split;
+    qp.splits = pl.chunk_splits;
+    qp.rows_per_wg = pl.rows_per_wg;
+    qp.row_blocks = pl.row_blocks;
+    qp.batch_tiles = pl.batch_tiles;
+    qp.ntasks = pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
+    qp.tasks_per_xcd = ceil_div(qp.ntasks, kNumXcd);
+    qp.row_mode = pl.row_mode;
+    qp.xcd_skew = pl.xcd_skew;
+}
+
+// Plan of one problem of a grouped launch: mu = 8, at most 4 planes, a single dispatch without
+// workspace (rows no wider than one tile), and only `cus` CUs' worth of workgroups, since the
+// other problems of the group fill the rest of the chip.  false: the shape needs biq_gemm.
+bool plan_grouped(biq_plan& pl, int& kind, int m, int n, int q, int batch, int mu, int cus) {
+    if (mu != 8 || q > 4) return false;
+    const int C = ceil_div(n, 8);
+    pl = biq_plan{};
+    pl.threads = 1024;
+    pl.tiles_per_split = 1;
+    pl.row_mode = 1;
+    if (batch == 1 && C <= kGemvTileChunks) {
+        kind = GROUP_GEMV8;
+        pl.kernel = KERNEL_GEMV8;
+        pl.chunks_per_tile = kGemvTileChunks;
+        pl.batch_tile = 1;
+        pl.rows_per_wg = rows_from(ceil_div_ll(m, cus), 8, 8, m);
+    } else if (batch == 1 && C <= kGemvHalfTileChunks) {
+        kind = GROUP_GEMV8H;
+        pl.kernel = KERNEL_GEMV8H;
+        pl.chunks_per_tile = kGemvHalfTileChunks;
+        pl.batch_tile = 1;
+        pl.rows_per_wg = rows_from(ceil_div_ll(m, cus), 4, 8, m);
+    } else if (batch >= 2 && C <= kGemmHalfTileChunks) {
+        kind = GROUP_GEMM8X2H;
+        pl.kernel = KERNEL_GEMM8X2H;
+        pl.chunks_per_tile = kGemmHalfTileChunks;
+        pl.batch_tile = 2;
+        pl.rows_per_wg = rows_from(ceil_div_ll((long long)m * ceil_div(batch, 2), cus), 8, 8, m);
+    } else {
+        return false;
+    }
+    return plan_finish(pl, m, n, q, batch, mu) && pl.chunk_splits == 1;
+}
+
 // Large-batch path: split X into bf16 terms in MFMA operand order (workspace), contract, and
 // sum the partial results when the key groups were split over workgroups.
 biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* alpha, const float* X,
@@ -479,27 +540,8 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
         return run_unpack_mfma(pl, K, alpha, X, Y, m, n, q, batch, workspace, s);
 
     QueryParams qp{};
-    qp.K = reinterpret_cast<const uint32_t*>(K);
-    qp.alpha = alpha;
-    qp.X = X;
-    qp.LUT = LUT;
-    qp.out = pl.chunk_splits > 1 ? reinterpret_cast<float*>(workspace) : Y;
-    qp.m = m; qp.n = n; qp.q = q; qp.batch = batch;
-    qp.stride_dw = (int)(biq_key_row_stride(n) / 4);
-    qp.C = ceil_div(n, mu);
-    qp.CT = pl.chunks_per_tile;
-    qp.G = pl.chunks_per_tile / unit_keys(mu);
-    qp.log2G = ilog2(qp.G);
-    qp.tiles = ceil_div(qp.C, qp.CT);
-    qp.tps = pl.tiles_per_split;
-    qp.splits = pl.chunk_splits;
-    qp.rows_per_wg = pl.rows_per_wg;
-    qp.row_blocks = pl.row_blocks;
-    qp.batch_tiles = pl.batch_tiles;
-    qp.ntasks = pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
-    qp.tasks_per_xcd = ceil_div(qp.ntasks, kNumXcd);
-    qp.row_mode = pl.row_mode;
-    qp.xcd_skew = pl.xcd_skew;
+    fill_query_params(qp, pl, K, alpha, X, LUT, pl.chunk_splits > 1 ? reinterpret_cast<float*>(workspace) : Y, m, n, q,
+                      batch, mu);
     const int grid = qp.tasks_per_xcd * kNumXcd;
 
     hipError_t e;
@@ -715,6 +757,96 @@ biq_status biq_gemm_noalloc(const uint8_t* K, const float* alpha, const float* X
     // full before reading it, so what an earlier call left there does not matter and nothing is
     // cleared.
     return run_query(true, K, alpha, X, nullptr, Y, m, n, q, batch, mu, &pl, ws, need, stream);
+}
+
+biq_status biq_gemm_grouped(const biq_problem* problems, int count, int mu, void* stream) {
+    if (!problems || count < 1) return BIQ_EINVAL;
+    for (int i = 0; i < count; ++i) {
+        const biq_problem& pr = problems[i];
+        if (!shape_ok(pr.m, pr.n, pr.q, pr.batch, mu)) return BIQ_EINVAL;
+        if (!pr.K || !pr.alpha || !pr.X || !pr.Y) return BIQ_EINVAL;
+        if (!aligned(pr.K, 16) || !aligned(pr.alpha, 4) || !aligned(pr.X, 4) || !aligned(pr.Y, 4)) return BIQ_EINVAL;
+    }
+    // every problem gets its share of the CUs; all are planned before anything is launched
+    const int cus = count >= kNumCu ? 1 : kNumCu / count;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    // first pass (launch = false) only checks that every problem has a single-dispatch plan
+    for (int pass = 0; pass < 2; ++pass) {
+        int i = 0;
+        while (i < count) {
+            GroupParams g{};
+            int kind = -1, q = 0, lds = 0, grid = 0;
+            while (i < count && g.count < kGroupMax) {
+                const biq_problem& pr = problems[i];
+                biq_plan pl;
+                int k = -1;
+                if (!plan_grouped(pl, k, pr.m, pr.n, pr.q, pr.batch, mu, cus)) return BIQ_EUNSUPPORTED;
+                if (g.count > 0 && (k != kind || pr.q != q)) break;  // next dispatch
+                kind = k;
+                q = pr.q;
+                if (pl.lds_bytes > lds) lds = pl.lds_bytes;
+                QueryParams& qp = g.p[g.count];
+                fill_query_params(qp, pl, pr.K, pr.alpha, pr.X, nullptr, pr.Y, pr.m, pr.n, pr.q, pr.batch, mu);
+                g.first_wg[g.count] = grid;
+                grid += qp.tasks_per_xcd * kNumXcd;
+                ++g.count;
+                ++i;
+            }
+            g.first_wg[g.count] = grid;
+            if (pass == 1 && launch_grouped(kind, q, g, grid, lds, s) != hipSuccess) return BIQ_EHIP;
+        }
+    }
+    return BIQ_OK;
+}
+
+biq_status biq_lstm_cell(const uint8_t* K, const float* alpha, const float* bias, const float* X,
+                         const float* C_prev, float* H_out, float* C_out, int hidden, int n, int q, int batch,
+                         int mu, void* stream) {
+    if (hidden < 1 || hidden > (1 << 28)) return BIQ_EINVAL;
+    const int m = 4 * hidden;
+    if (!shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
+    if (!K || !alpha || !bias || !X || !C_prev || !H_out || !C_out) return BIQ_EINVAL;
+    if (!aligned(K, 16) || !aligned(alpha, 4) || !aligned(bias, 4) || !aligned(X, 4) || !aligned(C_prev, 4) ||
+        !aligned(H_out, 4) || !aligned(C_out, 4))
+        return BIQ_EINVAL;
+    if (mu != 8 || q > 4) return BIQ_EUNSUPPORTED;
+    const int C = ceil_div(n, 8);
+    biq_plan pl{};
+    pl.threads = 1024;
+    pl.tiles_per_split = 1;
+    pl.row_mode = 1;
+    int units;  // hidden units per workgroup: one workgroup per CU if the units allow it
+    if (batch == 1 && C <= kGemvHalfTileChunks) {
+        pl.kernel = KERNEL_GEMV8H;
+        pl.chunks_per_tile = kGemvHalfTileChunks;
+        pl.batch_tile = 1;
+        units = ceil_div(hidden, kNumCu);
+    } else if (batch >= 2 && C <= kGemmHalfTileChunks) {
+        pl.kernel = KERNEL_GEMM8X2H;
+        pl.chunks_per_tile = kGemmHalfTileChunks;
+        pl.batch_tile = 2;
+        units = 2 * (int)ceil_div_ll((long long)hidden * ceil_div(batch, 2), 2ll * kNumCu);  // two per wave step
+    } else {
+        return BIQ_EUNSUPPORTED;  // rows wider than one half-table tile: biq_gemm, then the cell update by the caller
+    }
+    if (units < 1) units = 1;
+    pl.rows_per_wg = 4 * units;
+    if (!plan_finish(pl, m, n, q, batch, mu) || pl.chunk_splits != 1) return BIQ_EUNSUPPORTED;
+    QueryParams qp{};
+    fill_query_params(qp, pl, K, alpha, X, nullptr, H_out, m, n, q, batch, mu);
+    // workgroups are laid out over hidden units, not gate rows
+    qp.row_blocks = ceil_div(hidden, units);
+    qp.ntasks = qp.row_blocks * qp.batch_tiles;
+    qp.tasks_per_xcd = ceil_div(qp.ntasks, kNumXcd);
+    qp.bias = bias;
+    qp.c_prev = C_prev;
+    qp.c_out = C_out;
+    qp.hidden = hidden;
+    const int grid = qp.tasks_per_xcd * kNumXcd;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const hipError_t e = pl.kernel == KERNEL_GEMV8H ? launch_lstm8h(q, qp, grid, pl.threads, pl.lds_bytes, s)
+                                                    : launch_lstm8x2h(q, qp, grid, pl.threads, pl.lds_bytes, s);
+    return e == hipSuccess ? BIQ_OK : BIQ_EHIP;
 }
 
 }  // extern "C"

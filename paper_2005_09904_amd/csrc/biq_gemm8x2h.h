@@ -57,12 +57,17 @@ __device__ __forceinline__ void gemm8x2h_copy_tile(const QueryParams& p, char* l
 
 // One 128-chunk tile and one pair of input vectors per workgroup, one step of 8 rows per wave
 // at a time; the first step's keys and scales are requested before the tables are built.
-template <int Q, bool FUSED>
-__global__ __launch_bounds__(1024) void gemm8x2h_kernel(const QueryParams p) {
+//
+// LSTM = true: the rows are the four gates i, f, g, o of an LSTM cell stacked (m = 4 * hidden); the
+// 8 rows of a wave step are the 4 gates of TWO hidden units (rows 0..3 of the step: unit 2s, rows
+// 4..7: unit 2s + 1), so the step's epilogue has all pre-activations of its units in one wave
+// and applies the cell update for both input vectors: p.out receives h, p.c_out the new cell
+// state.  rows_per_wg counts gate rows (4 per unit, a multiple of 8).
+template <int Q, bool FUSED, bool LSTM>
+__device__ __forceinline__ void gemm8x2h_body(const QueryParams& p, const int wg) {
     extern __shared__ __align__(16) float lds[];
     char* const lds_bytes = reinterpret_cast<char*>(lds);
 
-    const int wg = blockIdx.x;
     const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
     if (task >= p.ntasks) return;
     const int bt = task % p.batch_tiles;
@@ -123,24 +128,36 @@ __global__ __launch_bounds__(1024) void gemm8x2h_kernel(const QueryParams p) {
     const uint32_t stride_bytes = (uint32_t)p.stride_dw * 4u;
     const int nrows = r1 - r0;
     const bool have_keys = (uint32_t)(tile * 128 + L * 16) < stride_bytes;
-    const int nsteps = (nrows + 7) >> 3;
-    auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q]) {
-        const int row = 8 * s + rsub;
-        const bool ok = have_keys && s < nsteps && row < nrows;
+    // LSTM: the workgroup's hidden units [u0, u0 + nunits), two units (8 gate rows) per step
+    const int u0 = LSTM ? rb * (p.rows_per_wg >> 2) : 0;
+    const int nunits = LSTM ? min(p.hidden, u0 + (p.rows_per_wg >> 2)) - u0 : 0;
+    const int nsteps = LSTM ? (nunits + 1) >> 1 : (nrows + 7) >> 3;
+    // al[0..Q) = the scales of this lane's row; LSTM: al[Q] = its bias, al[Q + 1], al[Q + 2] = the
+    // previous cell state of its unit for the two input vectors (requested with the keys, so that
+    // the cell update waits for no memory access)
+    auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q + 3]) {
+        // row of the key matrix inside a plane: LSTM: gate (rsub & 3) of unit u0 + 2s + (rsub >> 2)
+        const int unit = 2 * s + (rsub >> 2);
+        const int row = LSTM ? (rsub & 3) * p.hidden + u0 + unit : r0 + 8 * s + rsub;
+        const bool row_ok = s < nsteps && (LSTM ? unit < nunits : row < r1);
+        const bool ok = have_keys && row_ok;
 #pragma unroll
         for (int i = 0; i < Q; ++i) {
             k[i] = (u32x4){0u, 0u, 0u, 0u};
             al[i] = 0.0f;
             if (ok) {
-                const size_t kr = (size_t)i * p.m + r0 + row;
+                const size_t kr = (size_t)i * p.m + row;
                 k[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.K) +
                                                        kr * stride_bytes + tile * 128 + 16 * L);
                 al[i] = p.alpha[kr];
             }
         }
+        al[Q] = (LSTM && row_ok) ? p.bias[row] : 0.0f;
+        al[Q + 1] = (LSTM && row_ok) ? p.c_prev[(size_t)b0 * p.hidden + u0 + unit] : 0.0f;
+        al[Q + 2] = (LSTM && row_ok && b0 + 1 < p.batch) ? p.c_prev[(size_t)(b0 + 1) * p.hidden + u0 + unit] : 0.0f;
     };
     u32x4 k[Q], kn[Q];
-    float al[Q], aln[Q];
+    float al[Q + 3], aln[Q + 3];
     load_step(wave, k, al);
     if constexpr (FUSED) gemm8x2h_build_tile(p, lds_bytes, tile * kGemmHalfTileChunks, b0, tid, nthreads);
     else gemm8x2h_copy_tile(p, lds_bytes, tile * kGemmHalfTileChunks, b0, tid, nthreads);
@@ -157,15 +174,52 @@ __global__ __launch_bounds__(1024) void gemm8x2h_kernel(const QueryParams p) {
         }
         y0 = reduce8(y0);
         y1 = reduce8(y1);
-        const int row = 8 * s + rsub;
-        if (L == 0 && row < nrows) {
-            float* out = p.out + ((size_t)sp * p.batch + b0) * p.m + r0 + row;
-            out[0] = y0;
-            if (b0 + 1 < p.batch) out[p.m] = y1;
+        if constexpr (LSTM) {
+            // each half of the wave holds z_i, z_f, z_g, z_o of one unit in its four groups of 8 lanes
+            y0 += al[Q];
+            y1 += al[Q];
+            const int half = lane & 32;
+            const float zi0 = __shfl(y0, half, 64), zf0 = __shfl(y0, half + 8, 64);
+            const float zg0 = __shfl(y0, half + 16, 64), zo0 = __shfl(y0, half + 24, 64);
+            const float zi1 = __shfl(y1, half, 64), zf1 = __shfl(y1, half + 8, 64);
+            const float zg1 = __shfl(y1, half + 16, 64), zo1 = __shfl(y1, half + 24, 64);
+            const int unit = 2 * s + (lane >> 5);
+            if ((lane & 31) == 0 && unit < nunits) {
+                const size_t u = (size_t)b0 * p.hidden + u0 + unit;
+                float h, c;
+                lstm_cell_update(zi0, zf0, zg0, zo0, al[Q + 1], h, c);
+                p.out[u] = h;
+                p.c_out[u] = c;
+                if (b0 + 1 < p.batch) {
+                    lstm_cell_update(zi1, zf1, zg1, zo1, al[Q + 2], h, c);
+                    p.out[u + p.hidden] = h;
+                    p.c_out[u + p.hidden] = c;
+                }
+            }
+        } else {
+            const int row = 8 * s + rsub;
+            if (L == 0 && row < nrows) {
+                float* out = p.out + ((size_t)sp * p.batch + b0) * p.m + r0 + row;
+                out[0] = y0;
+                if (b0 + 1 < p.batch) out[p.m] = y1;
+            }
         }
 #pragma unroll
-        for (int i = 0; i < Q; ++i) { k[i] = kn[i]; al[i] = aln[i]; }
+        for (int i = 0; i < Q; ++i) k[i] = kn[i];
+#pragma unroll
+        for (int i = 0; i < Q + 3; ++i) al[i] = aln[i];
     }
+}
+
+template <int Q, bool FUSED>
+__global__ __launch_bounds__(1024) void gemm8x2h_kernel(const QueryParams p) {
+    gemm8x2h_body<Q, FUSED, false>(p, blockIdx.x);
+}
+
+// The LSTM cell step for two input vectors per workgroup (fused tables): see gemm8x2h_body.
+template <int Q>
+__global__ __launch_bounds__(1024) void lstm8x2h_kernel(const QueryParams p) {
+    gemm8x2h_body<Q, true, true>(p, blockIdx.x);
 }
 
 }  // namespace biq

@@ -110,13 +110,12 @@ __device__ __forceinline__ void gemv8_copy_tile(const QueryParams& p, char* lds_
 
 // MAXT = largest workgroup the instantiation may be launched with: 1024 threads leave 128 VGPRs
 // per lane (4 planes then keep 2 steps of keys in flight per wave instead of 4), 512 leave 256.
-template <int Q, bool FUSED, int MAXT = 1024>
-__global__ __launch_bounds__(MAXT) void gemv8_kernel(const QueryParams p) {
+template <int Q, bool FUSED, int MAXT>
+__device__ __forceinline__ void gemv8_body(const QueryParams& p, const int wg) {
     extern __shared__ __align__(16) float lds[];
     char* const lds_bytes = reinterpret_cast<char*>(lds);
     float* const yacc = lds + kGemvTileBytes / 4;  // [rows_per_wg], used when a workgroup walks > 1 tile
 
-    const int wg = blockIdx.x;
     const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
     if (task >= p.ntasks) return;
     const int sp = task % p.splits;
@@ -323,6 +322,11 @@ __global__ __launch_bounds__(MAXT) void gemv8_kernel(const QueryParams p) {
             __syncthreads();
         }
     }
+}
+
+template <int Q, bool FUSED, int MAXT = 1024>
+__global__ __launch_bounds__(MAXT) void gemv8_kernel(const QueryParams p) {
+    gemv8_body<Q, FUSED, MAXT>(p, blockIdx.x);
 }
 
 }  // namespace biq

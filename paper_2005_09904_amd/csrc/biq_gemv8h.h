@@ -66,12 +66,16 @@ __device__ __forceinline__ void gemv8h_copy_tile(const QueryParams& p, char* lds
 // One 256-chunk tile per workgroup; one step of 4 rows per wave at a time (row_mode 1) or one
 // row per wave at a time (row_mode 2); the first step's keys and scales are requested before the
 // tables are built.
-template <int Q, bool FUSED>
-__global__ __launch_bounds__(1024) void gemv8h_kernel(const QueryParams p) {
+//
+// LSTM = true (row_mode 1 only): the rows are the four gates i, f, g, o of an LSTM cell stacked
+// (m = 4 * hidden); the 4 rows of a wave step are the 4 gates of ONE hidden unit, so that the
+// step's epilogue has all four pre-activations in one wave and applies the cell update itself:
+// p.out receives h, p.c_out the new cell state.  rows_per_wg counts gate rows (4 per unit).
+template <int Q, bool FUSED, bool LSTM>
+__device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) {
     extern __shared__ __align__(16) float lds[];
     char* const lds_bytes = reinterpret_cast<char*>(lds);
 
-    const int wg = blockIdx.x;
     const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
     if (task >= p.ntasks) return;
     const int sp = task % p.splits;
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(1024) void gemv8h_kernel(const QueryParams p) {
     const uint32_t stride_bytes = (uint32_t)p.stride_dw * 4u;
     const int nrows = r1 - r0;
 
-    if (p.row_mode == 2) {
+    if (!LSTM && p.row_mode == 2) {
         // ---- one row per wave at a time: the 64 lanes hold the row's 64 key dwords (4 lookups
         // per lane and plane instead of 16), for workgroups with so few rows that most waves
         // would otherwise idle through the lookups.  Lane = 4*L1 + td1 holds dword td1 of the
@@ -188,24 +192,32 @@ __global__ __launch_bounds__(1024) void gemv8h_kernel(const QueryParams p) {
     }
 
     const bool have_keys = (uint32_t)(tile * 256 + L * 16) < stride_bytes;
-    const int nsteps = (nrows + 3) >> 2;
-    auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q]) {
-        const int row = 4 * s + rsub;
-        const bool ok = have_keys && s < nsteps && row < nrows;
+    // LSTM: the workgroup's hidden units [u0, u0 + nunits), one unit (4 gate rows) per step
+    const int u0 = LSTM ? rb * (p.rows_per_wg >> 2) : 0;
+    const int nunits = LSTM ? min(p.hidden, u0 + (p.rows_per_wg >> 2)) - u0 : 0;
+    const int nsteps = LSTM ? nunits : (nrows + 3) >> 2;
+    // al[0..Q) = the scales of this lane's row; LSTM: al[Q] = its bias, al[Q + 1] = the previous cell
+    // state of its unit (requested with the keys, so that the cell update waits for no memory access)
+    auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q + 2]) {
+        // row of the key matrix inside a plane: LSTM: gate rsub of unit u0 + s
+        const int row = LSTM ? rsub * p.hidden + u0 + s : r0 + 4 * s + rsub;
+        const bool ok = have_keys && s < nsteps && (LSTM || row < r1);
 #pragma unroll
         for (int i = 0; i < Q; ++i) {
             k[i] = (u32x4){0u, 0u, 0u, 0u};
             al[i] = 0.0f;
             if (ok) {
-                const size_t kr = (size_t)i * p.m + r0 + row;
+                const size_t kr = (size_t)i * p.m + row;
                 k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(
                     reinterpret_cast<const char*>(p.K) + kr * stride_bytes + tile * 256 + 16 * L));
                 al[i] = p.alpha[kr];
             }
         }
+        al[Q] = (LSTM && s < nsteps) ? p.bias[row] : 0.0f;
+        al[Q + 1] = (LSTM && s < nsteps) ? p.c_prev[u0 + s] : 0.0f;
     };
     u32x4 k[Q], kn[Q];
-    float al[Q], aln[Q];
+    float al[Q + 2], aln[Q + 2];
     load_step(wave, k, al);
     if constexpr (FUSED) gemv8h_build_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
     else gemv8h_copy_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
@@ -216,11 +228,37 @@ __global__ __launch_bounds__(1024) void gemv8h_kernel(const QueryParams p) {
 #pragma unroll
         for (int i = 0; i < Q; ++i) y = fmaf(al[i], lookup16(k[i]), y);
         y = reduce16(y);
-        const int row = 4 * s + rsub;
-        if (L == 0 && row < nrows) p.out[(size_t)sp * p.m + r0 + row] = y;
+        if constexpr (LSTM) {
+            // the four groups of 16 lanes hold z_i, z_f, z_g, z_o of unit u0 + s
+            y += al[Q];
+            const float zi = __shfl(y, 0, 64), zf = __shfl(y, 16, 64), zg = __shfl(y, 32, 64), zo = __shfl(y, 48, 64);
+            if (lane == 0) {
+                const size_t u = (size_t)(u0 + s);
+                float h, c;
+                lstm_cell_update(zi, zf, zg, zo, al[Q + 1], h, c);
+                p.out[u] = h;
+                p.c_out[u] = c;
+            }
+        } else {
+            const int row = 4 * s + rsub;
+            if (L == 0 && row < nrows) p.out[(size_t)sp * p.m + r0 + row] = y;
+        }
 #pragma unroll
-        for (int i = 0; i < Q; ++i) { k[i] = kn[i]; al[i] = aln[i]; }
+        for (int i = 0; i < Q; ++i) k[i] = kn[i];
+#pragma unroll
+        for (int i = 0; i < Q + 2; ++i) al[i] = aln[i];
     }
+}
+
+template <int Q, bool FUSED>
+__global__ __launch_bounds__(1024) void gemv8h_kernel(const QueryParams p) {
+    gemv8h_body<Q, FUSED, false>(p, blockIdx.x);
+}
+
+// The LSTM cell step for one input vector (fused tables): see gemv8h_body.
+template <int Q>
+__global__ __launch_bounds__(1024) void lstm8h_kernel(const QueryParams p) {
+    gemv8h_body<Q, true, true>(p, blockIdx.x);
 }
 
 }  // namespace biq

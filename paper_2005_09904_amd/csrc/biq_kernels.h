@@ -131,7 +131,26 @@ struct QueryParams {
     int ntasks, tasks_per_xcd;
     int row_mode;  // mu = 8 kernels: 0 = 64-row blocks per wave, 1 = one row step per wave
     int xcd_skew;  // gemv8 throughput mode: rows moved from each odd-XCD workgroup to an even-XCD one
+    // LSTM-cell epilogue (the LSTM instantiations of the half-table kernels only): the m = 4 * hidden
+    // rows are the gates i, f, g, o stacked; `out` receives h [batch][hidden]
+    const float* bias;    // [4 * hidden]
+    const float* c_prev;  // [batch][hidden]
+    float* c_out;         // [batch][hidden]
+    int hidden;
 };
+
+// One step of the textbook LSTM cell from the four gate pre-activations (bias included).
+// sigma(z) = 1 / (1 + e^-z) and tanh(x) = 1 - 2 / (e^2x + 1) through the hardware exponential and
+// reciprocal: absolute error of a few 2^-24 on values in [-1, 1] (and exact limits for large |z|),
+// below what the fp32 summation of z itself contributes.
+__device__ __forceinline__ float lstm_sigmoid(float z) { return __fdividef(1.0f, 1.0f + __expf(-z)); }
+__device__ __forceinline__ float lstm_tanh(float x) { return 1.0f - __fdividef(2.0f, __expf(2.0f * x) + 1.0f); }
+
+__device__ __forceinline__ void lstm_cell_update(float zi, float zf, float zg, float zo, float c_prev,
+                                                 float& h, float& c) {
+    c = fmaf(lstm_sigmoid(zf), c_prev, lstm_sigmoid(zi) * lstm_tanh(zg));
+    h = lstm_sigmoid(zo) * lstm_tanh(c);
+}
 
 template <int MU, int BT, int T>
 __device__ __forceinline__ void lookup_unit(const uint32_t (&w)[KeyUnit<MU>::UD],

@@ -55,6 +55,14 @@ hipError_t launch_gemv8h(bool fused, int q, const QueryParams& p, int grid, int 
 hipError_t launch_gemm8x2(bool fused, int q, const QueryParams& p, int grid, int threads, int lds, hipStream_t s);
 hipError_t launch_gemm8x2h(bool fused, int q, const QueryParams& p, int grid, int threads, int lds, hipStream_t s);
 
+// ---- fused LSTM cell step (half-table kernels with the cell update as epilogue) ----
+hipError_t launch_lstm8h(int q, const QueryParams& p, int grid, int threads, int lds, hipStream_t s);
+hipError_t launch_lstm8x2h(int q, const QueryParams& p, int grid, int threads, int lds, hipStream_t s);
+
+// ---- several small problems in one dispatch (kind: GroupKind) ----
+struct GroupParams;
+hipError_t launch_grouped(int kind, int q, const GroupParams& g, int grid, int lds, hipStream_t s);
+
 // ---- unpack + MFMA path ----
 hipError_t launch_xsplit(int ct, const float* X, mfma_u32x4* Xf, int n, int batch, int steps, long long total,
                          hipStream_t s);

@@ -36,6 +36,16 @@ hipError_t launch_gemm8x2(bool fused, int q, const QueryParams& qp, int grid, in
                  : launch_gemm8x2_q<false>(q, qp, grid, threads, lds, s);
 }
 
+hipError_t launch_lstm8x2h(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    switch (q) {
+        case 1: return launch_large_lds<lstm8x2h_kernel<1>, true>(qp, grid, threads, lds, s);
+        case 2: return launch_large_lds<lstm8x2h_kernel<2>, true>(qp, grid, threads, lds, s);
+        case 3: return launch_large_lds<lstm8x2h_kernel<3>, true>(qp, grid, threads, lds, s);
+        case 4: return launch_large_lds<lstm8x2h_kernel<4>, true>(qp, grid, threads, lds, s);
+    }
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_gemm8x2h(bool fused, int q, const QueryParams& qp, int grid, int threads, int lds,
                            hipStream_t s) {
     return fused ? launch_gemm8x2h_q<true>(q, qp, grid, threads, lds, s)

@@ -45,6 +45,16 @@ hipError_t launch_gemv8(bool fused, int q, const QueryParams& qp, int grid, int 
                  : launch_gemv8_q<false>(q, qp, grid, threads, lds, s);
 }
 
+hipError_t launch_lstm8h(int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
+    switch (q) {
+        case 1: return launch_large_lds<lstm8h_kernel<1>, true>(qp, grid, threads, lds, s);
+        case 2: return launch_large_lds<lstm8h_kernel<2>, true>(qp, grid, threads, lds, s);
+        case 3: return launch_large_lds<lstm8h_kernel<3>, true>(qp, grid, threads, lds, s);
+        case 4: return launch_large_lds<lstm8h_kernel<4>, true>(qp, grid, threads, lds, s);
+    }
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_gemv8h(bool fused, int q, const QueryParams& qp, int grid, int threads, int lds, hipStream_t s) {
     return fused ? launch_gemv8h_q<true>(q, qp, grid, threads, lds, s)
                  : launch_gemv8h_q<false>(q, qp, grid, threads, lds, s);

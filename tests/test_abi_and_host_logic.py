@@ -146,6 +146,39 @@ def test_argument_errors_are_reported_before_any_launch(biq):
     assert lib.biq_gemm_ex(fake, fake, fake, fake, 4, 4, 1, 1, 8, None, None, 0, None) == biq.BIQ_EINVAL
 
 
+def test_grouped_and_lstm_argument_errors_are_reported_before_any_launch(biq):
+    lib = biq.load_library()
+    fake = 0x1000  # never dereferenced: every call below fails its checks first
+    assert lib.biq_gemm_grouped(None, 1, 8, None) == biq.BIQ_EINVAL
+    arr = (biq.BiqProblem * 2)()
+    for d, n in zip(arr, (512, 512)):
+        d.K, d.alpha, d.X, d.Y, d.m, d.n, d.q, d.batch = fake, fake, fake, fake, 64, n, 1, 1
+    assert lib.biq_gemm_grouped(arr, 0, 8, None) == biq.BIQ_EINVAL
+    arr[1].Y = None
+    assert lib.biq_gemm_grouped(arr, 2, 8, None) == biq.BIQ_EINVAL
+    arr[1].Y, arr[1].n = fake, 4096           # wider than one tile of tables: needs biq_gemm
+    assert lib.biq_gemm_grouped(arr, 2, 8, None) == biq.BIQ_EUNSUPPORTED
+    arr[1].n, arr[1].q = 512, 5               # more planes than the specialised kernels take
+    assert lib.biq_gemm_grouped(arr, 2, 8, None) == biq.BIQ_EUNSUPPORTED
+    assert lib.biq_gemm_grouped(arr, 1, 6, None) == biq.BIQ_EUNSUPPORTED
+    args = [fake] * 7
+    assert lib.biq_lstm_cell(*args, 0, 512, 2, 1, 8, None) == biq.BIQ_EINVAL
+    assert lib.biq_lstm_cell(fake, fake, None, fake, fake, fake, fake, 64, 512, 2, 1, 8, None) == biq.BIQ_EINVAL
+    assert lib.biq_lstm_cell(*args, 64, 4096, 2, 1, 8, None) == biq.BIQ_EUNSUPPORTED
+    assert lib.biq_lstm_cell(*args, 64, 2048, 2, 2, 8, None) == biq.BIQ_EUNSUPPORTED
+    assert lib.biq_lstm_cell(*args, 64, 512, 2, 1, 7, None) == biq.BIQ_EUNSUPPORTED
+
+
+def test_shapes_beyond_the_tuned_kernels_fall_back_or_are_refused(biq):
+    """Rows so long that a tuned kernel's 32-bit offsets would overflow: the planner must hand out a
+    finished plan of another kernel (or an error), never an unfinished one."""
+    for (m, n, q, b) in [(1 << 20, 3000000, 1, 1), (100000, 2200000, 2, 1), (4096, 3000000, 1, 2)]:
+        p = biq.biq_plan_get(m, n, q, b, 8)
+        assert p.chunk_splits >= 1 and p.lds_bytes > 0 and p.row_blocks >= 1
+        biq.biq_plan_check(m, n, q, b, 8, p)
+        assert biq.biq_workspace_bytes(m, n, q, b, 8) == biq.biq_plan_workspace_bytes(p, m, b)
+
+
 def test_missing_library_fails_loudly(biq, tmp_path):
     with pytest.raises(FileNotFoundError):
         biq.load_library(str(tmp_path / "libbiq_missing.so"))
