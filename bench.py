@@ -478,6 +478,40 @@ def main() -> int:
             del Xd, Ld
             torch.cuda.empty_cache()
         out["build_lut"] = luts
+        # Table build methods (end of Sec. III-B): every entry from pair sums (table_fill 0, the default)
+        # against the order of Algorithm 1 (table_fill 1), on launches that are all table build: 8 rows
+        # per workgroup, 16 and 32 tiles per workgroup; the slope is the cost of one more 128 KiB tile.
+        fill = {}
+        for tf in (0, 1):
+            per = {}
+            for tiles in (16, 32):
+                w = Workload("table_fill_%d_tiles_%d" % (tf, tiles), 2048, 1024 * tiles, 1, 1, 8, "uniform")
+                plan = biq.BiqPlan()
+                plan.kernel, plan.threads, plan.chunks_per_tile, plan.batch_tile = 1, 1024, 128, 1
+                plan.tiles_per_split, plan.rows_per_wg, plan.table_fill = tiles, 8, tf
+                p = Problem(biq, torch, w, 2, real_first=False, plan=biq.biq_plan_check(w.m, w.n, 1, 1, 8, plan))
+                per[tiles] = time_steps(torch, p, 100, 10).median * 1e6
+                del p
+            fill["algorithm1_order" if tf else "pair_sums"] = {
+                "us_16_tiles": per[16], "us_32_tiles": per[32], "us_per_tile": (per[32] - per[16]) / 16}
+            log("table fill %s: %.2f us per 128 KiB tile (16 tiles %.1f us, 32 tiles %.1f us)" %
+                ("Algorithm 1 order" if tf else "pair sums", (per[32] - per[16]) / 16, per[16], per[32]))
+        out["table_fill_study"] = fill
+        # LUT-unit sweep on the FFN up-projection with the lookup-table kernels only, one and 128 input
+        # vectors: what mu costs on this chip (Sec. IV-A's rule counts operations, not table bytes)
+        sweep = []
+        for bb in (1, 128):
+            for mu in (4, 6, 8, 9, 10):
+                w = replace(CONFIGS["cfg5_ffn_up_q2_b128"], batch=bb, mu=mu, name="cfg5_ffn_up_q2_b%d_mu%d" % (bb, mu))
+                plan = biq.biq_plan_get_lut(w.m, w.n, w.q, w.batch, w.mu)
+                p = Problem(biq, torch, w, 4, real_first=False, plan=plan)
+                t = time_steps(torch, p, 20, 3, regions=5)
+                sweep.append({"batch": bb, "mu": mu, "kernel": biq.biq_kernel_name(plan.kernel),
+                              "us_per_call": t.median * 1e6})
+                log("mu sweep batch %d mu %d [%s]: %.1f us" % (bb, mu, sweep[-1]["kernel"], t.median * 1e6))
+                del p
+                torch.cuda.empty_cache()
+        out["mu_sweep_lut_kernels"] = sweep
         # small layers that do not depend on each other, L = 8 per dispatch (grouped launch) against the
         # same 8 as separate calls; and the LSTM cell step with its update fused (cfg 3's shape)
         class Calls:

@@ -125,7 +125,13 @@ typedef struct {
                             sums are added in LDS (0 is read as 1).  rows_per_wg is then
                             (4 / wave_splits) * 32 * r with r row tiles per wave and plane,
                             r in {1, 2, 4}, q * r <= 4                                       */
-    int reserved[3];
+    int table_fill;      /* GEMV kernel, fused tables: 0 = every entry from the chunk's pair sums (a direct,
+                            GEMM-like fill), 1 = the order of Algorithm 1: a block's first entry, then
+                            each further entry of the lower half from an earlier one by adding 2 x_t,
+                            the upper half by negation.  Same tables up to rounding; kept selectable
+                            so that the two build methods Sec. III-B weighs can be timed against each
+                            other (the default, 0, is the faster one here)                       */
+    int reserved[2];
 } biq_plan;
 
 biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan);

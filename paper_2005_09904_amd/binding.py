@@ -29,7 +29,8 @@ class BiqPlan(ctypes.Structure):
         ("kernel", ctypes.c_int), ("threads", ctypes.c_int), ("chunks_per_tile", ctypes.c_int),
         ("batch_tile", ctypes.c_int), ("chunk_splits", ctypes.c_int), ("tiles_per_split", ctypes.c_int),
         ("rows_per_wg", ctypes.c_int), ("row_blocks", ctypes.c_int), ("batch_tiles", ctypes.c_int),
-        ("lds_bytes", ctypes.c_int), ("row_mode", ctypes.c_int), ("xcd_skew", ctypes.c_int), ("wave_splits", ctypes.c_int), ("reserved", ctypes.c_int * 3),
+        ("lds_bytes", ctypes.c_int), ("row_mode", ctypes.c_int), ("xcd_skew", ctypes.c_int), ("wave_splits", ctypes.c_int), ("table_fill", ctypes.c_int),
+        ("reserved", ctypes.c_int * 2),
     ]
 
     def as_dict(self):

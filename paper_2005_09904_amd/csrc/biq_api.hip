@@ -107,6 +107,7 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     if (pl.kernel < 0 || pl.kernel >= KERNEL_COUNT) return false;
     if (pl.kernel == KERNEL_UNPACK_MFMA) return plan_finish_unpack(pl, m, n, q, batch);
     if (pl.wave_splits != 0) return false;  // unpack_mfma only
+    if (pl.table_fill != 0 && !(pl.table_fill == 1 && pl.kernel == KERNEL_GEMV8 && pl.row_mode == 0)) return false;
     if (pl.threads < 64 || pl.threads > 1024 || pl.threads % 64) return false;
     if (pl.kernel == KERNEL_GEMV8) {
         // mu = 8, one input vector, at most 4 planes; one 128-chunk tile per workgroup
@@ -439,6 +440,7 @@ void fill_query_params(QueryParams& qp, const biq_plan& pl, const uint8_t* K, co
     qp.tasks_per_xcd = ceil_div(qp.ntasks, kNumXcd);
     qp.row_mode = pl.row_mode;
     qp.xcd_skew = pl.xcd_skew;
+    qp.table_fill = pl.table_fill;
 }
 
 // Plan of one problem of a grouped launch: mu = 8, at most 4 planes, a single dispatch without
@@ -530,6 +532,7 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
         if (!plan_default(pl, m, n, q, batch, mu, !fused)) return BIQ_EUNSUPPORTED;
     }
     if (pl.kernel == KERNEL_UNPACK_MFMA && !fused) return BIQ_EINVAL;  // that kernel reads X, not tables
+    if (pl.table_fill != 0 && !fused) return BIQ_EINVAL;               // a build method needs tables to build
     const size_t need = plan_workspace(pl, m, batch);
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return BIQ_EWORKSPACE;

@@ -82,6 +82,47 @@ __device__ __forceinline__ void gemv8_job_build(const QueryParams& p, char* lds_
     for (int l = 0; l < 32; ++l) *reinterpret_cast<float*>(dst + l * 256) = ent[l];
 }
 
+// The same 32 entries in the order of Algorithm 1 (dynamic programming): the job's two blocks of 16
+// keys start from their first entry (all of the block's low four signs negative), every further
+// entry of a block comes from an earlier one by adding 2 x_t (t = highest set bit of its offset in
+// the block), and entries of the upper half of the table are the negated entries of the lower half:
+// the job of keys [32 hq, 32 hq + 32), hq < 4, also writes keys [224 - 32 hq, 256 - 32 hq) = the
+// complements, so only jobs with hq < 4 do anything here and each writes 64 entries.
+__device__ __forceinline__ void gemv8_job_build_dp(const QueryParams& p, char* lds_bytes, int c0, int job,
+                                                   float (&x)[8]) {
+    const int L = job & 7, e = (job >> 3) & 3, td = (job >> 5) & 3, hq = job >> 7;
+    if (hq >= 4) return;
+    chunk8_zero_tail(p.n, c0 + gemv8_job_chunk(job), x);
+    float x2[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x2[j] = 2.0f * x[j];
+    float r0 = x[0];  // entry of key 0: -(x_0 + ... + x_7)
+#pragma unroll
+    for (int j = 1; j < 8; ++j) r0 += x[j];
+    r0 = -r0;
+    // first entry of the job's two blocks: bits 5, 6 of the key from hq, bit 4 = block
+    float base = r0;
+    base = (hq & 1) ? base + x2[5] : base;
+    base = (hq & 2) ? base + x2[6] : base;
+    char* dst = lds_bytes + gemv8_slot_offset(L, td, e);
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+        float r[16];
+        r[0] = blk ? base + x2[4] : base;
+#pragma unroll
+        for (int k = 1; k < 16; ++k) {
+            const int t = 31 - __builtin_clz((unsigned)k);
+            r[k] = r[k - (1 << t)] + x2[t];
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int key = 32 * hq + 16 * blk + k;
+            *reinterpret_cast<float*>(dst + key * 256) = r[k];
+            *reinterpret_cast<float*>(dst + (255 - key) * 256) = -r[k];
+        }
+    }
+}
+
 __device__ __forceinline__ bool x_rows_vectorizable(const QueryParams& p) {
     return ((p.n & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
 }
@@ -263,7 +304,18 @@ __device__ __forceinline__ void gemv8_body(const QueryParams& p, const int wg) {
     if (x_ahead) gemv8_job_x_ahead(p, tile0 * kGemvTileChunks, tid, xa);
     auto build = [&](int tile) {
         if constexpr (FUSED) {
-            if (x_ahead) gemv8_job_build(p, lds_bytes, tile * kGemvTileChunks, tid, xa);
+            if (p.table_fill == 1) {  // Algorithm 1's order (needs all 1024 jobs: 512 do the work)
+                for (int job = tid; job < 1024; job += nthreads) {
+                    float x[8];
+                    if (x_ahead) {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) x[j] = xa[j];
+                    } else {
+                        load_chunk8(p.X, p.n, 1, 0, tile * kGemvTileChunks + gemv8_job_chunk(job), x_rows_vectorizable(p), x);
+                    }
+                    gemv8_job_build_dp(p, lds_bytes, tile * kGemvTileChunks, job, x);
+                }
+            } else if (x_ahead) gemv8_job_build(p, lds_bytes, tile * kGemvTileChunks, tid, xa);
             else gemv8_build_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
             if (x_ahead && tile + 1 < tile1) gemv8_job_x_ahead(p, (tile + 1) * kGemvTileChunks, tid, xa);
         } else {

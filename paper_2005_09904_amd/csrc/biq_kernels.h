@@ -131,6 +131,7 @@ struct QueryParams {
     int ntasks, tasks_per_xcd;
     int row_mode;  // mu = 8 kernels: 0 = 64-row blocks per wave, 1 = one row step per wave
     int xcd_skew;  // gemv8 throughput mode: rows moved from each odd-XCD workgroup to an even-XCD one
+    int table_fill;  // gemv8, fused tables: 0 = direct fill from pair sums, 1 = Algorithm 1's order
     // LSTM-cell epilogue (the LSTM instantiations of the half-table kernels only): the m = 4 * hidden
     // rows are the gates i, f, g, o stacked; `out` receives h [batch][hidden]
     const float* bias;    // [4 * hidden]

@@ -268,9 +268,21 @@ def test_explicit_plans_give_the_same_result(biq, oracle):
         ref = oracle.gemm_dense(B, alpha, X)
         for spec in [(1, 1024, 128, 1, 5, 8, 0), (1, 512, 128, 1, 5, 72, 0), (1, 1024, 128, 1, 2, 520, 0),
                      (1, 1024, 128, 1, 5, 2000, 0)]:
-            _say("plan q=%d n=%d " % (q, n2) + str(spec))
-            Y = gpu_gemm(biq, K, ad, Xd, 2000, n2, q, mu, plan=_plan(biq, *spec)).cpu().numpy()
-            assert_within_tolerance(Y, ref, alpha, X, "plan")
+            for fill in (0, 1):   # tables from pair sums / in the order of Algorithm 1
+                _say("plan q=%d n=%d fill=%d " % (q, n2, fill) + str(spec))
+                plan = _plan(biq, *spec)
+                plan.table_fill = fill
+                Y = gpu_gemm(biq, K, ad, Xd, 2000, n2, q, mu, plan=plan).cpu().numpy()
+                assert_within_tolerance(Y, ref, alpha, X, "plan")
+    # Algorithm 1's order on exactly representable inputs: bit for bit, like every other tiling
+    from paper_2005_09904_amd.workloads import Workload, make_exact_inputs
+
+    B, alpha, X = make_exact_inputs(Workload("exact", 600, 3000, 2, 1, 8, "uniform", seed=71))
+    Bd, ad, Xd = device_inputs(B, alpha, X)
+    plan = _plan(biq, 1, 1024, 128, 1, 3, 64, 0)
+    plan.table_fill = 1
+    Y = gpu_gemm(biq, gpu_pack(biq, Bd, mu), ad, Xd, 600, 3000, 2, mu, plan=plan).cpu().numpy()
+    assert np.array_equal(Y.astype(np.float64), oracle.gemm_dense(B, alpha, X))
 
 
 @pytest.mark.parametrize("q", [1, 2, 3, 4, 5])
