@@ -51,6 +51,25 @@ __device__ __forceinline__ void gemm8x2_build_tile(const QueryParams& p, char* l
     }
 }
 
+// One build job (vector, chunk, 32 keys) in two halves: its 8 inputs requested ahead of time (rows
+// that allow 128-bit loads; an input vector past the batch reads the last one), and the entries
+// built from them (inputs past the row or past the batch count as zero).
+__device__ __forceinline__ void gemm8x2_job_x_ahead(const QueryParams& p, int c0, int b0, int job, float (&x)[8]) {
+    const int L = job & 3, e = (job >> 2) & 3, td = (job >> 4) & 3, v = (job >> 6) & 1;
+    load_chunk8_raw(p.X + (size_t)min(b0 + v, p.batch - 1) * p.n, p.n, c0 + 16 * L + 4 * td + e, x);
+}
+
+__device__ __forceinline__ void gemm8x2_job_build(const QueryParams& p, char* lds_bytes, int c0, int b0, int job,
+                                                  float (&x)[8]) {
+    const int L = job & 3, e = (job >> 2) & 3, td = (job >> 4) & 3, v = (job >> 6) & 1, hq = job >> 7;
+    chunk8_zero_tail(b0 + v < p.batch ? p.n : 0, c0 + 16 * L + 4 * td + e, x);
+    float ent[32];
+    table32(x, (uint32_t)hq, ent);
+    char* dst = lds_bytes + gemm8x2_slot_offset(L, td, e, v) + (hq * 32) * 256;
+#pragma unroll
+    for (int l = 0; l < 32; ++l) *reinterpret_cast<float*>(dst + l * 256) = ent[l];
+}
+
 // The same tile copied from tables in device memory (LUT [C][256][batch]).
 __device__ __forceinline__ void gemm8x2_copy_tile(const QueryParams& p, char* lds_bytes, int c0,
                                                   int b0, int tid, int nthreads) {
@@ -189,83 +208,108 @@ __global__ __launch_bounds__(1024) void gemm8x2_kernel(const QueryParams p) {
 
     // ---- throughput mode.  Rows in blocks of 64 per wave: in step t (0..3) row group g reads
     // row 4*g + t and the lane with L == t keeps the row's sums, so after 4 steps lane j holds
-    // row j of the block.
+    // row j of the block.  Block b of a tile goes to wave b mod nwaves, every wave runs the same
+    // number of block iterations per tile.  As in the GEMV kernel all loads are issued
+    // unconditionally from clamped addresses (so the compiler can count the requests in flight
+    // instead of draining them), the ring of PD steps per wave runs on across tile boundaries, and
+    // the next tile's inputs are fetched a tile ahead.
     const int nblk = (nrows + 63) >> 6;
+    const int iters = (nblk + nwaves - 1) / nwaves;  // block iterations per wave and tile, >= 1
+    constexpr int PD = (Q == 1) ? 4 : (Q <= 3 ? 2 : 1);  // steps in flight per wave (VGPR budget 128)
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const char* kbase[Q];
+    const char* abase[Q];
+#pragma unroll
+    for (int i = 0; i < Q; ++i) {
+        kbase[i] = reinterpret_cast<const char*>(p.K) + ((size_t)i * p.m + r0) * stride_bytes;
+        abase[i] = reinterpret_cast<const char*>(p.alpha + (size_t)i * p.m + r0);
+    }
+    float* const obase = p.out + ((size_t)sp * p.batch + b0) * p.m + r0;
+    const uint32_t last_row = (uint32_t)(nrows - 1);
+    auto load_iter = [&](int tile, int bk, int t, u32x4 (&k)[Q]) {
+        const bool there = bk < nblk && tile < tile1;  // the same for the whole wave
+        const uint32_t row = min((uint32_t)(64 * bk + 4 * rsub + t), last_row);
+        const uint32_t seg = min((uint32_t)(tile * 64 + L * 16), stride_bytes - 16u);
+        const uint32_t voff = there ? row * stride_bytes + seg : 0u;
+#pragma unroll
+        for (int i = 0; i < Q; ++i) k[i] = *reinterpret_cast<const u32x4*>(kbase[i] + voff);
+    };
+    const bool x_ahead = FUSED && nthreads == 1024 && x_rows_vectorizable(p);
+    float xa[8];
+    if (x_ahead) gemm8x2_job_x_ahead(p, tile0 * kGemmTileChunks, b0, tid, xa);
+    auto build = [&](int tile) {
+        if constexpr (FUSED) {
+            if (x_ahead) gemm8x2_job_build(p, lds_bytes, tile * kGemmTileChunks, b0, tid, xa);
+            else gemm8x2_build_tile(p, lds_bytes, tile * kGemmTileChunks, b0, tid, nthreads);
+            if (x_ahead && tile + 1 < tile1) gemm8x2_job_x_ahead(p, (tile + 1) * kGemmTileChunks, b0, tid, xa);
+        } else {
+            gemm8x2_copy_tile(p, lds_bytes, tile * kGemmTileChunks, b0, tid, nthreads);
+        }
+    };
+
+    // start-up: one step of keys per wave, the tables, then the rest of the ring
+    u32x4 buf[PD][Q];
+    load_iter(tile0, wave_u, 0, buf[0]);
+    build(tile0);
+    __syncthreads();
+#pragma unroll
+    for (int s = 1; s < PD; ++s) load_iter(tile0, wave_u, s, buf[s]);
 
     for (int tile = tile0; tile < tile1; ++tile) {
-        const int c0 = tile * kGemmTileChunks;
-        if (tile != tile0) __syncthreads();
-
-        if constexpr (FUSED) gemm8x2_build_tile(p, lds_bytes, c0, b0, tid, nthreads);
-        else gemm8x2_copy_tile(p, lds_bytes, c0, b0, tid, nthreads);
-        __syncthreads();
-
-        // ---- stream the rows ---------------------------------------------------------------------
-        const bool have_keys = (uint32_t)(tile * 64 + L * 16) < stride_bytes;
-        const char* kbase[Q];
-#pragma unroll
-        for (int i = 0; i < Q; ++i)
-            kbase[i] = reinterpret_cast<const char*>(p.K) +
-                       ((size_t)i * p.m + r0) * stride_bytes + (size_t)tile * 64;
-
-        auto load_iter = [&](int bk, int t, u32x4 (&k)[Q]) {
-            const uint32_t row = (uint32_t)(64 * bk + 4 * rsub + t);  // relative to r0
-            const bool ok = have_keys && bk < nblk && (int)row < r1 - r0;
-            const uint32_t voff = row * stride_bytes + (uint32_t)(16 * L);
-#pragma unroll
-            for (int i = 0; i < Q; ++i) {
-                k[i] = (u32x4){0u, 0u, 0u, 0u};
-                if (ok) k[i] = *reinterpret_cast<const u32x4*>(kbase[i] + voff);
-            }
-        };
-
-        constexpr int PD = (Q == 1) ? 4 : (Q == 2 ? 2 : 1);  // steps in flight per wave (VGPR budget 128)
-        u32x4 buf[PD][Q];
-        int bk = wave;
-#pragma unroll
-        for (int s = 0; s < PD; ++s) load_iter(bk, s, buf[s]);
-        for (; bk < nblk; bk += nwaves) {
+        int it = 0;
+        do {
+            const int bk = wave_u + it * nwaves;
+            const bool last = it + 1 >= iters;
+            const int next_bk = last ? wave_u : bk + nwaves;
+            const int next_tile = last ? tile + 1 : tile;
             const int row_l = 64 * bk + lane;  // the row this lane finishes, relative to r0
-            const bool row_ok = row_l < r1 - r0;
             float al[Q], keep0[Q], keep1[Q];
 #pragma unroll
             for (int i = 0; i < Q; ++i) {
-                al[i] = row_ok ? p.alpha[(size_t)i * p.m + r0 + row_l] : 0.0f;
+                al[i] = *reinterpret_cast<const float*>(abase[i] + 4u * min((uint32_t)row_l, last_row));
                 keep0[i] = 0.0f;
                 keep1[i] = 0.0f;
             }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
+                if (bk < nblk) {  // the same for the whole wave
+#pragma unroll
+                    for (int i = 0; i < Q; ++i) {
+                        float s0, s1;
+                        lookup16(buf[t % PD][i], s0, s1);
+                        s0 = reduce4(s0);
+                        s1 = reduce4(s1);
+                        keep0[i] = (L == t) ? s0 : keep0[i];
+                        keep1[i] = (L == t) ? s1 : keep1[i];
+                    }
+                }
+                if (t + PD < 4) load_iter(tile, bk, t + PD, buf[t % PD]);
+                else load_iter(next_tile, next_bk, t + PD - 4, buf[t % PD]);
+            }
+            if (bk < nblk) {
+                float y0 = 0.0f, y1 = 0.0f;
 #pragma unroll
                 for (int i = 0; i < Q; ++i) {
-                    float s0, s1;
-                    lookup16(buf[t % PD][i], s0, s1);
-                    s0 = reduce4(s0);
-                    s1 = reduce4(s1);
-                    keep0[i] = (L == t) ? s0 : keep0[i];
-                    keep1[i] = (L == t) ? s1 : keep1[i];
+                    y0 = fmaf(al[i], keep0[i], y0);
+                    y1 = fmaf(al[i], keep1[i], y1);
                 }
-                if (t + PD < 4) load_iter(bk, t + PD, buf[t % PD]);
-                else load_iter(bk + nwaves, t + PD - 4, buf[t % PD]);
+                if (tile != tile0) {
+                    const float2 prev = *reinterpret_cast<const float2*>(yacc + 2 * row_l);
+                    y0 += prev.x;
+                    y1 += prev.y;
+                }
+                if (tile + 1 < tile1) {
+                    *reinterpret_cast<float2*>(yacc + 2 * row_l) = make_float2(y0, y1);
+                } else if (row_l < nrows) {
+                    obase[row_l] = y0;
+                    if (b0 + 1 < p.batch) obase[p.m + row_l] = y1;
+                }
             }
-            float y0 = 0.0f, y1 = 0.0f;
-#pragma unroll
-            for (int i = 0; i < Q; ++i) {
-                y0 = fmaf(al[i], keep0[i], y0);
-                y1 = fmaf(al[i], keep1[i], y1);
-            }
-            if (tile != tile0) {
-                const float2 prev = *reinterpret_cast<const float2*>(yacc + 2 * row_l);
-                y0 += prev.x;
-                y1 += prev.y;
-            }
-            if (tile + 1 < tile1) {
-                *reinterpret_cast<float2*>(yacc + 2 * row_l) = make_float2(y0, y1);
-            } else if (row_ok) {
-                float* out = p.out + ((size_t)sp * p.batch + b0) * p.m + r0 + row_l;
-                out[0] = y0;
-                if (b0 + 1 < p.batch) out[p.m] = y1;
-            }
+        } while (++it < iters);
+        if (tile + 1 < tile1) {
+            __syncthreads();  // every wave is done with these tables
+            build(tile + 1);
+            __syncthreads();
         }
     }
 }
