@@ -248,9 +248,14 @@ bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool table
             pl.tiles_per_split = tiles;
             int rows = ceil_div(ceil_div(m, kNumCu), 64) * 64;
             pl.rows_per_wg = rows > 8192 ? 8192 : rows;
-            // odd XCDs stream a few per cent slower: move 3 % of their rows to the even ones (measured best: 2-5 %)
-            if (ceil_div(m, pl.rows_per_wg) % kNumXcd == 0) {
-                pl.xcd_skew = ((pl.rows_per_wg * 3 / 100 + 32) / 64) * 64;
+            // Odd XCDs stream slower than even ones, by an amount that differs from box to box and
+            // grows with the run time (in-kernel time stamps, back-to-back launches, equal shares:
+            // workgroups on odd XCDs end 6 % later on one box and 13 % on another with 4096 rows
+            // each, 0-7 % with 1024 rows): rows are moved from the odd to the even XCDs, 4.5 % of a
+            // workgroup's share from 4096 rows on, 3 % from 2048, in units of 32 rows.
+            if (ceil_div(m, pl.rows_per_wg) % kNumXcd == 0 && pl.rows_per_wg >= 2048) {
+                const int permille = pl.rows_per_wg >= 4096 ? 45 : 30;
+                pl.xcd_skew = ((pl.rows_per_wg * permille / 1000 + 16) / 32) * 32;
                 if (tiles > 1 && pl.rows_per_wg + pl.xcd_skew > 8192) pl.xcd_skew = 0;
             }
         } else if (C > kGemvTileChunks && (long long)m * ceil_div(C, kGemvHalfTileChunks) <= 256ll * kNumCu) {
@@ -545,6 +550,9 @@ biq_status run_query(bool fused, const uint8_t* K, const float* alpha, const flo
     QueryParams qp{};
     fill_query_params(qp, pl, K, alpha, X, LUT, pl.chunk_splits > 1 ? reinterpret_cast<float*>(workspace) : Y, m, n, q,
                       batch, mu);
+#ifdef BIQ_TRACE
+    if (fused) qp.LUT = reinterpret_cast<const float*>(workspace);  // time stamps of a trace build go here
+#endif
     const int grid = qp.tasks_per_xcd * kNumXcd;
 
     hipError_t e;

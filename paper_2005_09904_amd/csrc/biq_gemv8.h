@@ -22,6 +22,19 @@
 
 namespace biq {
 
+// Time stamps of a trace build (-DBIQ_TRACE, never the product's): lane 0 of every wave writes the
+// 100 MHz wall clock into slot i of its entry in the buffer passed as QueryParams::LUT.
+#ifdef BIQ_TRACE
+#define BIQ_STAMP(p, i)                                                                               \
+    do {                                                                                              \
+        if ((threadIdx.x & 63) == 0)                                                                  \
+            reinterpret_cast<unsigned long long*>(const_cast<float*>((p).LUT))                        \
+                [((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (i)] = wall_clock64();          \
+    } while (0)
+#else
+#define BIQ_STAMP(p, i) do { } while (0)
+#endif
+
 constexpr int kGemvTileChunks = 128;
 constexpr int kGemvTileBytes = kGemvTileChunks * 256 * 4;  // 131072
 
@@ -327,9 +340,12 @@ __device__ __forceinline__ void gemv8_body(const QueryParams& p, const int wg) {
     // are built, then the rest of the ring is requested.  (A CU's address unit takes about 20 clocks
     // per 128-bit wave load: the whole ring first would put the table build 2 us behind it.)
     u32x4 buf[PD][Q];
+    BIQ_STAMP(p, 0);
     load_iter(tile0, wave_u, 0, buf[0]);
+    BIQ_STAMP(p, 1);
     build(tile0);
     __syncthreads();
+    BIQ_STAMP(p, 2);
 #pragma unroll
     for (int s = 1; s < PD; ++s) load_iter(tile0, wave_u, s, buf[s]);
 
@@ -369,11 +385,15 @@ __device__ __forceinline__ void gemv8_body(const QueryParams& p, const int wg) {
             }
         } while (++it < iters);
         if (tile + 1 < tile1) {
+            BIQ_STAMP(p, 3);
             __syncthreads();  // every wave is done with these tables
+            BIQ_STAMP(p, 4);
             build(tile + 1);
             __syncthreads();
+            BIQ_STAMP(p, 5);
         }
     }
+    BIQ_STAMP(p, 6);
 }
 
 template <int Q, bool FUSED, int MAXT = 1024>
