@@ -27,6 +27,18 @@
  *     across this boundary.  On an error no kernel has been launched unless
  *     the status is BIQ_EHIP.
  *   - Inputs are assumed finite; behaviour on NaN/Inf is unspecified.
+ *   - Threads: every function may be called from several host threads at once.  The library
+ *     keeps no state between calls apart from per-device one-time set-up (the opt-in to large
+ *     LDS per kernel, the address of the biq_gemm_noalloc buffer), which is idempotent: two
+ *     threads racing through it do the same work twice and store the same values.  Calls use
+ *     the calling thread's current device.  What the caller must keep apart is the memory:
+ *     two calls whose workspace or output buffers overlap (and any two biq_gemm_noalloc calls
+ *     on one GPU) must not be in flight at the same time, whatever threads or streams issue them.
+ *   - Beyond the paper's problem statement (pack, build tables, query; m, n, q, batch, mu):
+ *     biq_query takes a workspace like biq_gemm (wide rows are split over workgroups in both),
+ *     mu goes up to 10 (keys of 9 and 10 bits are served by the generic kernel;
+ *     biq_unpack_keys16 returns them), and biq_plan_*, biq_gemm_ex, biq_gemm_grouped,
+ *     biq_lstm_cell, biq_quantize and biq_gemm_noalloc are additions.
  *
  * Data layouts
  *   B      int8   [q][m][n]            +1 / -1 (bit = (B > 0); other values are
@@ -152,7 +164,8 @@ const char* biq_kernel_name(int kernel);
 
 /*
  * Key packing (Sec. III-B: mu consecutive binary weights of a row become the
- * integer key; K "can be loaded in advance").  B device int8 [q][m][n] -> K device
+ * integer key; the weights are fixed at inference time, so K is produced once, ahead of the
+ * multiplies).  B device int8 [q][m][n] -> K device
  * uint8 [q][m][stride].  The byte format does not depend on mu (see above); mu is
  * validated only.  Bit = (B > 0).
  */
@@ -200,9 +213,9 @@ biq_status biq_query(const uint8_t* K, const float* alpha, const float* LUT, flo
 
 /*
  * The fused multiply (Algorithm 2 as a whole + Eq. 2): tables are built on the
- * fly in LDS from X and never written to device memory (Sec. III-B: "not taken
- * from DRAM"), keys are streamed once, partial sums are combined in a fixed
- * order (deterministic: same inputs, same bits).
+ * fly in LDS from X and never written to device memory (Sec. III-B builds them per
+ * tile in fast memory instead of fetching them from DRAM), keys are streamed once,
+ * partial sums are combined in a fixed order (deterministic: same inputs, same bits).
  *
  * For many input vectors (see biq_plan_get / biq_plan_get_lut) the default plan is the
  * unpack_mfma kernel instead: the "GEMM with unpacking" alternative of Sec. IV-B
