@@ -93,33 +93,42 @@ __device__ __forceinline__ void gemm8x2h_body(const QueryParams& p, const int wg
 
     // v_perm_b32: S0 = key dword, S1 = base; byte 0 <- base byte 0, byte 1 <- key byte
     // (te + rho) & 3, byte 2 <- base byte 2 (td >> 1), byte 3 <- 0.
-    uint32_t sel[4], base[2][4];
+    uint32_t sel[4], sgn_sel[4], base[2][4];
 #pragma unroll
     for (int te = 0; te < 4; ++te) {
         const int e = (te + rho) & 3;
         sel[te] = 0x0c020000u | ((uint32_t)(4 + e) << 8);
+        sgn_sel[te] = half_table_sign_selector(e);
         base[0][te] = (uint32_t)((L + 8 * e) * 4);
         base[1][te] = base[0][te] | 0x10000u;
     }
 
+    // In three phases (addresses, reads, signed additions) so that the reads of all 16 lookups are
+    // in flight together: see gemv8h_body.
     auto lookup16 = [&](const u32x4& k, float& s0, float& s1) {
         const uint32_t w[4] = {k.x, k.y, k.z, k.w};
-        float a0 = 0.0f, a1 = 0.0f, c0 = 0.0f, c1 = 0.0f;
+        uint32_t sg[4], addr[16];
+        float v0[16], v1[16];
 #pragma unroll
         for (int td = 0; td < 4; ++td) {
+            uint32_t idx;
+            half_table_prepare(w[td], idx, sg[td]);   // entry ~key & 127, negated, for keys >= 128
 #pragma unroll
-            for (int te = 0; te < 4; ++te) {
-                const uint32_t t = __builtin_amdgcn_perm(w[td], base[td >> 1][te], sel[te]);
-                // bit 15 = bit 7 of the key: entry ~key & 127, negated
-                const int32_t neg = (int32_t)(t << 16) >> 31;                  // 0 or -1
-                uint32_t addr = t ^ ((uint32_t)neg & 0xff00u);                 // clears bit 15 as well
-                if (td & 1) addr |= 0x8000u;
-                const float v0 = lds_read_abs(addr);
-                const float v1 = lds_read_abs(addr + 128);
-                const float sgn = __uint_as_float(((uint32_t)neg & 0x80000000u) | 0x3f800000u);
-                if (te & 1) { a1 = fmaf(v0, sgn, a1); c1 = fmaf(v1, sgn, c1); }
-                else { a0 = fmaf(v0, sgn, a0); c0 = fmaf(v1, sgn, c0); }
-            }
+            for (int te = 0; te < 4; ++te) addr[4 * td + te] = __builtin_amdgcn_perm(idx, base[td >> 1][te], sel[te]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            v0[j] = lds_read_abs(addr[j] + ((j >> 2) & 1) * 32768);
+            v1[j] = lds_read_abs(addr[j] + ((j >> 2) & 1) * 32768 + 128);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        float a0 = 0.0f, a1 = 0.0f, c0 = 0.0f, c1 = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float sgn = half_table_sign(sg[j >> 2], sgn_sel[j & 3]);
+            if (j & 1) { a1 = fmaf(v0[j], sgn, a1); c1 = fmaf(v1[j], sgn, c1); }
+            else { a0 = fmaf(v0[j], sgn, a0); c0 = fmaf(v1[j], sgn, c0); }
         }
         s0 = a0 + a1;
         s1 = c0 + c1;

@@ -35,6 +35,27 @@ __device__ __forceinline__ float reduce16(float v) {
     return v;
 }
 
+// Half-table lookups, the part done once per key dword (4 keys): a key k >= 128 reads entry
+// ~k & 127 and its value counts negative.  idx = the four keys with every byte that has its top
+// bit set inverted (v_perm_b32's selectors 8..11 replicate the top bit of bytes 1 and 3 of either
+// source over a byte: with the dword and the dword shifted by one byte as sources that is a 0xff
+// mask on exactly the bytes to invert), so that each byte is the entry index and has bit 7 clear;
+// sgn = per byte 0x3f or 0xbf, the top byte of +1.0f / -1.0f.  4 instructions per 4 keys.
+__device__ __forceinline__ void half_table_prepare(uint32_t w, uint32_t& idx, uint32_t& sgn) {
+    const uint32_t inv = __builtin_amdgcn_perm(w, w << 8, 0x0b090a08u);
+    idx = w ^ inv;
+    // (w & 0x80808080) | 0x3f3f3f3f as one v_bfi_b32: both constants in registers (a VOP3
+    // instruction takes no literal here, and the compiler otherwise emits v_and + v_or)
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(sgn) : "v"(0x80808080u), "v"(w), "v"(0x3f3f3f3fu));
+}
+// Selector that moves byte e of sgn to the top of 0x00800000: +-1.0f in one v_perm_b32.
+__device__ __forceinline__ constexpr uint32_t half_table_sign_selector(int e) {
+    return ((uint32_t)(4 + e) << 24) | 0x00020c0cu;
+}
+__device__ __forceinline__ float half_table_sign(uint32_t sgn, uint32_t selector) {
+    return __uint_as_float(__builtin_amdgcn_perm(sgn, 0x00800000u, selector));
+}
+
 // Entries 0..127 of the tables of chunks [c0, c0 + 256), built from X into the layout above.
 // One job = (chunk, 32 keys): 256 x 4 = 1024 jobs; consecutive threads write consecutive banks.
 __device__ __forceinline__ void gemv8h_build_tile(const QueryParams& p, char* lds_bytes, int c0,
@@ -98,31 +119,40 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
 
     // v_perm_b32: S0 = key dword, S1 = base; byte 0 <- base byte 0, byte 1 <- key byte
     // (te + rho) & 3, byte 2 <- base byte 2 (td >> 1), byte 3 <- 0.
-    uint32_t sel[4], base[2][4];
+    uint32_t sel[4], sgn_sel[4], base[2][4];
 #pragma unroll
     for (int te = 0; te < 4; ++te) {
         const int e = (te + rho) & 3;
         sel[te] = 0x0c020000u | ((uint32_t)(4 + e) << 8);
+        sgn_sel[te] = half_table_sign_selector(e);
         base[0][te] = (uint32_t)((e >> 1) * 128 + (e & 1) * 64 + L * 4);
         base[1][te] = base[0][te] | 0x10000u;
     }
 
+    // The 16 lookups of a lane's 16 key bytes, in three phases - all addresses, all reads, all
+    // signed additions - so that the 16 LDS reads are in flight together (written lookup by
+    // lookup, the compiler keeps at most three in flight and the loop runs at LDS latency).
     auto lookup16 = [&](const u32x4& k) -> float {
         const uint32_t w[4] = {k.x, k.y, k.z, k.w};
-        float a0 = 0.0f, a1 = 0.0f;
+        uint32_t sg[4], addr[16];
+        float v[16];
 #pragma unroll
         for (int td = 0; td < 4; ++td) {
+            uint32_t idx;
+            half_table_prepare(w[td], idx, sg[td]);
 #pragma unroll
-            for (int te = 0; te < 4; ++te) {
-                const uint32_t t = __builtin_amdgcn_perm(w[td], base[td >> 1][te], sel[te]);
-                // bit 15 = bit 7 of the key: entry ~key & 127, negated
-                const int32_t neg = (int32_t)(t << 16) >> 31;                  // 0 or -1
-                const uint32_t addr = t ^ ((uint32_t)neg & 0xff00u);           // clears bit 15 as well
-                const float v = lds_read_abs(addr + (td & 1) * 32768);
-                const float sgn = __uint_as_float(((uint32_t)neg & 0x80000000u) | 0x3f800000u);
-                if (te & 1) a1 = fmaf(v, sgn, a1);
-                else a0 = fmaf(v, sgn, a0);
-            }
+            for (int te = 0; te < 4; ++te) addr[4 * td + te] = __builtin_amdgcn_perm(idx, base[td >> 1][te], sel[te]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = lds_read_abs(addr[j] + ((j >> 2) & 1) * 32768);
+        __builtin_amdgcn_sched_barrier(0);
+        float a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float f = half_table_sign(sg[j >> 2], sgn_sel[j & 3]);
+            if (j & 1) a1 = fmaf(v[j], f, a1);
+            else a0 = fmaf(v[j], f, a0);
         }
         return a0 + a1;
     };
@@ -137,11 +167,12 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
         // 16-byte group L1; at static step te it visits byte (te + td1) & 3, which leaves a 2-way
         // bank conflict per half-wave (8 groups x 2 byte parities = 16 banks for 32 lanes).
         const int L1 = lane >> 2, td1 = lane & 3;
-        uint32_t sel1[4], base1[4];
+        uint32_t sel1[4], sgn_sel1[4], base1[4];
 #pragma unroll
         for (int te = 0; te < 4; ++te) {
             const int e = (te + td1) & 3;
             sel1[te] = 0x0c020000u | ((uint32_t)(4 + e) << 8);
+            sgn_sel1[te] = half_table_sign_selector(e);
             base1[te] = (uint32_t)((e >> 1) * 128 + (e & 1) * 64 + L1 * 4) | ((uint32_t)(td1 >> 1) << 16);
         }
         const uint32_t td_bit15 = (uint32_t)(td1 & 1) << 15;
@@ -171,13 +202,13 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
 #pragma unroll
             for (int i = 0; i < Q; ++i) {
                 float acc = 0.0f;
+                uint32_t idx, sgn;
+                half_table_prepare(kw[i], idx, sgn);
 #pragma unroll
                 for (int te = 0; te < 4; ++te) {
-                    const uint32_t t = __builtin_amdgcn_perm(kw[i], base1[te], sel1[te]);
-                    const int32_t neg = (int32_t)(t << 16) >> 31;
-                    const uint32_t addr = (t ^ ((uint32_t)neg & 0xff00u)) | td_bit15;
+                    const uint32_t addr = __builtin_amdgcn_perm(idx, base1[te], sel1[te]) | td_bit15;
                     const float v = lds_read_abs(addr);
-                    acc = fmaf(v, __uint_as_float(((uint32_t)neg & 0x80000000u) | 0x3f800000u), acc);
+                    acc = fmaf(v, half_table_sign(sgn, sgn_sel1[te]), acc);
                 }
                 y = fmaf(a1[i], acc, y);
             }
@@ -197,33 +228,37 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
     const int nunits = LSTM ? min(p.hidden, u0 + (p.rows_per_wg >> 2)) - u0 : 0;
     const int nsteps = LSTM ? nunits : (nrows + 3) >> 2;
     // al[0..Q) = the scales of this lane's row; LSTM: al[Q] = its bias, al[Q + 1] = the previous cell
-    // state of its unit (requested with the keys, so that the cell update waits for no memory access)
-    auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q + 2]) {
+    // state of its unit (requested with the keys, so that the cell update waits for no memory access).
+    // Inside the loop every load is issued by every lane: a load behind a condition makes the
+    // compiler wait for ALL outstanding loads before the first use of any, and the step requested
+    // ahead would no longer be in flight during the lookups.  A step past the end is replaced by
+    // the step `s_else` (the one being worked on: its lines are in the caches, and they differ
+    // from wave to wave - sending every idle request to one address queues them on one memory
+    // channel), a lane without a row or without keys reads the workgroup's first row.  What such a
+    // lane loads is harmless: the tables of chunks past the end of the row are zero, sums of absent
+    // rows are not stored.
+    auto load_step = [&](int s_want, int s_else, u32x4 (&k)[Q], float (&al)[Q + 2]) {
+        const int s = s_want < nsteps ? s_want : s_else;
         // row of the key matrix inside a plane: LSTM: gate rsub of unit u0 + s
-        const int row = LSTM ? rsub * p.hidden + u0 + s : r0 + 4 * s + rsub;
-        const bool ok = have_keys && s < nsteps && (LSTM || row < r1);
+        int row = LSTM ? rsub * p.hidden + u0 + s : r0 + 4 * s + rsub;
+        if (!LSTM && row >= r1) row = r0;
+        const uint32_t seg = have_keys ? (uint32_t)(tile * 256 + 16 * L) : 0u;
 #pragma unroll
         for (int i = 0; i < Q; ++i) {
-            k[i] = (u32x4){0u, 0u, 0u, 0u};
-            al[i] = 0.0f;
-            if (ok) {
-                const size_t kr = (size_t)i * p.m + row;
-                k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(
-                    reinterpret_cast<const char*>(p.K) + kr * stride_bytes + tile * 256 + 16 * L));
-                al[i] = p.alpha[kr];
-            }
+            const size_t kr = (size_t)i * p.m + row;
+            k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(
+                reinterpret_cast<const char*>(p.K) + kr * stride_bytes + seg));
+            al[i] = p.alpha[kr];
         }
-        al[Q] = (LSTM && s < nsteps) ? p.bias[row] : 0.0f;
-        al[Q + 1] = (LSTM && s < nsteps) ? p.c_prev[u0 + s] : 0.0f;
+        if constexpr (LSTM) {
+            al[Q] = p.bias[row];
+            al[Q + 1] = p.c_prev[u0 + s];
+        } else {
+            al[Q] = 0.0f;
+            al[Q + 1] = 0.0f;
+        }
     };
-    u32x4 k[Q], kn[Q];
-    float al[Q + 2], aln[Q + 2];
-    load_step(wave, k, al);
-    if constexpr (FUSED) gemv8h_build_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
-    else gemv8h_copy_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
-    __syncthreads();
-    for (int s = wave; s < nsteps; s += nwaves) {
-        load_step(s + nwaves, kn, aln);
+    auto do_step = [&](int s, const u32x4 (&k)[Q], const float (&al)[Q + 2]) {
         float y = 0.0f;
 #pragma unroll
         for (int i = 0; i < Q; ++i) y = fmaf(al[i], lookup16(k[i]), y);
@@ -243,10 +278,26 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
             const int row = 4 * s + rsub;
             if (L == 0 && row < nrows) p.out[(size_t)sp * p.m + r0 + row] = y;
         }
-#pragma unroll
-        for (int i = 0; i < Q; ++i) k[i] = kn[i];
-#pragma unroll
-        for (int i = 0; i < Q + 2; ++i) al[i] = aln[i];
+    };
+    u32x4 k[Q], kn[Q];
+    float al[Q + 2], aln[Q + 2];
+    int s = wave;
+    const bool busy = s < nsteps;  // wave-uniform: a wave without a step requests nothing
+    if (busy) load_step(s, s, k, al);
+    if constexpr (FUSED) gemv8h_build_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
+    else gemv8h_copy_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
+    __syncthreads();
+    // two steps per trip, so that the step requested ahead lands in registers of its own
+    if (busy) {
+        do {
+            load_step(s + nwaves, s, kn, aln);
+            do_step(s, k, al);
+            s += nwaves;
+            if (s >= nsteps) break;
+            load_step(s + nwaves, s, k, al);
+            do_step(s, kn, aln);
+            s += nwaves;
+        } while (s < nsteps);
     }
 }
 
