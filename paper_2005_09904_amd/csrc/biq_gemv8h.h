@@ -279,10 +279,14 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
             if (L == 0 && row < nrows) p.out[(size_t)sp * p.m + r0 + row] = y;
         }
     };
+    // Two steps per wave in flight: the one being worked on and the next.  (A deeper ring - three or
+    // four steps requested ahead, as in the streaming kernel - was measured 5-10 % SLOWER here at
+    // every size from 16 to 128 MiB of keys: with 4 rows x 256 bytes per request the extra requests
+    // in flight cost more in the memory system than the latency they hide.)
+    int s = __builtin_amdgcn_readfirstlane(wave);
+    const bool busy = s < nsteps;  // wave-uniform: a wave without a step requests nothing
     u32x4 k[Q], kn[Q];
     float al[Q + 2], aln[Q + 2];
-    int s = wave;
-    const bool busy = s < nsteps;  // wave-uniform: a wave without a step requests nothing
     if (busy) load_step(s, s, k, al);
     if constexpr (FUSED) gemv8h_build_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
     else gemv8h_copy_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
