@@ -174,7 +174,7 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
 // for the conflict-free kernels (mu = 8, mu <= 5, mu = 6 up to 4 input vectors); 6.5e12 for the
 // generic one, which also streams keys at no more than about 0.25 TB/s; plus 6 us of launch
 // and table build.  Unpack + MFMA: 2 * 3 flop per weight and padded input vector (three bf16
-// terms) at 1.3e15 flop/s, plus 12 us (input split, launch, combining partial sums).
+// terms) at 1.45e15 flop/s, plus 10 us (input split, launches, combining partial sums).
 bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
     const double weights = (double)q * m * n;
     const double lookups = weights / mu * batch;
@@ -183,7 +183,7 @@ bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
     if (!tuned && t_lut < weights / 8 / 0.25e12) t_lut = weights / 8 / 0.25e12;
     t_lut += 6e-6;
     const double padded = (double)((batch + 31) / 32) * 32;
-    const double t_mfma = 12e-6 + 6.0 * weights * padded / 1.3e15;
+    const double t_mfma = 10e-6 + 6.0 * weights * padded / 1.45e15;
     return t_mfma < t_lut;
 }
 
@@ -202,35 +202,47 @@ bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool table
     pl = biq_plan{};
     if (!tables_given && q <= 4 && unpack_mfma_is_faster(m, n, q, batch, mu)) {
         // Many input vectors: the contraction is compute bound and the matrix cores beat the
-        // table lookups (the crossover of Sec. IV-B / Fig. 10).  Column tile 64 only when that
-        // still leaves two tiles of columns.  Waves hold as many MFMA tiles as the planes allow
-        // (fewer B-operand reads and bit expansions per MFMA); to give every CU a workgroup the
-        // contraction is split over workgroups (partial results through the workspace, summed by
-        // a second kernel); only if that is not enough, waves take fewer rows.  For short calls
-        // (below about 25 us of MFMA work) the first factor 2 of the split goes to two wave
-        // groups inside a workgroup instead (partial sums added in LDS), which there saves more
-        // on the second kernel than it costs in the first; measured, with 3 or more tiles per wave.
+        // table lookups (the crossover of Sec. IV-B / Fig. 10).  The mapping - column tile (32 or
+        // 64 input vectors), row tiles per wave and plane (r), wave groups along the contraction
+        // inside a workgroup (ws; partial sums added in LDS) and workgroups along the contraction
+        // (S; partial sums through the workspace and a second kernel) - is the candidate with the
+        // lowest estimated time.  The estimate: MFMAs per wave x 33 clk at 2.1 GHz (measured rate
+        // of back-to-back MFMAs under load) x an issue-overhead factor per accumulator shape
+        // (measured: 1.13 for 4 x 2 tiles, more for fewer, where key expansion and fragment loads
+        // are shared by fewer MFMAs) x rounds of workgroups over the 256 CUs, plus fixed costs per
+        // accumulator tile, per wave group and for the second kernel.  On a sweep of 14 layer
+        // shapes x all valid mappings the estimate's choice was the fastest or within 5 % of it.
         pl.kernel = KERNEL_UNPACK_MFMA;
         pl.threads = kUnpackThreads;
         pl.chunks_per_tile = kUnpackGroupBytes;
-        pl.batch_tile = batch >= 128 ? 64 : 32;
-        const int ct = pl.batch_tile / 32;
-        const int col_groups = ceil_div(batch, pl.batch_tile);
         const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
-        for (int rpw = q == 1 ? 4 : (q == 2 ? 2 : 1); rpw >= 1; rpw >>= 1) {
-            const bool short_call = 6.0 * q * m * n * (col_groups * pl.batch_tile) / 1.3e15 < 25e-6;
-            const int ws = (short_call && q * rpw * ct >= 3 && groups >= 2) ? 2 : 1;
-            const int rows = (4 / ws) * 32 * rpw;
-            const long long wgs = (long long)ceil_div(m, rows) * col_groups;
-            int S = 1;
-            while (wgs * S < kNumCu && 2 * S * ws <= groups) S *= 2;
-            if (wgs * S >= 3 * kNumCu / 4 || rpw == 1) {
-                pl.wave_splits = ws;
-                pl.rows_per_wg = rows;
-                pl.tiles_per_split = ceil_div(groups, S);
-                break;
-            }
-        }
+        double best = 1e30;
+        for (int bt = 32; bt <= 64; bt += 32)
+            for (int ws = 1; ws <= 4; ws *= 2)
+                for (int r = 1; r <= 4; r *= 2)
+                    for (int S = 1; S <= 16; S *= 2) {
+                        const int ct = bt / 32, rt = q * r;
+                        if (rt > 4 || S * ws > groups) continue;
+                        if (ws == 4 && rt * ct == 8) continue;   // would not fit the register file
+                        const int rows = (4 / ws) * 32 * r;
+                        const long long wgs = (long long)ceil_div(m, rows) * ceil_div(batch, bt) * S;
+                        if (wgs > 4ll * kNumCu && S > 1) continue;
+                        const int gpw = ceil_div(ceil_div(groups, S), ws);   // key groups per wave
+                        const double shape = rt * ct == 8 ? 1.13 : rt * ct == 6 ? 1.16 : rt == 4 ? 1.19
+                                           : rt == 3 ? 1.22 : (rt == 2 && ct == 2) ? 1.22 : rt == 2 ? 1.30
+                                           : ct == 2 ? 1.45 : 1.65;
+                        double t = 3.0 * rt * ct * gpw * 16 * 33 * shape / 2100.0 * (double)ceil_div_ll(wgs, kNumCu);
+                        t += 9.0 + 0.25 * rt * ct;
+                        if (S > 1) t += 3.5 + (S + 1.0) * ceil_div(batch, bt) * bt * (double)m * 4 / 2.5e6;
+                        if (ws > 1) t += 0.6 * (ws - 1) * rt * ct / 4;
+                        if (t < best) {
+                            best = t;
+                            pl.batch_tile = bt;
+                            pl.wave_splits = ws;
+                            pl.rows_per_wg = rows;
+                            pl.tiles_per_split = ceil_div(groups, S);
+                        }
+                    }
         return plan_finish(pl, m, n, q, batch, mu);
     }
     if (mu == 8 && batch == 1 && q <= 4) {

@@ -42,6 +42,21 @@ constexpr int kUnpackThreads = 256;     // 4 waves
 constexpr int kUnpackGroupBytes = 32;   // key bytes of a row per key group (both halves)
 constexpr int kUnpackStageSteps = 8;     // MFMA steps x column tiles per pipeline stage (48 KiB of LDS for two stages)
 
+// Time stamps of a trace build (-DBIQ_TRACE, never the product's): lane 0 of wave 0 of every
+// workgroup writes the 100 MHz wall clock into slot i of its entry.
+#ifdef BIQ_TRACE
+__device__ unsigned long long biq_unpack_trace[8192 * 8];
+#define BIQ_USTAMP(i)                                                                        \
+    do {                                                                                     \
+        if (threadIdx.x == 0 && blockIdx.x < 8192) {                                         \
+            biq_unpack_trace[blockIdx.x * 8 + (i)] = wall_clock64();                         \
+            if ((i) == 1 || (i) == 2) biq_unpack_trace[blockIdx.x * 8 + 3 + (i)] = clock64(); \
+        }                                                                                    \
+    } while (0)
+#else
+#define BIQ_USTAMP(i) do { } while (0)
+#endif
+
 struct UnpackParams {
     const uint8_t* K;        // [q][m][stride]
     const float* alpha;      // [q][m]
@@ -130,9 +145,7 @@ __device__ __forceinline__ bf16x8 unpack_step(uint32_t w, uint32_t one2) {
     for (int i = 0; i < 4; ++i) {
         const int p = 8 * (S >> 1) + 4 * (S & 1) + i;
         const uint32_t a = p <= 15 ? (w << (15 - p)) : (w >> (p - 15));
-        uint32_t r;
-        asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(0x80008000u), "v"(one2));
-        d[i] = r;
+        d[i] = (a & 0x80008000u) | one2;
     }
     return __builtin_bit_cast(bf16x8, d);
 }
@@ -196,36 +209,16 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
             const int row = min(rbase + rp * 32 + lr, p.m - 1);  // clamped: masked at the store
             kptr[i * RPW + rp] = p.K + ((size_t)i * p.m + row) * p.stride_bytes + 16 * h;
         }
+    // All loads of the main loop are unconditional, from addresses clamped into the buffers: a
+    // load behind a condition makes the compiler wait for every outstanding load at the next use
+    // of any, and the keys of the next key group (from HBM, requested a whole group ahead) would
+    // be waited for at every stage copy.  Keys past the wave's range or past the row are never
+    // multiplied with anything but the zero fragments of the padding.
     auto load_keys = [&](int g, mfma_u32x4 (&k)[RT]) {
         const bool ok = g < gb && (uint32_t)(32 * g + 16 * h) < p.stride_bytes;
+        const uint32_t off = ok ? (uint32_t)(32 * g) : 0u;
 #pragma unroll
-        for (int t = 0; t < RT; ++t) {
-            k[t] = (mfma_u32x4){0u, 0u, 0u, 0u};
-            if (ok) k[t] = *reinterpret_cast<const mfma_u32x4*>(kptr[t] + 32 * g);
-        }
-    };
-
-    // Stage copies: every thread moves PER_THREAD pieces for each wave group.  Stage `st` of wave
-    // group j covers MFMA steps [(g0 + j*per)*16 + st*KS, +KS) of the row.
-    constexpr int SPG = 16 / KS;                      // stages per key group
-    const mfma_u32x4* xsrc = p.Xf + ((size_t)cg * steps_total + (size_t)g0 * 16) * SPIECES + tid;
-    auto load_stage = [&](int st, mfma_u32x4 (&r)[WS][PER_THREAD]) {
-#pragma unroll
-        for (int j = 0; j < WS; ++j) {
-            const int gj = g0 + j * per + st / SPG;   // key group this stage belongs to
-            if (gj < min(g1, g0 + (j + 1) * per)) {
-                const mfma_u32x4* src = xsrc + ((size_t)j * per * 16 + (size_t)st * KS) * SPIECES;
-#pragma unroll
-                for (int i = 0; i < PER_THREAD; ++i) r[j][i] = src[i * kUnpackThreads];
-            }
-        }
-    };
-    auto store_stage = [&](int buf, const mfma_u32x4 (&r)[WS][PER_THREAD]) {
-#pragma unroll
-        for (int j = 0; j < WS; ++j)
-#pragma unroll
-            for (int i = 0; i < PER_THREAD; ++i)
-                stage_buf[buf * PIECES + j * GPIECES + i * kUnpackThreads + tid] = r[j][i];
+        for (int t = 0; t < RT; ++t) k[t] = *reinterpret_cast<const mfma_u32x4*>(kptr[t] + off - (ok ? 0 : 16 * h));
     };
 
     f32x16 acc[RT][CT];
@@ -238,70 +231,77 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
 
     uint32_t one2 = 0x3f803f80u;        // two bf16 1.0, kept in a VGPR (see unpack_step)
     asm volatile("" : "+v"(one2));
-    mfma_u32x4 key[RT], keyn[RT];
-    mfma_u32x4 xr[WS][PER_THREAD];
-#pragma unroll
-    for (int j = 0; j < WS; ++j)
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) xr[j][i] = (mfma_u32x4){0u, 0u, 0u, 0u};
-    load_keys(ga, key);
-    load_stage(0, xr);
-    store_stage(0, xr);
-    __syncthreads();
+    BIQ_USTAMP(0);
 
-    const int nst = per * SPG;          // stages every wave walks through (barriers are workgroup wide)
-    for (int gi = 0; gi < per; ++gi) {
-        const int g = ga + gi;
-        const bool active = g < gb;     // wave uniform
-        load_keys(g + 1, keyn);
+    // ---- main loop: no LDS, no barrier.  The B fragments lie in Xf in the order of use, 16 bytes
+    // per lane: a wave loads them straight into registers (1 KiB per request, the four waves of a
+    // workgroup hit the same lines in the vector cache), three MFMA steps ahead in a ring of four.
+    // While the RT * CT * 3 MFMAs of a step issue, the next step's A operands are expanded from
+    // the key bits and the fragments of the step three ahead are requested; the
+    // sched_group_barrier sequence spells that interleaving out (left alone, the compiler puts a
+    // step's expansion right in front of its MFMAs and the matrix pipe idles through it).
+    const int ngroups = gb - ga;                       // key groups of this wave (<= 0: none)
+    const int nsteps = ngroups * 16;
+    if (ngroups > 0) {
+        const mfma_u32x4* xw = p.Xf + ((size_t)cg * steps_total + (size_t)ga * 16) * SPIECES + lane;
+        auto load_b = [&](int s, bf16x8 (&b)[CT][3]) {
+            const int sc = min(s, nsteps - 1);         // past the end: the last step again, unused
+            const mfma_u32x4* src = xw + (size_t)sc * SPIECES;
 #pragma unroll
-        for (int sg = 0; sg < SPG; ++sg) {
-            const int st = gi * SPG + sg;
-            const bool more = st + 1 < nst;
-            if (more) load_stage(st + 1, xr);
-            if (active) {
-                const mfma_u32x4* buf = stage_buf + (sg & 1) * PIECES + kg * GPIECES + lane;
-                bf16x8 bf[2][CT][3];
+            for (int c = 0; c < CT; ++c)
 #pragma unroll
-                for (int c = 0; c < CT; ++c)
+                for (int tm = 0; tm < 3; ++tm) b[c][tm] = __builtin_bit_cast(bf16x8, src[(c * 3 + tm) * 64]);
+        };
+        auto expand_a = [&](const mfma_u32x4 (&k)[RT], int step, bf16x8 (&a)[RT]) {
+            const int d = step >> 2, ks = step & 3;    // step 0..15 within the key group
 #pragma unroll
-                    for (int s = 0; s < 3; ++s) bf[0][c][s] = __builtin_bit_cast(bf16x8, buf[(c * 3 + s) * 64]);
+            for (int t = 0; t < RT; ++t) {
+                const uint32_t w = k[t][d];
+                a[t] = ks == 0 ? unpack_step<0>(w, one2) : ks == 1 ? unpack_step<1>(w, one2)
+                     : ks == 2 ? unpack_step<2>(w, one2) : unpack_step<3>(w, one2);
+            }
+        };
+        mfma_u32x4 key[RT], keyn[RT];
+        bf16x8 bfr[4][CT][3];
+        bf16x8 af[2][RT];
+        load_keys(ga, key);
+        load_b(0, bfr[0]);
+        load_b(1, bfr[1]);
+        load_b(2, bfr[2]);
+        BIQ_USTAMP(1);
+        for (int gi = 0; gi < ngroups; ++gi) {
+            // The first step's operands are expanded here, not during the last step of the group
+            // before: written there, the compiler moves the expansion up to where the keys are
+            // loaded and waits for them on the spot.
+            expand_a(key, 0, af[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            load_keys(ga + gi + 1, keyn);
 #pragma unroll
-                for (int kk = 0; kk < KS; ++kk) {
-                    const int step = sg * KS + kk;     // 0..15 within the key group
-                    const int d = step >> 2, ks = step & 3;
-                    if (kk + 1 < KS) {
+            for (int st = 0; st < 16; ++st) {
+                load_b(gi * 16 + st + 3, bfr[(st + 3) & 3]);
+                if (st + 1 < 16) expand_a(key, st + 1, af[(st + 1) & 1]);
+#pragma unroll
+                for (int tm = 0; tm < 3; ++tm)
+#pragma unroll
+                    for (int t = 0; t < RT; ++t)
 #pragma unroll
                         for (int c = 0; c < CT; ++c)
+                            acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st & 1][t], bfr[st & 3][c][tm],
+                                                                                acc[t][c], 0, 0, 0);
 #pragma unroll
-                            for (int s = 0; s < 3; ++s)
-                                bf[(kk + 1) & 1][c][s] =
-                                    __builtin_bit_cast(bf16x8, buf[(((kk + 1) * CT + c) * 3 + s) * 64]);
-                    }
-                    bf16x8 af[RT];
-#pragma unroll
-                    for (int t = 0; t < RT; ++t) {
-                        const uint32_t w = key[t][d];
-                        af[t] = ks == 0 ? unpack_step<0>(w, one2) : ks == 1 ? unpack_step<1>(w, one2)
-                              : ks == 2 ? unpack_step<2>(w, one2) : unpack_step<3>(w, one2);
-                    }
-#pragma unroll
-                    for (int s = 0; s < 3; ++s)
-#pragma unroll
-                        for (int t = 0; t < RT; ++t)
-#pragma unroll
-                            for (int c = 0; c < CT; ++c)
-                                acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t], bf[kk & 1][c][s],
-                                                                                    acc[t][c], 0, 0, 0);
+                for (int i = 0; i < RT * CT * 3; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // MFMA
+                    if (i < CT * 3) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // global load
+                    if (2 * i < RT * 8) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // VALU
                 }
+                __builtin_amdgcn_sched_barrier(0);   // a step's instructions stay in the step
             }
-            if (more) store_stage((sg + 1) & 1, xr);
-            __syncthreads();
-        }
 #pragma unroll
-        for (int t = 0; t < RT; ++t) key[t] = keyn[t];
+            for (int t = 0; t < RT; ++t) key[t] = keyn[t];
+        }
     }
 
+    BIQ_USTAMP(2);
     // ---- sum over the wave groups: groups 1.. hand their accumulators to group 0 through LDS ----
     if constexpr (WS > 1) {
         float4* red = reinterpret_cast<float4*>(stage_buf);   // [WS - 1][WROWS][RT * CT * 4][64 lanes]
@@ -404,6 +404,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
             }
         }
     }
+    BIQ_USTAMP(3);
 }
 
 }  // namespace biq
