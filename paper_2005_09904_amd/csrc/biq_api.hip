@@ -76,7 +76,7 @@ bool plan_finish_unpack(biq_plan& pl, int m, int n, int q, int batch) {
     pl.chunk_splits = (groups + pl.tiles_per_split - 1) / pl.tiles_per_split;
     pl.row_blocks = (m + pl.rows_per_wg - 1) / pl.rows_per_wg;
     pl.batch_tiles = (batch + pl.batch_tile - 1) / pl.batch_tile;
-    pl.lds_bytes = ws == 1 ? 48 * 1024 : 96 * 1024;   // two pipeline stages (UnpackGeom::LDS_BYTES)
+    pl.lds_bytes = ws == 1 ? 24 * 1024 : 96 * 1024;   // partial sums of the wave groups, transpose patches (UnpackGeom::LDS_BYTES)
     const long long tasks = (long long)pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
     if (tasks > (1ll << 30)) return false;
     // prepared input: 6 bytes per (padded column, padded element)

@@ -24,9 +24,8 @@
 //
 // B operands are prepared by xsplit_kernel in exactly the order the main kernel consumes them:
 //   Xf[col_group][step][col_tile][term 0..2][lane] : 16 bytes (8 bf16)
-// (step = MFMA step along the row, 16 per key group), so a workgroup stages one contiguous
-// block per pipeline stage into LDS (double buffered) and its four waves read their fragments
-// from there with conflict-free 128-bit reads.
+// (step = MFMA step along the row, 16 per key group), so a wave's load of a fragment is one
+// contiguous KiB; the waves load their fragments straight into registers, a few steps ahead.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -40,7 +39,6 @@ typedef uint32_t mfma_u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kUnpackThreads = 256;     // 4 waves
 constexpr int kUnpackGroupBytes = 32;   // key bytes of a row per key group (both halves)
-constexpr int kUnpackStageSteps = 8;     // MFMA steps x column tiles per pipeline stage (48 KiB of LDS for two stages)
 
 // Time stamps of a trace build (-DBIQ_TRACE, never the product's): lane 0 of wave 0 of every
 // workgroup writes the 100 MHz wall clock into slot i of its entry.
@@ -150,33 +148,24 @@ __device__ __forceinline__ bf16x8 unpack_step(uint32_t w, uint32_t one2) {
     return __builtin_bit_cast(bf16x8, d);
 }
 
-// Pipeline-stage geometry.  A workgroup's four waves form WS groups along the contraction
-// ("wave splits"): group kg works on its own contiguous part of the workgroup's key groups with
-// 4 / WS waves side by side along the rows, and the WS partial accumulators are added through
-// LDS in a fixed order at the end.  A stage holds KS MFMA steps of B operands for every wave
-// group; two stages are resident (48 KiB for WS = 1, 96 KiB otherwise).
+// A workgroup's four waves form WS groups along the contraction ("wave splits"): group kg works
+// on its own contiguous part of the workgroup's key groups, with 4 / WS waves side by side along
+// the rows, and the WS partial accumulators are added through LDS in a fixed order at the end.
+// LDS holds only those partial sums and the epilogue's transpose patches.
 template <int CT, int WS>
 struct UnpackGeom {
-    static constexpr int KS = kUnpackStageSteps / CT / (WS == 4 ? 2 : 1);  // MFMA steps per stage
-    static constexpr int SPIECES = CT * 3 * 64;                           // 16-byte pieces per step
-    static constexpr int GPIECES = KS * SPIECES;                          // ... per stage and wave group
-    static constexpr int PIECES = WS * GPIECES;                           // ... per stage
-    static constexpr int LDS_BYTES = 2 * PIECES * 16;
+    static constexpr int SPIECES = CT * 3 * 64;                  // 16-byte pieces of B per MFMA step
+    static constexpr int LDS_BYTES = (WS == 1 ? 24 : 96) * 1024;
 };
 
 template <int Q, int RPW, int CT, int WS>
 __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const UnpackParams p) {
     using G = UnpackGeom<CT, WS>;
-    constexpr int KS = G::KS;
     constexpr int RT = Q * RPW;                       // row tiles (32 key rows each) per wave
     constexpr int WROWS = 4 / WS;                     // waves side by side along the rows
     constexpr int SPIECES = G::SPIECES;
-    constexpr int GPIECES = G::GPIECES;
-    constexpr int PIECES = G::PIECES;
-    constexpr int PER_THREAD = GPIECES / kUnpackThreads;  // per wave group
-    static_assert(GPIECES % kUnpackThreads == 0, "stage copy must divide evenly over the threads");
-    static_assert((WS - 1) * WROWS * RT * CT * 4096 <= G::LDS_BYTES, "partial sums must fit the stage buffers");
-    extern __shared__ __align__(16) mfma_u32x4 stage_buf[];  // [2][WS][GPIECES]
+    static_assert((WS - 1) * WROWS * RT * CT * 4096 <= G::LDS_BYTES, "partial sums must fit");
+    extern __shared__ __align__(16) mfma_u32x4 stage_buf[];  // partial sums, transpose patches
 
     const int wg = blockIdx.x;
     const int task = (wg & 7) * p.tasks_per_xcd + (wg >> 3);
