@@ -291,8 +291,10 @@ __device__ __forceinline__ void gemv8_body(const QueryParams& p, const int wg) {
     // fetched a tile ahead.
     const int nblk = (nrows + 63) >> 6;
     const int iters = (nblk + nwaves - 1) / nwaves;  // block iterations per wave and tile, >= 1
-    // PD * Q KiB in flight per wave; fewer for many planes to stay inside 128 VGPRs
-    constexpr int PD = (Q <= 3 || MAXT <= 512) ? 4 : 2;
+    // PD * Q KiB in flight per wave.  About 4 KiB per wave (64 KiB per CU) is the optimum: measured
+    // with two planes, a ring of 4 steps is 3-6 % slower than one of 2 from 64 to 512 MiB of keys and
+    // one of 8 is 15-30 % slower (requests queue in the memory system); with one plane 4 beats 2.
+    constexpr int PD = Q == 1 ? 4 : 2;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const char* kbase[Q];
     const char* abase[Q];
