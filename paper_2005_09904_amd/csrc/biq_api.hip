@@ -90,7 +90,8 @@ inline int plan_lds_bytes(const biq_plan& pl, int mu) {
     if (pl.kernel == KERNEL_GEMV8)
         return kGemvTileBytes +
                (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + pl.xcd_skew + 63) / 64) * 64 * 4 : 0);
-    if (pl.kernel == KERNEL_GEMV8H) return kGemvHalfTileBytes;
+    if (pl.kernel == KERNEL_GEMV8H)
+        return kGemvHalfTileBytes + (pl.tiles_per_split > 1 ? ((pl.rows_per_wg + 3) / 4) * 16 : 0);
     if (pl.kernel == KERNEL_GEMM8X2H) return kGemmHalfTileBytes;
     if (pl.kernel == KERNEL_WIDE) return 128 * 1024;
     if (pl.kernel == KERNEL_GEMM8X2)
@@ -117,11 +118,12 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
         if ((long long)pl.rows_per_wg * (long long)biq_key_row_stride(n) >= (1ll << 31)) return false;
     }
     if (pl.kernel == KERNEL_GEMV8H) {
-        // mu = 8, one input vector, at most 4 planes; one 256-chunk tile of half tables per
-        // workgroup, latency mode only
+        // mu = 8, one input vector, at most 4 planes; 256-chunk tiles of half tables, latency mode
+        // only; row_mode 1 can walk several tiles (row sums carried in LDS beside the tables)
         if (mu != 8 || batch != 1 || q > 4) return false;
         if (pl.chunks_per_tile != kGemvHalfTileChunks || pl.batch_tile != 1) return false;
-        if ((pl.row_mode != 1 && pl.row_mode != 2) || pl.tiles_per_split != 1) return false;
+        if (pl.row_mode != 1 && pl.row_mode != 2) return false;
+        if (pl.tiles_per_split != 1 && (pl.row_mode != 1 || pl.rows_per_wg > 4096)) return false;
     }
     if (pl.kernel == KERNEL_WIDE) {
         // mu <= 6; one tile of 32 key units per workgroup, batch tile fixed by mu (tables fill 128 KiB)
@@ -149,7 +151,8 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     if (pl.rows_per_wg < 1 || pl.tiles_per_split < 1) return false;
     const int tiles = ceil_div(C, pl.chunks_per_tile);
     if (pl.tiles_per_split > tiles) pl.tiles_per_split = tiles;
-    if (pl.row_mode != 0 && !(pl.row_mode == 1 && pl.kernel != KERNEL_GENERIC && pl.tiles_per_split == 1) &&
+    if (pl.row_mode != 0 &&
+        !(pl.row_mode == 1 && pl.kernel != KERNEL_GENERIC && (pl.tiles_per_split == 1 || pl.kernel == KERNEL_GEMV8H)) &&
         !(pl.row_mode == 2 && pl.kernel == KERNEL_GEMV8H))
         return false;
     if (pl.xcd_skew != 0) {
@@ -280,9 +283,17 @@ bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool table
             pl.tiles_per_split = 1;
             pl.row_mode = 1;
             const int tiles_h = ceil_div(C, kGemvHalfTileChunks);
-            pl.rows_per_wg = rows_from(ceil_div_ll((long long)m * tiles_h, kNumCu), 4, 8, m);
-            // up to one row per wave: 64 lanes per row instead of 16 (4 lookups per lane and plane)
-            if (pl.rows_per_wg <= 16) pl.row_mode = 2;
+            if (tiles_h == 2 || tiles_h == 3) {
+                // two or three tiles: a workgroup walks them (a table build of 1.3 us each) rather
+                // than sharing the row with other workgroups, which costs a second dispatch (2.5 us
+                // and more) for the sum of the partial results
+                pl.tiles_per_split = tiles_h;
+                pl.rows_per_wg = rows_from(ceil_div(m, kNumCu), 4, 8, m);
+            } else {
+                pl.rows_per_wg = rows_from(ceil_div_ll((long long)m * tiles_h, kNumCu), 4, 8, m);
+                // up to one row per wave: 64 lanes per row instead of 16 (4 lookups per lane and plane)
+                if (pl.rows_per_wg <= 16) pl.row_mode = 2;
+            }
         } else if ((long long)m * tiles <= 4ll * 128 * kNumCu) {
             // small: latency mode, 8 rows per wave step, at most 4 steps per wave
             pl.tiles_per_split = 1;

@@ -84,9 +84,10 @@ __device__ __forceinline__ void gemv8h_copy_tile(const QueryParams& p, char* lds
     }
 }
 
-// One 256-chunk tile per workgroup; one step of 4 rows per wave at a time (row_mode 1) or one
-// row per wave at a time (row_mode 2); the first step's keys and scales are requested before the
-// tables are built.
+// One step of 4 rows per wave at a time (row_mode 1) or one row per wave at a time (row_mode 2);
+// a tile's first step of keys and scales is requested before its tables are built.  row_mode 1
+// can walk several 256-chunk tiles per workgroup (rows up to three tiles wide then need no second
+// dispatch for partial sums): the row sums are carried in LDS behind the tables.
 //
 // LSTM = true (row_mode 1 only): the rows are the four gates i, f, g, o of an LSTM cell stacked
 // (m = 4 * hidden); the 4 rows of a wave step are the 4 gates of ONE hidden unit, so that the
@@ -103,7 +104,9 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
     const int rb = task / p.splits;
     const int r0 = rb * p.rows_per_wg;
     const int r1 = min(p.m, r0 + p.rows_per_wg);
-    const int tile = sp;  // one tile per split
+    const int tile0 = sp * p.tps;  // tiles [tile0, tile1) of this split: one, or (row_mode 1) a few
+    const int tile1 = min(p.tiles, tile0 + p.tps);
+    const int tile = tile0;
 
     const int tid = threadIdx.x;
     const int nthreads = blockDim.x;
@@ -222,7 +225,9 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
         return;
     }
 
-    const bool have_keys = (uint32_t)(tile * 256 + L * 16) < stride_bytes;
+    int tl = tile0;  // the tile being worked on
+    // row sums carried from tile to tile (only with several tiles per workgroup): behind the tables
+    float* const yacc = reinterpret_cast<float*>(lds_bytes + kGemvHalfTileBytes);
     // LSTM: the workgroup's hidden units [u0, u0 + nunits), one unit (4 gate rows) per step
     const int u0 = LSTM ? rb * (p.rows_per_wg >> 2) : 0;
     const int nunits = LSTM ? min(p.hidden, u0 + (p.rows_per_wg >> 2)) - u0 : 0;
@@ -242,7 +247,8 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
         // row of the key matrix inside a plane: LSTM: gate rsub of unit u0 + s
         int row = LSTM ? rsub * p.hidden + u0 + s : r0 + 4 * s + rsub;
         if (!LSTM && row >= r1) row = r0;
-        const uint32_t seg = have_keys ? (uint32_t)(tile * 256 + 16 * L) : 0u;
+        const bool have_keys = (uint32_t)(tl * 256 + L * 16) < stride_bytes;
+        const uint32_t seg = have_keys ? (uint32_t)(tl * 256 + 16 * L) : 0u;
 #pragma unroll
         for (int i = 0; i < Q; ++i) {
             const size_t kr = (size_t)i * p.m + row;
@@ -276,32 +282,42 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
             }
         } else {
             const int row = 4 * s + rsub;
-            if (L == 0 && row < nrows) p.out[(size_t)sp * p.m + r0 + row] = y;
+            if (L == 0 && row < nrows) {
+                // the same lane handles this row in every tile: no synchronisation needed
+                if (tl != tile0) y += yacc[row];
+                if (tl + 1 < tile1) yacc[row] = y;
+                else p.out[(size_t)sp * p.m + r0 + row] = y;
+            }
         }
     };
     // Two steps per wave in flight: the one being worked on and the next.  (A deeper ring - three or
     // four steps requested ahead, as in the streaming kernel - was measured 5-10 % SLOWER here at
     // every size from 16 to 128 MiB of keys: with 4 rows x 256 bytes per request the extra requests
     // in flight cost more in the memory system than the latency they hide.)
-    int s = __builtin_amdgcn_readfirstlane(wave);
-    const bool busy = s < nsteps;  // wave-uniform: a wave without a step requests nothing
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const bool busy = wave_u < nsteps;  // wave-uniform: a wave without a step requests nothing
     u32x4 k[Q], kn[Q];
     float al[Q + 2], aln[Q + 2];
-    if (busy) load_step(s, s, k, al);
-    if constexpr (FUSED) gemv8h_build_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
-    else gemv8h_copy_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
-    __syncthreads();
-    // two steps per trip, so that the step requested ahead lands in registers of its own
-    if (busy) {
-        do {
-            load_step(s + nwaves, s, kn, aln);
-            do_step(s, k, al);
-            s += nwaves;
-            if (s >= nsteps) break;
-            load_step(s + nwaves, s, k, al);
-            do_step(s, kn, aln);
-            s += nwaves;
-        } while (s < nsteps);
+    for (; tl < tile1; ++tl) {
+        int s = wave_u;
+        // the tile's first step is requested before its tables are built
+        if (busy) load_step(s, s, k, al);
+        if (tl != tile0) __syncthreads();  // every wave is done with the previous tables
+        if constexpr (FUSED) gemv8h_build_tile(p, lds_bytes, tl * kGemvHalfTileChunks, tid, nthreads);
+        else gemv8h_copy_tile(p, lds_bytes, tl * kGemvHalfTileChunks, tid, nthreads);
+        __syncthreads();
+        // two steps per trip, so that the step requested ahead lands in registers of its own
+        if (busy) {
+            do {
+                load_step(s + nwaves, s, kn, aln);
+                do_step(s, k, al);
+                s += nwaves;
+                if (s >= nsteps) break;
+                load_step(s + nwaves, s, k, al);
+                do_step(s, kn, aln);
+                s += nwaves;
+            } while (s < nsteps);
+        }
     }
 }
 

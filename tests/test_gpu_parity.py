@@ -253,6 +253,9 @@ def test_explicit_plans_give_the_same_result(biq, oracle):
                  # ... one row per wave at a time
                  (4, 1024, 256, 1, 1, 8, 2), (4, 256, 256, 1, 1, 700, 2), (4, 64, 256, 1, 1, 5, 2),
                  (4, 1024, 256, 1, 1, 16, 2),
+                 # ... walking both tiles of the row (row sums carried in LDS)
+                 (4, 1024, 256, 1, 2, 64, 1), (4, 256, 256, 1, 2, 700, 1), (4, 64, 256, 1, 2, 5, 1),
+                 (4, 1024, 256, 1, 2, 130, 1),
                  # throughput mode, several tiles per workgroup, ragged block counts per wave
                  (1, 1024, 128, 1, 3, 700, 0), (1, 1024, 128, 1, 3, 64, 0), (1, 1024, 128, 1, 2, 1000, 0),
                  (1, 256, 128, 1, 3, 333, 0), (1, 64, 128, 1, 3, 9, 0)]:
@@ -267,8 +270,10 @@ def test_explicit_plans_give_the_same_result(biq, oracle):
         K = gpu_pack(biq, Bd, mu)
         ref = oracle.gemm_dense(B, alpha, X)
         for spec in [(1, 1024, 128, 1, 5, 8, 0), (1, 512, 128, 1, 5, 72, 0), (1, 1024, 128, 1, 2, 520, 0),
-                     (1, 1024, 128, 1, 5, 2000, 0)]:
-            for fill in (0, 1):   # tables from pair sums / in the order of Algorithm 1
+                     (1, 1024, 128, 1, 5, 2000, 0),
+                     # half tables: all three tiles in one workgroup; two of three, then one (partial sums)
+                     (4, 1024, 256, 1, 3, 72, 1), (4, 1024, 256, 1, 2, 520, 1), (4, 512, 256, 1, 3, 2000, 1)]:
+            for fill in ((0, 1) if spec[0] == 1 else (0,)):   # tables from pair sums / in the order of Algorithm 1
                 _say("plan q=%d n=%d fill=%d " % (q, n2, fill) + str(spec))
                 plan = _plan(biq, *spec)
                 plan.table_fill = fill

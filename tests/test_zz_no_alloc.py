@@ -44,7 +44,7 @@ def test_noalloc_matches_gemm_on_consecutive_calls(biq, oracle):
     # shapes whose default plans use the workspace: matrix cores with split input and partial sums
     # (7 MiB), then smaller ones: the same path with less of it (4 MiB), batched table kernels with a
     # chunk split, a GEMV whose chunks are split over workgroups, and one that needs no workspace
-    shapes = [(4096, 2048, 2, 96), (4096, 4096, 3, 32), (1024, 2048, 2, 128), (2048, 4096, 2, 1),
+    shapes = [(4096, 2048, 2, 96), (4096, 4096, 3, 32), (1024, 2048, 2, 128), (1024, 16384, 2, 1),
               (600, 3000, 3, 6), (512, 512, 1, 1)]
     used = []
     for i, (m, n, q, b) in enumerate(shapes):
