@@ -72,6 +72,26 @@ __device__ __forceinline__ void gemv8h_build_tile(const QueryParams& p, char* ld
     }
 }
 
+// The same job by job for workgroups of 1024 threads (thread = job): the inputs are requested
+// first (raw, from clamped addresses), ahead of the first step's keys, and the build then waits
+// for them alone - requested after the keys, they would arrive behind a round trip to HBM.
+__device__ __forceinline__ int gemv8h_job_chunk(int job) {
+    return 16 * (job & 15) + 4 * ((job >> 6) & 3) + ((job >> 4) & 3);
+}
+__device__ __forceinline__ void gemv8h_job_x_ahead(const QueryParams& p, int c0, int job, float (&x)[8]) {
+    load_chunk8_raw(p.X, p.n, c0 + gemv8h_job_chunk(job), x);
+}
+__device__ __forceinline__ void gemv8h_job_build(const QueryParams& p, char* lds_bytes, int c0, int job,
+                                                 float (&x)[8]) {
+    const int L = job & 15, e = (job >> 4) & 3, td = (job >> 6) & 3, hq = job >> 8;
+    chunk8_zero_tail(p.n, c0 + gemv8h_job_chunk(job), x);
+    float ent[32];
+    table32(x, (uint32_t)hq, ent);
+    char* dst = lds_bytes + gemv8h_slot_offset(L, td, e) + (hq * 32) * 256;
+#pragma unroll
+    for (int l = 0; l < 32; ++l) *reinterpret_cast<float*>(dst + l * 256) = ent[l];
+}
+
 // The same half tables copied from tables in device memory (LUT [C][256][1]).
 __device__ __forceinline__ void gemv8h_copy_tile(const QueryParams& p, char* lds_bytes, int c0,
                                                  int tid, int nthreads) {
@@ -180,24 +200,31 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
         }
         const uint32_t td_bit15 = (uint32_t)(td1 & 1) << 15;
         const bool have = (uint32_t)(tile * 256 + lane * 4) < stride_bytes;
+        // unconditional, from clamped addresses (a row past the end: the workgroup's first; a lane
+        // past the end of the row: its start), so that the compiler can count the requests in
+        // flight; such lanes meet zero tables, such rows are not stored
         auto load_row = [&](int row, uint32_t (&kw)[Q], float (&a)[Q]) {
+            const int row_c = row < nrows ? row : 0;
+            const uint32_t seg = have ? (uint32_t)(tile * 256 + lane * 4) : 0u;
 #pragma unroll
             for (int i = 0; i < Q; ++i) {
-                kw[i] = 0u;
-                a[i] = 0.0f;
-                if (have && row < nrows) {
-                    const size_t kr = (size_t)i * p.m + r0 + row;
-                    kw[i] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(p.K) +
-                                                               kr * stride_bytes + tile * 256 + lane * 4);
-                    a[i] = p.alpha[kr];
-                }
+                const size_t kr = (size_t)i * p.m + r0 + row_c;
+                kw[i] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(p.K) + kr * stride_bytes + seg);
+                a[i] = p.alpha[kr];
             }
         };
         uint32_t kw[Q], kwn[Q];
         float a1[Q], a1n[Q];
+        const bool x_ahead = FUSED && nthreads == 1024 && x_rows_vectorizable(p);
+        float xa[8];
+        if (x_ahead) gemv8h_job_x_ahead(p, tile * kGemvHalfTileChunks, tid, xa);
         load_row(wave, kw, a1);
-        if constexpr (FUSED) gemv8h_build_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
-        else gemv8h_copy_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
+        if constexpr (FUSED) {
+            if (x_ahead) gemv8h_job_build(p, lds_bytes, tile * kGemvHalfTileChunks, tid, xa);
+            else gemv8h_build_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
+        } else {
+            gemv8h_copy_tile(p, lds_bytes, tile * kGemvHalfTileChunks, tid, nthreads);
+        }
         __syncthreads();
         for (int row = wave; row < nrows; row += nwaves) {
             load_row(row + nwaves, kwn, a1n);
@@ -298,19 +325,32 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
     const bool busy = wave_u < nsteps;  // wave-uniform: a wave without a step requests nothing
     u32x4 k[Q], kn[Q];
     float al[Q + 2], aln[Q + 2];
+    const bool x_ahead = FUSED && nthreads == 1024 && x_rows_vectorizable(p);
+    float xa[8];
+    BIQ_STAMP(p, 0);
     for (; tl < tile1; ++tl) {
         int s = wave_u;
-        // the tile's first step is requested before its tables are built
-        if (busy) load_step(s, s, k, al);
+        // the tile's inputs, then its first step of keys (a wave without a step: step 0 again),
+        // are requested before its tables are built; the build waits for the inputs alone
+        if (x_ahead) gemv8h_job_x_ahead(p, tl * kGemvHalfTileChunks, tid, xa);
+        load_step(s, 0, k, al);
+        BIQ_STAMP(p, 1);
         if (tl != tile0) __syncthreads();  // every wave is done with the previous tables
-        if constexpr (FUSED) gemv8h_build_tile(p, lds_bytes, tl * kGemvHalfTileChunks, tid, nthreads);
-        else gemv8h_copy_tile(p, lds_bytes, tl * kGemvHalfTileChunks, tid, nthreads);
+        if constexpr (FUSED) {
+            if (x_ahead) gemv8h_job_build(p, lds_bytes, tl * kGemvHalfTileChunks, tid, xa);
+            else gemv8h_build_tile(p, lds_bytes, tl * kGemvHalfTileChunks, tid, nthreads);
+        } else {
+            gemv8h_copy_tile(p, lds_bytes, tl * kGemvHalfTileChunks, tid, nthreads);
+        }
+        BIQ_STAMP(p, 4);
         __syncthreads();
+        BIQ_STAMP(p, 2);
         // two steps per trip, so that the step requested ahead lands in registers of its own
         if (busy) {
             do {
                 load_step(s + nwaves, s, kn, aln);
                 do_step(s, k, al);
+                BIQ_STAMP(p, 3);
                 s += nwaves;
                 if (s >= nsteps) break;
                 load_step(s + nwaves, s, k, al);
@@ -319,6 +359,7 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
             } while (s < nsteps);
         }
     }
+    BIQ_STAMP(p, 6);
 }
 
 template <int Q, bool FUSED>
