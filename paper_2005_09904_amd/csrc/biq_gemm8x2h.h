@@ -42,6 +42,27 @@ __device__ __forceinline__ void gemm8x2h_build_tile(const QueryParams& p, char* 
     }
 }
 
+// The same job by job for workgroups of 1024 threads (thread = job), with the inputs requested
+// ahead of the first step's keys (see gemv8h_job_x_ahead).  An absent second input vector reads
+// the last one again; its results are never stored.
+__device__ __forceinline__ int gemm8x2h_job_chunk(int job) {
+    return 16 * (job & 7) + 4 * ((job >> 5) & 3) + ((job >> 3) & 3);
+}
+__device__ __forceinline__ void gemm8x2h_job_x_ahead(const QueryParams& p, int c0, int b0, int job, float (&x)[8]) {
+    const int col = min(b0 + ((job >> 7) & 1), p.batch - 1);
+    load_chunk8_raw(p.X + (size_t)col * p.n, p.n, c0 + gemm8x2h_job_chunk(job), x);
+}
+__device__ __forceinline__ void gemm8x2h_job_build(const QueryParams& p, char* lds_bytes, int c0, int job,
+                                                   float (&x)[8]) {
+    const int L = job & 7, e = (job >> 3) & 3, td = (job >> 5) & 3, v = (job >> 7) & 1, hq = job >> 8;
+    chunk8_zero_tail(p.n, c0 + gemm8x2h_job_chunk(job), x);
+    float ent[32];
+    table32(x, (uint32_t)hq, ent);
+    char* dst = lds_bytes + gemm8x2h_slot_offset(L, td, e, v) + (hq * 32) * 256;
+#pragma unroll
+    for (int l = 0; l < 32; ++l) *reinterpret_cast<float*>(dst + l * 256) = ent[l];
+}
+
 // The same half tables copied from tables in device memory (LUT [C][256][batch]).
 __device__ __forceinline__ void gemm8x2h_copy_tile(const QueryParams& p, char* lds_bytes, int c0,
                                                    int b0, int tid, int nthreads) {
@@ -144,32 +165,47 @@ __device__ __forceinline__ void gemm8x2h_body(const QueryParams& p, const int wg
     // al[0..Q) = the scales of this lane's row; LSTM: al[Q] = its bias, al[Q + 1], al[Q + 2] = the
     // previous cell state of its unit for the two input vectors (requested with the keys, so that
     // the cell update waits for no memory access)
-    auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q + 3]) {
+    // Unconditional, from clamped addresses (a step past the end: step 0; a row past the end: the
+    // workgroup's first; a lane past the end of the row: its start), so that the compiler can
+    // count the requests in flight; such lanes meet zero tables, such rows are not stored.
+    auto load_step = [&](int s_want, u32x4 (&k)[Q], float (&al)[Q + 3]) {
+        const int s = s_want < nsteps ? s_want : 0;
         // row of the key matrix inside a plane: LSTM: gate (rsub & 3) of unit u0 + 2s + (rsub >> 2)
-        const int unit = 2 * s + (rsub >> 2);
-        const int row = LSTM ? (rsub & 3) * p.hidden + u0 + unit : r0 + 8 * s + rsub;
-        const bool row_ok = s < nsteps && (LSTM ? unit < nunits : row < r1);
-        const bool ok = have_keys && row_ok;
+        int unit = 2 * s + (rsub >> 2);
+        if (LSTM && unit >= nunits) unit = 0;
+        int row = LSTM ? (rsub & 3) * p.hidden + u0 + unit : r0 + 8 * s + rsub;
+        if (!LSTM && row >= r1) row = r0;
+        const uint32_t seg = have_keys ? (uint32_t)(tile * 128 + 16 * L) : 0u;
 #pragma unroll
         for (int i = 0; i < Q; ++i) {
-            k[i] = (u32x4){0u, 0u, 0u, 0u};
-            al[i] = 0.0f;
-            if (ok) {
-                const size_t kr = (size_t)i * p.m + row;
-                k[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.K) +
-                                                       kr * stride_bytes + tile * 128 + 16 * L);
-                al[i] = p.alpha[kr];
-            }
+            const size_t kr = (size_t)i * p.m + row;
+            k[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.K) + kr * stride_bytes + seg);
+            al[i] = p.alpha[kr];
         }
-        al[Q] = (LSTM && row_ok) ? p.bias[row] : 0.0f;
-        al[Q + 1] = (LSTM && row_ok) ? p.c_prev[(size_t)b0 * p.hidden + u0 + unit] : 0.0f;
-        al[Q + 2] = (LSTM && row_ok && b0 + 1 < p.batch) ? p.c_prev[(size_t)(b0 + 1) * p.hidden + u0 + unit] : 0.0f;
+        if constexpr (LSTM) {
+            al[Q] = p.bias[row];
+            al[Q + 1] = p.c_prev[(size_t)b0 * p.hidden + u0 + unit];
+            al[Q + 2] = p.c_prev[(size_t)min(b0 + 1, p.batch - 1) * p.hidden + u0 + unit];
+        } else {
+            al[Q] = 0.0f;
+            al[Q + 1] = 0.0f;
+            al[Q + 2] = 0.0f;
+        }
     };
     u32x4 k[Q], kn[Q];
     float al[Q + 3], aln[Q + 3];
+    // the tile's inputs, then the first step of keys, are requested before the tables are built;
+    // the build waits for the inputs alone
+    const bool x_ahead = FUSED && nthreads == 1024 && x_rows_vectorizable(p);
+    float xa[8];
+    if (x_ahead) gemm8x2h_job_x_ahead(p, tile * kGemmHalfTileChunks, b0, tid, xa);
     load_step(wave, k, al);
-    if constexpr (FUSED) gemm8x2h_build_tile(p, lds_bytes, tile * kGemmHalfTileChunks, b0, tid, nthreads);
-    else gemm8x2h_copy_tile(p, lds_bytes, tile * kGemmHalfTileChunks, b0, tid, nthreads);
+    if constexpr (FUSED) {
+        if (x_ahead) gemm8x2h_job_build(p, lds_bytes, tile * kGemmHalfTileChunks, tid, xa);
+        else gemm8x2h_build_tile(p, lds_bytes, tile * kGemmHalfTileChunks, b0, tid, nthreads);
+    } else {
+        gemm8x2h_copy_tile(p, lds_bytes, tile * kGemmHalfTileChunks, b0, tid, nthreads);
+    }
     __syncthreads();
     for (int s = wave; s < nsteps; s += nwaves) {
         load_step(s + nwaves, kn, aln);

@@ -244,26 +244,35 @@ __device__ __forceinline__ void gemv8_body(const QueryParams& p, const int wg) {
         const int tile = tile0;
         const bool have_keys = (uint32_t)(tile * 128 + L * 16) < stride_bytes;
         const int nsteps = (nrows + 7) >> 3;
+        // unconditional, from clamped addresses (a step or row past the end: the workgroup's first
+        // row; a lane past the end of the row: its start), so that the compiler can count the
+        // requests in flight; such lanes meet zero tables, such rows are not stored
         auto load_step = [&](int s, u32x4 (&k)[Q], float (&al)[Q]) {
-            const int row = 8 * s + rsub;
-            const bool ok = have_keys && s < nsteps && row < nrows;
+            int row = 8 * s + rsub;
+            if (s >= nsteps || row >= nrows) row = 0;
+            const uint32_t seg = have_keys ? (uint32_t)(tile * 128 + 16 * L) : 0u;
 #pragma unroll
             for (int i = 0; i < Q; ++i) {
-                k[i] = (u32x4){0u, 0u, 0u, 0u};
-                al[i] = 0.0f;
-                if (ok) {
-                    const size_t kr = (size_t)i * p.m + r0 + row;
-                    k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(
-                        reinterpret_cast<const char*>(p.K) + kr * stride_bytes + tile * 128 + 16 * L));
-                    al[i] = p.alpha[kr];
-                }
+                const size_t kr = (size_t)i * p.m + r0 + row;
+                k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(
+                    reinterpret_cast<const char*>(p.K) + kr * stride_bytes + seg));
+                al[i] = p.alpha[kr];
             }
         };
         u32x4 k[Q], kn[Q];
         float al[Q], aln[Q];
+        // the tile's inputs, then the first step of keys, are requested before the tables are
+        // built; the build waits for the inputs alone
+        const bool x_first = FUSED && nthreads == 1024 && x_rows_vectorizable(p) && p.table_fill == 0;
+        float xf[8];
+        if (x_first) gemv8_job_x_ahead(p, tile * kGemvTileChunks, tid, xf);
         load_step(wave, k, al);
-        if constexpr (FUSED) gemv8_build_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
-        else gemv8_copy_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
+        if constexpr (FUSED) {
+            if (x_first) gemv8_job_build(p, lds_bytes, tile * kGemvTileChunks, tid, xf);
+            else gemv8_build_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
+        } else {
+            gemv8_copy_tile(p, lds_bytes, tile * kGemvTileChunks, tid, nthreads);
+        }
         __syncthreads();
         for (int s = wave; s < nsteps; s += nwaves) {
             load_step(s + nwaves, kn, aln);
