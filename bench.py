@@ -553,6 +553,29 @@ def main() -> int:
             (hid, w.n, w.q, w.batch, tl.median * 1e6, tgm.median * 1e6))
         del pl
         torch.cuda.empty_cache()
+        # the same small calls as nodes of a HIP graph: 16 consecutive calls (16 key matrices) captured
+        # once and replayed, against the same 16 calls issued one by one (the library allocates nothing
+        # and records no memset nodes, so its calls can be captured)
+        replay = []
+        side = torch.cuda.Stream()
+        for name in ["cfg1_fc512_b1", "cfg2_gemv2048_q2_b1", "cfg3_lstm4096x1024_q3_b8", "cfg4_sq4096_q3_b32"]:
+            w = CONFIGS[name]
+            L = 16
+            with torch.cuda.stream(side):
+                pr = Problem(biq, torch, w, L, real_first=False)
+                te = time_steps(torch, Calls(pr.prepared), 20, 3, regions=5)
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    for call in pr.prepared:
+                        call()
+                tr = time_steps(torch, Calls([graph.replay]), 20, 3, regions=5)
+            replay.append({"workload": w.name, "calls_per_graph": L, "eager_us_per_call": te.median * 1e6 / L,
+                           "graph_replay_us_per_call": tr.median * 1e6 / L})
+            log("hip graph %s: %.2f us per call replayed (%d calls per graph), %.2f us issued one by one" %
+                (w.name, tr.median * 1e6 / L, L, te.median * 1e6 / L))
+            del graph, pr
+            torch.cuda.empty_cache()
+        out["hip_graph_replay"] = replay
         # the batch-1 bandwidth family: cfg 2's shape with m scaled by powers of two (the launch-latency
         # knee), and the FFN matrices of cfg 5 with one input vector; cold keys, median per call
         fam = []
