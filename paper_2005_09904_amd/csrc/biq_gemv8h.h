@@ -332,13 +332,18 @@ __device__ __forceinline__ void gemv8h_body(const QueryParams& p, const int wg) 
         int s = wave_u;
         // the tile's inputs, then its first step of keys (a wave without a step: step 0 again),
         // are requested before its tables are built; the build waits for the inputs alone
-        if (x_ahead) gemv8h_job_x_ahead(p, tl * kGemvHalfTileChunks, tid, xa);
+        // (the inputs of a further tile were requested a tile ahead, right after the build before)
+        if (x_ahead && tl == tile0) gemv8h_job_x_ahead(p, tl * kGemvHalfTileChunks, tid, xa);
         load_step(s, 0, k, al);
         BIQ_STAMP(p, 1);
         if (tl != tile0) __syncthreads();  // every wave is done with the previous tables
         if constexpr (FUSED) {
-            if (x_ahead) gemv8h_job_build(p, lds_bytes, tl * kGemvHalfTileChunks, tid, xa);
-            else gemv8h_build_tile(p, lds_bytes, tl * kGemvHalfTileChunks, tid, nthreads);
+            if (x_ahead) {
+                gemv8h_job_build(p, lds_bytes, tl * kGemvHalfTileChunks, tid, xa);
+                if (tl + 1 < tile1) gemv8h_job_x_ahead(p, (tl + 1) * kGemvHalfTileChunks, tid, xa);
+            } else {
+                gemv8h_build_tile(p, lds_bytes, tl * kGemvHalfTileChunks, tid, nthreads);
+            }
         } else {
             gemv8h_copy_tile(p, lds_bytes, tl * kGemvHalfTileChunks, tid, nthreads);
         }
