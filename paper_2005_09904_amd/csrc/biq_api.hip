@@ -273,9 +273,10 @@ bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool table
                 pl.xcd_skew = ((pl.rows_per_wg * permille / 1000 + 16) / 32) * 32;
                 if (tiles > 1 && pl.rows_per_wg + pl.xcd_skew > 8192) pl.xcd_skew = 0;
             }
-        } else if (C > kGemvTileChunks && (long long)m * ceil_div(C, kGemvHalfTileChunks) <= 256ll * kNumCu) {
-            // small, wider than one full-table tile: half tables (256 chunks per workgroup), so that
-            // rows up to n = 2048 need no split and no second kernel.  One workgroup per CU if the
+        } else if (C > kGemvTileChunks && (long long)m * ceil_div(C, kGemvHalfTileChunks) <= 512ll * kNumCu) {
+            // small and mid-size (up to where a workgroup of the full-table kernel gets 512 rows and
+            // walks all its tiles), wider than one full-table tile: half tables (256 chunks per
+            // workgroup), so that rows up to n = 2048 need no split and no second kernel.  One workgroup per CU if the
             // rows allow it (a second round of workgroups pays the table build again), at least
             // 8 rows each; 4 rows per wave step, at most 4 steps per wave.
             pl.kernel = KERNEL_GEMV8H;
