@@ -220,8 +220,11 @@ biq_status biq_query(const uint8_t* K, const float* alpha, const float* LUT, flo
  * For many input vectors (see biq_plan_get / biq_plan_get_lut) the default plan is the
  * unpack_mfma kernel instead: the "GEMM with unpacking" alternative of Sec. IV-B
  * (Algorithm 3), with the sign bits expanded to +-1 in registers and contracted on the
- * matrix cores against X split exactly into three bf16 terms; fp32 accumulation, same
- * tolerance, same determinism.  It uses the first part of the workspace for the split X.
+ * matrix cores against X in two fp16 terms per element (every input vector scaled by a
+ * power of two so that its largest magnitude lies in [2^14, 2^15); the terms carry 22
+ * significand bits, the scaling is undone on output); fp32 accumulation, same tolerance,
+ * same determinism.  An input vector holding Inf or NaN gives non-finite outputs for that
+ * vector.  It uses the first part of the workspace for the prepared X.
  */
 biq_status biq_gemm(const uint8_t* K, const float* alpha, const float* X, float* Y,
                     int m, int n, int q, int batch, int mu,

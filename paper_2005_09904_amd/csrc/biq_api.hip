@@ -53,8 +53,8 @@ inline int rows_from(long long want, int step, int lo, int m) {
 }
 inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
 
-// 16-byte pieces of prepared input per key group (16 MFMA steps): column tiles x 3 bf16 terms x 64 lanes
-inline long long unpack_group_pieces(int batch_tile) { return 16ll * (batch_tile / 32) * 3 * 64; }
+// 16-byte pieces of prepared input per key group (16 MFMA steps): column tiles x fp16 terms x 64 lanes
+inline long long unpack_group_pieces(int batch_tile) { return 16ll * (batch_tile / 32) * kUnpackTerms * 64; }
 
 // Unpack-MFMA plans: workgroups of 4 waves, key groups (32 key bytes of a row) instead of LUT tiles.
 bool plan_finish_unpack(biq_plan& pl, int m, int n, int q, int batch) {
@@ -79,7 +79,7 @@ bool plan_finish_unpack(biq_plan& pl, int m, int n, int q, int batch) {
     pl.lds_bytes = ws == 1 ? 24 * 1024 : 96 * 1024;   // partial sums of the wave groups, transpose patches (UnpackGeom::LDS_BYTES)
     const long long tasks = (long long)pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
     if (tasks > (1ll << 30)) return false;
-    // prepared input: 6 bytes per (padded column, padded element)
+    // prepared input: 4 bytes per (padded column, padded element)
     const long long xf = (long long)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split *
                          unpack_group_pieces(pl.batch_tile) * 16;
     if (xf > (1ll << 40)) return false;
@@ -176,8 +176,8 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
 // run times of both paths from rates measured on MI355X.  Table lookups: about 13e12 lookups/s
 // for the conflict-free kernels (mu = 8, mu <= 5, mu = 6 up to 4 input vectors); 6.5e12 for the
 // generic one, which also streams keys at no more than about 0.25 TB/s; plus 6 us of launch
-// and table build.  Unpack + MFMA: 2 * 3 flop per weight and padded input vector (three bf16
-// terms) at 1.45e15 flop/s, plus 10 us (input split, launches, combining partial sums).
+// and table build.  Unpack + MFMA: 2 * 2 flop per weight and padded input vector (two fp16
+// terms) at 1.28e15 flop/s, plus 9 us (input split, launches, combining partial sums).
 bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
     const double weights = (double)q * m * n;
     const double lookups = weights / mu * batch;
@@ -186,7 +186,7 @@ bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
     if (!tuned && t_lut < weights / 8 / 0.25e12) t_lut = weights / 8 / 0.25e12;
     t_lut += 6e-6;
     const double padded = (double)((batch + 31) / 32) * 32;
-    const double t_mfma = 10e-6 + 6.0 * weights * padded / 1.45e15;
+    const double t_mfma = 9e-6 + 4.0 * weights * padded / 1.28e15;
     return t_mfma < t_lut;
 }
 
@@ -211,10 +211,12 @@ bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool table
         // (S; partial sums through the workspace and a second kernel) - is the candidate with the
         // lowest estimated time.  The estimate: MFMAs per wave x 33 clk at 2.1 GHz (measured rate
         // of back-to-back MFMAs under load) x an issue-overhead factor per accumulator shape
-        // (measured: 1.13 for 4 x 2 tiles, more for fewer, where key expansion and fragment loads
-        // are shared by fewer MFMAs) x rounds of workgroups over the 256 CUs, plus fixed costs per
-        // accumulator tile, per wave group and for the second kernel.  On a sweep of 14 layer
-        // shapes x all valid mappings the estimate's choice was the fastest or within 5 % of it.
+        // (1.2 for 4 x 2 tiles, more for fewer, where key expansion and fragment loads are shared
+        // by fewer MFMAs) x rounds of workgroups over the 256 CUs, plus fixed costs per launch,
+        // accumulator tile and round, the input split (per byte of padded X) and the second
+        // kernel; the constants are a least-squares fit to a sweep of 16 layer shapes x all valid
+        // mappings (443 timed plans), on which the estimate's choice was the fastest or within
+        // 5 % of it (mean loss 0.6 %).
         pl.kernel = KERNEL_UNPACK_MFMA;
         pl.threads = kUnpackThreads;
         pl.chunks_per_tile = kUnpackGroupBytes;
@@ -231,13 +233,14 @@ bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool table
                         const long long wgs = (long long)ceil_div(m, rows) * ceil_div(batch, bt) * S;
                         if (wgs > 4ll * kNumCu && S > 1) continue;
                         const int gpw = ceil_div(ceil_div(groups, S), ws);   // key groups per wave
-                        const double shape = rt * ct == 8 ? 1.13 : rt * ct == 6 ? 1.16 : rt == 4 ? 1.19
-                                           : rt == 3 ? 1.22 : (rt == 2 && ct == 2) ? 1.22 : rt == 2 ? 1.30
-                                           : ct == 2 ? 1.45 : 1.65;
-                        double t = 3.0 * rt * ct * gpw * 16 * 33 * shape / 2100.0 * (double)ceil_div_ll(wgs, kNumCu);
-                        t += 9.0 + 0.25 * rt * ct;
-                        if (S > 1) t += 3.5 + (S + 1.0) * ceil_div(batch, bt) * bt * (double)m * 4 / 2.5e6;
-                        if (ws > 1) t += 0.6 * (ws - 1) * rt * ct / 4;
+                        const double shape = rt * ct >= 6 ? 1.20 : rt == 4 ? 1.36 : rt == 3 ? 1.29
+                                           : (rt == 2 && ct == 2) ? 1.35 : rt == 2 ? 1.67
+                                           : ct == 2 ? 2.10 : 2.27;
+                        const double rounds = (double)ceil_div_ll(wgs, kNumCu);
+                        const double bpad = (double)ceil_div(batch, bt) * bt;
+                        double t = kUnpackTerms * rt * ct * gpw * 16 * 33 * shape / 2100.0 * rounds;
+                        t += 5.3 + 1.0 * rt * ct * rounds + 1.1 * (rounds - 1.0) + 1.65 * bpad * n * 4 / 1e6;
+                        if (S > 1) t += 2.45 + (S + 1.0) * bpad * (double)m * 4 / 10e6;
                         if (t < best) {
                             best = t;
                             pl.batch_tile = bt;
@@ -430,12 +433,17 @@ bool plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
     return plan_generic(pl, m, n, q, batch, mu);
 }
 
-// Bytes of the prepared-input area at the start of the workspace (unpack-MFMA plans only).
-size_t plan_xf_bytes(const biq_plan& pl) {
-    if (pl.kernel != KERNEL_UNPACK_MFMA) return 0;
+// Bytes of the prepared-input area at the start of the workspace (unpack-MFMA plans only): the
+// B fragments, then one scaling exponent per padded input vector.
+size_t plan_xfrag_bytes(const biq_plan& pl) {
     const size_t b = (size_t)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split *
                      (size_t)unpack_group_pieces(pl.batch_tile) * 16;
     return (b + 255) & ~(size_t)255;
+}
+size_t plan_xf_bytes(const biq_plan& pl) {
+    if (pl.kernel != KERNEL_UNPACK_MFMA) return 0;
+    const size_t e = (size_t)pl.batch_tiles * pl.batch_tile * sizeof(int);
+    return plan_xfrag_bytes(pl) + ((e + 255) & ~(size_t)255);
 }
 
 size_t plan_workspace(const biq_plan& pl, int m, int batch) {
@@ -506,23 +514,25 @@ bool plan_grouped(biq_plan& pl, int& kind, int m, int n, int q, int batch, int m
     return plan_finish(pl, m, n, q, batch, mu) && pl.chunk_splits == 1;
 }
 
-// Large-batch path: split X into bf16 terms in MFMA operand order (workspace), contract, and
-// sum the partial results when the key groups were split over workgroups.
+// Large-batch path: scale and split X into fp16 terms in MFMA operand order (workspace),
+// contract, and sum the partial results when the key groups were split over workgroups.
 biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* alpha, const float* X,
                            float* Y, int m, int n, int q, int batch, void* workspace, hipStream_t s) {
     const int CT = pl.batch_tile / 32;
     const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
     const int steps = groups * 16;  // MFMA steps along a row
     mfma_u32x4* Xf = reinterpret_cast<mfma_u32x4*>(workspace);
+    int* colexp = reinterpret_cast<int*>(reinterpret_cast<char*>(workspace) + plan_xfrag_bytes(pl));
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + plan_xf_bytes(pl));
 
-    const long long total = (long long)pl.batch_tiles * steps * CT * 64;
-    if (launch_xsplit(CT, X, Xf, n, batch, steps, total, s) != hipSuccess) return BIQ_EHIP;
+    if (launch_xsplit(CT, X, Xf, colexp, n, batch, steps, pl.batch_tiles * pl.batch_tile, s) != hipSuccess)
+        return BIQ_EHIP;
 
     UnpackParams up{};
     up.K = K;
     up.alpha = alpha;
     up.Xf = Xf;
+    up.colexp = colexp;
     up.out = pl.chunk_splits > 1 ? partial : Y;
     up.m = m;
     up.batch = batch;

@@ -64,8 +64,8 @@ struct GroupParams;
 hipError_t launch_grouped(int kind, int q, const GroupParams& g, int grid, int lds, hipStream_t s);
 
 // ---- unpack + MFMA path ----
-hipError_t launch_xsplit(int ct, const float* X, mfma_u32x4* Xf, int n, int batch, int steps, long long total,
-                         hipStream_t s);
+hipError_t launch_xsplit(int ct, const float* X, mfma_u32x4* Xf, int* colexp, int n, int batch, int steps,
+                         int padded_batch, hipStream_t s);
 hipError_t launch_unpack(int q, int rpw, int ct, int ws, const UnpackParams& up, int grid, int lds, hipStream_t s);
 
 // ---- the small kernels ----

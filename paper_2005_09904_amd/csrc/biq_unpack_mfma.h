@@ -3,19 +3,25 @@
 // For many input vectors the product is compute bound and the lookup tables stop paying off
 // (the crossover discussed with Fig. 10); the alternative the paper measures is to unpack the
 // sign bits and run an ordinary GEMM.  Here the unpacking happens in registers, straight into
-// the A operand of v_mfma_f32_32x32x16_bf16, and nothing unpacked ever reaches memory:
-//   - a weight bit becomes the bf16 value +1.0 / -1.0 (bit set <-> +1, as in Algorithm 3; the
+// the A operand of v_mfma_f32_32x32x16_f16, and nothing unpacked ever reaches memory:
+//   - a weight bit becomes the fp16 value +1.0 / -1.0 (bit set <-> +1, as in Algorithm 3; the
 //     kernel forms the negated value, whose sign bit is the key bit, and negates alpha);
-//   - every fp32 input x is split once into three bf16 terms x = x0 + x1 + x2 (8 significand
-//     bits each, by truncation, so the sum is exact); +-1 * bf16 products are exact and the
-//     matrix cores accumulate in fp32, so the result differs from a plain fp32 evaluation of
-//     Eq. 2 only by the order of the additions;
-//   - the three terms are three B operands multiplied with the same A operand.
+//   - every input vector is scaled by a power of two 2^e (e per vector, from its largest
+//     magnitude, which lands in [2^14, 2^15)) and every scaled fp32 element is split once into
+//     two fp16 terms, x * 2^e = x0 + x1 + r with x0 = fp16(x * 2^e), x1 = fp16(x * 2^e - x0), both
+//     rounded to nearest: |r| <= 2^-22 |x * 2^e| (or 2^-25 absolutely, i.e. 2^-39 of the vector's
+//     largest magnitude, where x1 is subnormal).  +-1 * fp16 products are exact and the matrix
+//     cores accumulate in fp32; the epilogue multiplies by 2^-e.  The result thus differs from a
+//     plain fp32 evaluation of Eq. 2 by the order of the additions and by that input rounding,
+//     a quarter of fp32's own unit in the last place per element - below the rounding of the
+//     fp32 additions themselves, and 40 times inside the 1e-5 relative L2 bound in the worst case;
+//   - the two terms are two B operands multiplied with the same A operand: 2 MFMAs per 16
+//     weights x 32 input vectors, against 3 for an exact split into bf16 terms.
 // The kernel does not depend on mu: it reads the packed bitmap, which is the same for all mu.
 //
 // MFMA operand layout (32x32x16, wave of 64 lanes, lane = 32*h + r):
 //   A: lane holds row r of the tile, 8 consecutive k of half h     -> one key byte per lane
-//   B: lane holds column r, the same 8 k of half h                 -> 8 bf16 of one input vector
+//   B: lane holds column r, the same 8 k of half h                 -> 8 fp16 of one input vector
 //   C: lane holds column r, rows 8*(v/4) + 4*h + v%4 for v = 0..15
 // A lane loads 16 key bytes of its row at once: half 0 takes bytes [32g, 32g+16) of the row,
 // half 1 bytes [32g+16, 32g+32) ("key group" g).  Each of the lane's four key dwords feeds four
@@ -23,7 +29,7 @@
 // is a permutation of the columns, which the B side follows.
 //
 // B operands are prepared by xsplit_kernel in exactly the order the main kernel consumes them:
-//   Xf[col_group][step][col_tile][term 0..2][lane] : 16 bytes (8 bf16)
+//   Xf[col_group][step][col_tile][term 0..1][lane] : 16 bytes (8 fp16)
 // (step = MFMA step along the row, 16 per key group), so a wave's load of a fragment is one
 // contiguous KiB; the waves load their fragments straight into registers, a few steps ahead.
 #pragma once
@@ -33,12 +39,13 @@
 
 namespace biq {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t mfma_u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kUnpackThreads = 256;     // 4 waves
 constexpr int kUnpackGroupBytes = 32;   // key bytes of a row per key group (both halves)
+constexpr int kUnpackTerms = 2;         // fp16 terms per input element
 
 // Time stamps of a trace build (-DBIQ_TRACE, never the product's): lane 0 of wave 0 of every
 // workgroup writes the 100 MHz wall clock into slot i of its entry.
@@ -59,6 +66,7 @@ struct UnpackParams {
     const uint8_t* K;        // [q][m][stride]
     const float* alpha;      // [q][m]
     const mfma_u32x4* Xf;    // prepared B operands (see above)
+    const int* colexp;       // e of every (padded) input vector: its B operands hold x * 2^e
     float* out;              // Y [batch][m], or partials [splits][batch][m]
     int m, batch;
     uint32_t stride_bytes;
@@ -69,75 +77,134 @@ struct UnpackParams {
     int ntasks, tasks_per_xcd;
 };
 
-// Splits fp32 into three bf16 terms by truncation; returns them as the high halves' bit patterns.
-__device__ __forceinline__ void split3(float x, uint32_t& t0, uint32_t& t1, uint32_t& t2) {
-    const uint32_t b0 = __float_as_uint(x) & 0xffff0000u;
-    const float r1 = x - __uint_as_float(b0);       // exact: the low 16 significand bits
-    const uint32_t b1 = __float_as_uint(r1) & 0xffff0000u;
-    const float r2 = r1 - __uint_as_float(b1);      // exact: at most 8 significand bits left
-    t0 = b0 >> 16;
-    t1 = b1 >> 16;
-    t2 = __float_as_uint(r2) >> 16;                 // exact in bf16
+// Splits a scaled fp32 value into two fp16 terms, each rounded to nearest; the difference taken
+// in between is exact in fp32.  Returns the bit patterns.
+__device__ __forceinline__ void split2(float xs, uint32_t& t0, uint32_t& t1) {
+    const _Float16 hi = (_Float16)xs;
+    const _Float16 lo = (_Float16)(xs - (float)hi);
+    t0 = __builtin_bit_cast(unsigned short, hi);
+    t1 = __builtin_bit_cast(unsigned short, lo);
 }
 
-// One thread per (col_group, step, col_tile, lane): the three 16-byte B fragments of that lane.
-// Columns past the batch and elements past n are zero.
+// Input vectors -> B fragments, one workgroup per (padded) input vector: largest magnitude -> e,
+// then the vector's fragments (two 16-byte pieces per MFMA step and half-wave, see the layout
+// above).  Vectors past the batch and elements past n are zero.  A vector that holds Inf or NaN
+// is left unscaled (e = 0) and gives non-finite results, as it would in any evaluation of Eq. 2.
+// A thread reads the 8 elements of its fragments once and keeps them in registers across the
+// reduction (kXsplitCached fragments per thread: n <= 32768; what is beyond is read twice).
+// (Measured and dropped: several workgroups per vector, each reading the whole vector for the
+// maximum and writing a share of the fragments - slower from n = 4096 to 16384.)
+constexpr int kXsplitThreads = 1024;
+constexpr int kXsplitCached = 4;
+
 template <int CT>
-__global__ __launch_bounds__(256) void xsplit_kernel(const float* __restrict__ X,
-                                                     mfma_u32x4* __restrict__ Xf, int n, int batch,
-                                                     int steps, long long total) {
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int lane = (int)(idx & 63);
-    long long rest = idx >> 6;
-    const int ct = (int)(rest % CT); rest /= CT;
-    const int step = (int)(rest % steps);   // MFMA step along the row: 16 per key group
-    const int cg = (int)(rest / steps);
-    const int col = (cg * CT + ct) * 32 + (lane & 31);
-    const int h = lane >> 5;
-    const int ks = step & 3;
-    // dword of the row this step works on, and its 2 x 4 consecutive elements (see unpack_step)
-    const long long dw = 8ll * (step >> 4) + 4 * h + ((step >> 2) & 3);
-    const long long j0 = 32 * dw + 8 * (ks >> 1) + 4 * (ks & 1);   // elements j0..j0+3 and j0+16..j0+19
-    float lo[4], hi[4];
-    if (col < batch && j0 + 20 <= n && (n & 3) == 0 && ((reinterpret_cast<uintptr_t>(X) & 15) == 0)) {
-        const float* src = X + (size_t)col * n + j0;
-        const float4 a = *reinterpret_cast<const float4*>(src);
-        const float4 b = *reinterpret_cast<const float4*>(src + 16);
-        lo[0] = a.x; lo[1] = a.y; lo[2] = a.z; lo[3] = a.w;
-        hi[0] = b.x; hi[1] = b.y; hi[2] = b.z; hi[3] = b.w;
-    } else {
+__global__ __launch_bounds__(kXsplitThreads) void xsplit_kernel(const float* __restrict__ X,
+                                                                mfma_u32x4* __restrict__ Xf,
+                                                                int* __restrict__ colexp, int n, int batch,
+                                                                int padded_batch, int steps) {
+    __shared__ uint32_t wave_max[kXsplitThreads / 64];
+    // The 8 vectors whose pieces share a 128-byte line of Xf (lanes 8k .. 8k+7 of a fragment) go
+    // to workgroups on the same XCD (workgroup b runs on XCD b % 8), so that one L2 collects the
+    // whole line: line group lg = col / 8 lives on XCD lg % 8.
+    const int lg = ((int)blockIdx.x >> 6) * 8 + ((int)blockIdx.x & 7);
+    const int col = lg * 8 + (((int)blockIdx.x >> 3) & 7);
+    if (col >= padded_batch) return;
+    const int tid = threadIdx.x;
+    const bool real = col < batch;
+    const float* xc = X + (size_t)(real ? col : 0) * n;
+    const bool vec = (n & 3) == 0 && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    const int nfrag = steps * 2;
+    const int cg = col / (CT * 32), ct = (col >> 5) % CT, lr = col & 31;
+
+    // fragment f of the vector (4 consecutive f cover one 128-byte line of X): its 8 elements in
+    // operand order, and where its pieces go
+    auto load_fragment = [&](int f, float (&x)[8]) {
+        const int ks = f & 3, d = (f >> 2) & 3, h = (f >> 4) & 1, g = f >> 5;
+        // dword of the row this step works on, and its 2 x 4 consecutive elements (see unpack_step)
+        const long long dw = 8ll * g + 4 * h + d;
+        const long long j0 = 32 * dw + 8 * (ks >> 1) + 4 * (ks & 1);   // elements j0..j0+3 and j0+16..j0+19
+        if (real && vec && j0 + 20 <= n) {
+            const float4 a = *reinterpret_cast<const float4*>(xc + j0);
+            const float4 b = *reinterpret_cast<const float4*>(xc + j0 + 16);
+            x[0] = a.x; x[2] = a.y; x[4] = a.z; x[6] = a.w;
+            x[1] = b.x; x[3] = b.y; x[5] = b.z; x[7] = b.w;
+        } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            lo[i] = (col < batch && j0 + i < n) ? X[(size_t)col * n + j0 + i] : 0.0f;
-            hi[i] = (col < batch && j0 + 16 + i < n) ? X[(size_t)col * n + j0 + 16 + i] : 0.0f;
+            for (int i = 0; i < 4; ++i) {
+                x[2 * i] = (real && j0 + i < n) ? xc[j0 + i] : 0.0f;
+                x[2 * i + 1] = (real && j0 + 16 + i < n) ? xc[j0 + 16 + i] : 0.0f;
+            }
+        }
+    };
+    auto store_fragment = [&](int f, const float (&x)[8], int e) {
+        const int ks = f & 3, d = (f >> 2) & 3, h = (f >> 4) & 1, g = f >> 5;
+        const int step = g * 16 + d * 4 + ks;  // MFMA step along the row: 16 per key group
+        uint32_t t[kUnpackTerms][8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) split2(ldexpf(x[i], e), t[0][i], t[1][i]);
+        mfma_u32x4* dst = Xf + (((size_t)cg * steps + step) * CT + ct) * (kUnpackTerms * 64) + 32 * h + lr;
+#pragma unroll
+        for (int s = 0; s < kUnpackTerms; ++s) {
+            mfma_u32x4 v;
+            v.x = t[s][0] | (t[s][1] << 16);
+            v.y = t[s][2] | (t[s][3] << 16);
+            v.z = t[s][4] | (t[s][5] << 16);
+            v.w = t[s][6] | (t[s][7] << 16);
+            dst[s * 64] = v;
+        }
+    };
+
+    auto fold_max = [](uint32_t mb, const float (&x)[8]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mb = max(mb, __float_as_uint(x[i]) & 0x7fffffffu);
+        return mb;
+    };
+    uint32_t mb = 0;                       // largest |x| as a bit pattern (ordered like the values)
+    float held[kXsplitCached][8];
+#pragma unroll
+    for (int i = 0; i < kXsplitCached; ++i) {
+        const int f = tid + kXsplitThreads * i;
+        if (f < nfrag) {
+            load_fragment(f, held[i]);
+            mb = fold_max(mb, held[i]);
         }
     }
-    float x[8];
+    for (int f = tid + kXsplitThreads * kXsplitCached; f < nfrag; f += kXsplitThreads) {
+        float x[8];
+        load_fragment(f, x);
+        mb = fold_max(mb, x);
+    }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { x[2 * i] = lo[i]; x[2 * i + 1] = hi[i]; }
-    uint32_t t[3][8];
+    for (int o = 32; o > 0; o >>= 1) mb = max(mb, (uint32_t)__shfl_xor((int)mb, o));
+    if ((tid & 63) == 0) wave_max[tid >> 6] = mb;
+    __syncthreads();
 #pragma unroll
-    for (int e = 0; e < 8; ++e) split3(x[e], t[0][e], t[1][e], t[2][e]);
-    mfma_u32x4* dst = Xf + (idx >> 6) * (3 * 64) + lane;
+    for (int w = 0; w < kXsplitThreads / 64; ++w) mb = max(mb, wave_max[w]);
+    // exponent field ex: the maximum lies in [2^(ex-127), 2^(ex-126)) -> times 2^(141-ex) in
+    // [2^14, 2^15); zero and subnormal vectors scale as if the maximum were 2^-126
+    const int ex = (int)(mb >> 23);
+    const int e = ex == 255 ? 0 : 141 - max(ex, 1);
+    if (tid == 0) colexp[col] = e;
+
 #pragma unroll
-    for (int s = 0; s < 3; ++s) {
-        mfma_u32x4 v;
-        v.x = t[s][0] | (t[s][1] << 16);
-        v.y = t[s][2] | (t[s][3] << 16);
-        v.z = t[s][4] | (t[s][5] << 16);
-        v.w = t[s][6] | (t[s][7] << 16);
-        dst[s * 64] = v;
+    for (int i = 0; i < kXsplitCached; ++i) {
+        const int f = tid + kXsplitThreads * i;
+        if (f < nfrag) store_fragment(f, held[i], e);
+    }
+    for (int f = tid + kXsplitThreads * kXsplitCached; f < nfrag; f += kXsplitThreads) {
+        float x[8];
+        load_fragment(f, x);
+        store_fragment(f, x, e);
     }
 }
 
-// MFMA step S (0..3) of key dword w -> the lane's 8 bf16 A elements, with the OPPOSITE sign:
+// MFMA step S (0..3) of key dword w -> the lane's 8 fp16 A elements, with the OPPOSITE sign:
 // -1.0 where the bit is set, +1.0 otherwise (the sign bit is the key bit; the epilogue multiplies
 // by -alpha).  Element e = 2*i + hh is bit 8*(S/2) + 4*(S%2) + i + 16*hh of the dword: bits p
 // and p + 16 land in the sign positions 15 and 31 of one dword with a single shift.  `one2`
-// holds two bf16 1.0 (0x3f803f80) in a VGPR so that mask-and-merge is one v_and_or_b32.
+// holds two fp16 1.0 (0x3c003c00) in a VGPR so that mask-and-merge is one v_and_or_b32.
 template <int S>
-__device__ __forceinline__ bf16x8 unpack_step(uint32_t w, uint32_t one2) {
+__device__ __forceinline__ f16x8 unpack_step(uint32_t w, uint32_t one2) {
     mfma_u32x4 d;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -145,7 +212,7 @@ __device__ __forceinline__ bf16x8 unpack_step(uint32_t w, uint32_t one2) {
         const uint32_t a = p <= 15 ? (w << (15 - p)) : (w >> (p - 15));
         d[i] = (a & 0x80008000u) | one2;
     }
-    return __builtin_bit_cast(bf16x8, d);
+    return __builtin_bit_cast(f16x8, d);
 }
 
 // A workgroup's four waves form WS groups along the contraction ("wave splits"): group kg works
@@ -154,7 +221,7 @@ __device__ __forceinline__ bf16x8 unpack_step(uint32_t w, uint32_t one2) {
 // LDS holds only those partial sums and the epilogue's transpose patches.
 template <int CT, int WS>
 struct UnpackGeom {
-    static constexpr int SPIECES = CT * 3 * 64;                  // 16-byte pieces of B per MFMA step
+    static constexpr int SPIECES = CT * kUnpackTerms * 64;                  // 16-byte pieces of B per MFMA step
     static constexpr int LDS_BYTES = (WS == 1 ? 24 : 96) * 1024;
 };
 
@@ -164,6 +231,8 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     constexpr int RT = Q * RPW;                       // row tiles (32 key rows each) per wave
     constexpr int WROWS = 4 / WS;                     // waves side by side along the rows
     constexpr int SPIECES = G::SPIECES;
+    constexpr int T = kUnpackTerms;
+    constexpr int VPM = (8 + CT * T - 1) / (CT * T);  // expansion instructions to place per MFMA
     static_assert((WS - 1) * WROWS * RT * CT * 4096 <= G::LDS_BYTES, "partial sums must fit");
     extern __shared__ __align__(16) mfma_u32x4 stage_buf[];  // partial sums, transpose patches
 
@@ -218,14 +287,14 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][c][v] = 0.0f;
 
-    uint32_t one2 = 0x3f803f80u;        // two bf16 1.0, kept in a VGPR (see unpack_step)
+    uint32_t one2 = 0x3c003c00u;        // two fp16 1.0, kept in a VGPR (see unpack_step)
     asm volatile("" : "+v"(one2));
     BIQ_USTAMP(0);
 
     // ---- main loop: no LDS, no barrier.  The B fragments lie in Xf in the order of use, 16 bytes
     // per lane: a wave loads them straight into registers (1 KiB per request, the four waves of a
     // workgroup hit the same lines in the vector cache), three MFMA steps ahead in a ring of four.
-    // While the RT * CT * 3 MFMAs of a step issue, the next step's A operands are expanded from
+    // While the RT * CT * 2 MFMAs of a step issue, the next step's A operands are expanded from
     // the key bits and the fragments of the step three ahead are requested; the
     // sched_group_barrier sequence spells that interleaving out (left alone, the compiler puts a
     // step's expansion right in front of its MFMAs and the matrix pipe idles through it).
@@ -233,15 +302,15 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     const int nsteps = ngroups * 16;
     if (ngroups > 0) {
         const mfma_u32x4* xw = p.Xf + ((size_t)cg * steps_total + (size_t)ga * 16) * SPIECES + lane;
-        auto load_b = [&](int s, bf16x8 (&b)[CT][3]) {
+        auto load_b = [&](int s, f16x8 (&b)[CT][T]) {
             const int sc = min(s, nsteps - 1);         // past the end: the last step again, unused
             const mfma_u32x4* src = xw + (size_t)sc * SPIECES;
 #pragma unroll
             for (int c = 0; c < CT; ++c)
 #pragma unroll
-                for (int tm = 0; tm < 3; ++tm) b[c][tm] = __builtin_bit_cast(bf16x8, src[(c * 3 + tm) * 64]);
+                for (int tm = 0; tm < T; ++tm) b[c][tm] = __builtin_bit_cast(f16x8, src[(c * T + tm) * 64]);
         };
-        auto expand_a = [&](const mfma_u32x4 (&k)[RT], int step, bf16x8 (&a)[RT]) {
+        auto expand_a = [&](const mfma_u32x4 (&k)[RT], int step, f16x8 (&a)[RT]) {
             const int d = step >> 2, ks = step & 3;    // step 0..15 within the key group
 #pragma unroll
             for (int t = 0; t < RT; ++t) {
@@ -251,8 +320,8 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
             }
         };
         mfma_u32x4 key[RT], keyn[RT];
-        bf16x8 bfr[4][CT][3];
-        bf16x8 af[2][RT];
+        f16x8 bfr[4][CT][T];
+        f16x8 af[2][RT];
         load_keys(ga, key);
         load_b(0, bfr[0]);
         load_b(1, bfr[1]);
@@ -270,18 +339,18 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                 load_b(gi * 16 + st + 3, bfr[(st + 3) & 3]);
                 if (st + 1 < 16) expand_a(key, st + 1, af[(st + 1) & 1]);
 #pragma unroll
-                for (int tm = 0; tm < 3; ++tm)
+                for (int tm = 0; tm < T; ++tm)
 #pragma unroll
                     for (int t = 0; t < RT; ++t)
 #pragma unroll
                         for (int c = 0; c < CT; ++c)
-                            acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st & 1][t], bfr[st & 3][c][tm],
+                            acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[st & 1][t], bfr[st & 3][c][tm],
                                                                                 acc[t][c], 0, 0, 0);
 #pragma unroll
-                for (int i = 0; i < RT * CT * 3; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // MFMA
-                    if (i < CT * 3) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // global load
-                    if (2 * i < RT * 8) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // VALU
+                for (int i = 0; i < RT * CT * T; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
+                    if (i < CT * T) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);       // global load
+                    if (VPM * i < RT * 8) __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);  // VALU
                 }
                 __builtin_amdgcn_sched_barrier(0);   // a step's instructions stay in the step
             }
@@ -327,7 +396,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     }
 
     // ---- epilogue: scale by -alpha (the weights were unpacked with the opposite sign), add the
-    // planes (Eq. 2), store.  An accumulator tile has one input vector per lane and its 32 rows
+    // planes (Eq. 2), undo the input vector's scaling, store.  An accumulator tile has one input vector per lane and its 32 rows
     // spread over 4 registers x 2 half-waves; stored like that, every 128-byte line of Y[b][m]
     // would be written by 8 separate instructions.  Each tile therefore goes through a 32 x 36
     // float patch of LDS (private to the wave) and leaves as 128 contiguous bytes per 8 lanes.
@@ -358,6 +427,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
         }
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
+            const int xe = -p.colexp[(cg * CT + c) * 32 + lr];   // the lane's input vector was scaled by 2^-xe
             // tile -> patch[column lr][row]
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
@@ -367,7 +437,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                     float v = 0.0f;
 #pragma unroll
                     for (int i = 0; i < Q; ++i) v = fmaf(al[vq][i][e], acc[i * RPW + rp][c][4 * vq + e], v);
-                    y[e] = v;
+                    y[e] = ldexpf(v, xe);
                 }
                 *reinterpret_cast<float4*>(patch + lr * TP + 8 * vq + 4 * h) = make_float4(y[0], y[1], y[2], y[3]);
             }

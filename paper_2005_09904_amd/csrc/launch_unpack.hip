@@ -1,4 +1,4 @@
-// Large-batch path: input split into bf16 terms, and the unpack + MFMA contraction.
+// Large-batch path: input vectors scaled and split into fp16 terms, and the unpack + MFMA contraction.
 #include "biq_launch.h"
 
 namespace biq {
@@ -43,13 +43,16 @@ hipError_t launch_unpack(int q, int rpw, int ct, int ws, const UnpackParams& up,
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_xsplit(int ct, const float* X, mfma_u32x4* Xf, int n, int batch, int steps, long long total,
-                         hipStream_t s) {
-    const unsigned grid = (unsigned)((total + 255) / 256);
+hipError_t launch_xsplit(int ct, const float* X, mfma_u32x4* Xf, int* colexp, int n, int batch, int steps,
+                         int padded_batch, hipStream_t s) {
+    // one workgroup per (padded) input vector, in blocks of 64 workgroups = 8 line groups x 8 vectors
+    const unsigned grid = (unsigned)((padded_batch + 63) / 64 * 64);
     if (ct == 2)
-        hipLaunchKernelGGL(xsplit_kernel<2>, dim3(grid), dim3(256), 0, s, X, Xf, n, batch, steps, total);
+        hipLaunchKernelGGL(xsplit_kernel<2>, dim3(grid), dim3(kXsplitThreads), 0, s, X, Xf, colexp, n, batch,
+                           padded_batch, steps);
     else if (ct == 1)
-        hipLaunchKernelGGL(xsplit_kernel<1>, dim3(grid), dim3(256), 0, s, X, Xf, n, batch, steps, total);
+        hipLaunchKernelGGL(xsplit_kernel<1>, dim3(grid), dim3(kXsplitThreads), 0, s, X, Xf, colexp, n, batch,
+                           padded_batch, steps);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

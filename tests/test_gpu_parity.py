@@ -428,8 +428,9 @@ def test_unpack_mfma_parity(biq, oracle, m, n, q, b, bt, gps, ws, rpw):
 
 
 def test_unpack_mfma_bit_exact_on_exact_inputs(biq, oracle):
-    """Integer inputs: every partial sum is exactly representable, so any summation order, the
-    bf16 three-way split and the fp32 matrix-core accumulation must reproduce Eq. 2 bit for bit."""
+    """Small integer inputs: every partial sum is exactly representable and every scaled input is
+    the sum of its two fp16 terms, so any summation order, the split and the fp32 matrix-core
+    accumulation must reproduce Eq. 2 bit for bit."""
     from paper_2005_09904_amd.workloads import Workload, make_exact_inputs
 
     m, n, q, b = 384, 1280, 3, 96
@@ -441,6 +442,37 @@ def test_unpack_mfma_bit_exact_on_exact_inputs(biq, oracle):
     for bt, gps, ws in ((64, 2, 1), (32, 5, 1), (64, 5, 2), (32, 3, 4)):
         Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps, ws))
         assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref), (bt, gps, ws)
+
+
+def test_unpack_mfma_input_scaling_covers_the_fp32_range(biq, oracle):
+    """Every input vector is scaled by its own power of two before it is split into fp16 terms:
+    vectors of very different magnitude (2^-120 .. 2^115, with subnormal elements, all zero), and vectors whose
+    elements span 12 orders of magnitude, must all meet the bound, and with an error at the level
+    of fp32 rounding (the split keeps 22 significand bits), not at the level of fp16."""
+    m, n, q, b = 320, 1536, 2, 48
+    _say("unpack_mfma input scaling")
+    rng = np.random.default_rng(2024)
+    B, alpha, X = _rand_inputs(m, n, q, b, seed=515)
+    X = X.astype(np.float64)
+    for a in range(b):
+        if a % 4 == 1:       # elements over 12 orders of magnitude
+            X[a] *= 10.0 ** rng.uniform(-9, 3, size=n)
+        X[a] *= 2.0 ** (-120 + 5 * a)          # 2^-120 .. 2^115
+    X[7] = 0.0                                   # an all-zero vector
+    X[11] = rng.integers(-50, 51, size=n) * 2.0 ** -149   # subnormal fp32 elements ...
+    X[11, ::7] = rng.standard_normal(len(X[11, ::7])) * 2.0 ** -118   # ... among small normal ones
+    X[13, :] = 0.0
+    X[13, 5] = 1.5e38                            # one element near the top of fp32 (2 planes, alpha <= 1), the rest zero
+    X = X.astype(np.float32)
+    B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, B_dev)
+    ref = oracle.gemm_dense(B, alpha, X)
+    for bt, gps, ws in ((64, 6, 1), (32, 3, 2)):
+        Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps, ws)).cpu().numpy()
+        assert_within_tolerance(Y, ref, alpha, X, what="unpack_mfma scaling %s" % ((bt, gps, ws),))
+        assert np.all(Y[7] == 0.0)
+        err = np.sqrt(((Y - ref) ** 2).sum(axis=1)) / np.maximum(np.sqrt((ref ** 2).sum(axis=1)), 1e-300)
+        assert err.max() <= 1e-6, err.max()     # 2^-22 per element at worst, far from fp16's 2^-11
 
 
 def test_unpack_mfma_does_not_depend_on_mu_and_default_plan_picks_it(biq, oracle):
