@@ -234,7 +234,7 @@ bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool table
                         if (wgs > 4ll * kNumCu && S > 1) continue;
                         const int gpw = ceil_div(ceil_div(groups, S), ws);   // key groups per wave
                         const double shape = rt * ct >= 6 ? 1.20 : rt == 4 ? 1.36 : rt == 3 ? 1.29
-                                           : (rt == 2 && ct == 2) ? 1.35 : rt == 2 ? 1.67
+                                           : (rt == 2 && ct == 2) ? 1.42 : rt == 2 ? 1.67
                                            : ct == 2 ? 2.10 : 2.27;
                         const double rounds = (double)ceil_div_ll(wgs, kNumCu);
                         const double bpad = (double)ceil_div(batch, bt) * bt;
