@@ -351,7 +351,7 @@ def main() -> int:
         rows = [CONFIGS[k] for k in ["cfg1_fc512_b1", "cfg3_lstm4096x1024_q3_b8", "cfg4_sq4096_q3_b32",
                                      "cfg5_ffn_up_q2_b128", "cfg5_ffn_down_q2_b128"]]
         rows += [CONFIGS["cfg5_ffn_up_q2_b128"].with_mu(6), CONFIGS["cfg5_ffn_up_q2_b128"].with_mu(4)]
-        MFMA_BF16_PEAK_TFLOPS = 2500.0
+        MFMA_F16_PEAK_TFLOPS = 2500.0
         for w in rows:
             default = biq.biq_plan_get(w.m, w.n, w.q, w.batch, w.mu)
             lut = biq.biq_plan_get_lut(w.m, w.n, w.q, w.batch, w.mu)
@@ -369,11 +369,11 @@ def main() -> int:
                 s["kernel"] = kname
                 s["default_plan"] = plan is None
                 if kname == "unpack_mfma":
-                    # dense contraction: 2 flop per weight and input vector, times the three bf16
+                    # dense contraction: 2 flop per weight and input vector, times the two fp16
                     # terms of x, on columns padded to the 32-wide MFMA tile
                     padded = -(-w.batch // 32) * 32
-                    s["mfma_TFLOPs"] = 6.0 * w.q * w.m * w.n * padded / t.median / 1e12
-                    s["mfma_frac"] = s["mfma_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+                    s["mfma_TFLOPs"] = 4.0 * w.q * w.m * w.n * padded / t.median / 1e12
+                    s["mfma_frac"] = s["mfma_TFLOPs"] / MFMA_F16_PEAK_TFLOPS
                 elif w.batch > 1:
                     # batched table lookups are bounded by gathers from LDS (4 bytes per lookup)
                     s["lds_gather_GBps"] = 4.0 * w.lookups / t.median / 1e9
