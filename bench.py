@@ -228,8 +228,9 @@ def main() -> int:
     ap.add_argument("--m", type=int, default=0, help="with --workload: number of output rows instead of the workload's "
                                                      "(the batch-1 bandwidth family scales m)")
     ap.add_argument("--batch", type=int, default=0, help="with --workload: number of input vectors instead of the workload's")
-    ap.add_argument("--plan", choices=["default", "lut"], default="default",
-                    help="with --workload: the library's plan, or its choice among the lookup-table kernels only")
+    ap.add_argument("--plan", choices=["default", "lut", "mfma2"], default="default",
+                    help="with --workload: the library's plan, its choice among the lookup-table kernels only, or "
+                         "the matrix-core kernel with two input terms (on request only: plan.input_terms = 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -268,7 +269,8 @@ def main() -> int:
             w = w.scaled_m(args.m)
         if args.batch:
             w = replace(w, batch=args.batch, name="%s_b%d" % (w.name, args.batch))
-        plan = biq.biq_plan_get_lut(w.m, w.n, w.q, w.batch, w.mu) if args.plan == "lut" else None
+        plan = (biq.biq_plan_get_lut(w.m, w.n, w.q, w.batch, w.mu) if args.plan == "lut" else
+                biq.biq_plan_get_mfma(w.m, w.n, w.q, w.batch, w.mu, 2) if args.plan == "mfma2" else None)
         copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
         p = Problem(biq, torch, w, copies, real_first=False, plan=plan)
         steps = min(args.steps, 200 if w.lookups < 1e9 else 50)
@@ -355,10 +357,15 @@ def main() -> int:
         for w in rows:
             default = biq.biq_plan_get(w.m, w.n, w.q, w.batch, w.mu)
             lut = biq.biq_plan_get_lut(w.m, w.n, w.q, w.batch, w.mu)
-            # the library's choice first; where that is the unpack + MFMA kernel, the lookup-table
-            # kernel on the same inputs as a second row
-            for plan in ([None, lut] if default.kernel != lut.kernel else [None]):
+            # the library's choice first; where that is the unpack + MFMA kernel (exact input
+            # split), the lookup-table kernel on the same inputs as a second row and the two-term
+            # variant of the matrix-core kernel, which only an explicit plan selects, as a third
+            plans = [None]
+            if default.kernel != lut.kernel:
+                plans += [lut, biq.biq_plan_get_mfma(w.m, w.n, w.q, w.batch, w.mu, 2)]
+            for plan in plans:
                 kname = biq.biq_kernel_name((plan or default).kernel)
+                terms = (plan or default).input_terms
                 copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
                 p = Problem(biq, torch, w, copies, real_first=False, plan=plan)
                 steps = 200 if w.lookups < 1e9 else 20
@@ -369,11 +376,15 @@ def main() -> int:
                 s["kernel"] = kname
                 s["default_plan"] = plan is None
                 if kname == "unpack_mfma":
-                    # dense contraction: 2 flop per weight and input vector, times the two fp16
-                    # terms of x, on columns padded to the 32-wide MFMA tile
+                    # dense contraction: 2 flop per weight and input vector, times the 16-bit
+                    # terms of x (3 bf16: exact; 2 fp16: on request), on columns padded to the
+                    # 32-wide MFMA tile
                     padded = -(-w.batch // 32) * 32
-                    s["mfma_TFLOPs"] = 4.0 * w.q * w.m * w.n * padded / t.median / 1e12
+                    s["input_terms"] = terms
+                    s["mfma_TFLOPs"] = 2.0 * terms * w.q * w.m * w.n * padded / t.median / 1e12
                     s["mfma_frac"] = s["mfma_TFLOPs"] / MFMA_F16_PEAK_TFLOPS
+                    if terms == 2:
+                        kname = "unpack_mfma, 2 input terms"
                 elif w.batch > 1:
                     # batched table lookups are bounded by gathers from LDS (4 bytes per lookup)
                     s["lds_gather_GBps"] = 4.0 * w.lookups / t.median / 1e9

@@ -143,7 +143,17 @@ typedef struct {
                             the upper half by negation.  Same tables up to rounding; kept selectable
                             so that the two build methods Sec. III-B weighs can be timed against each
                             other (the default, 0, is the faster one here)                       */
-    int reserved[2];
+    int input_terms;     /* unpack_mfma kernel: 16-bit terms every fp32 input is split into for the matrix
+                            cores.  3 (0 is read as 3; what the library chooses): three bf16 terms, an
+                            exact split - the result is that of an fp32 evaluation of Eq. 2 up to the
+                            order of the additions.  2: every input vector scaled by a power of two (its
+                            largest magnitude in [2^14, 2^15)) and split into two fp16 terms rounded to
+                            nearest, 22 significand bits: a third fewer matrix instructions for an input
+                            rounding of 2^-22 relative per element (2^-39 of the vector's largest
+                            magnitude where the second term is subnormal), the scaling undone on
+                            output; an input vector holding Inf or NaN gives non-finite outputs for that
+                            vector.  Only on request                                              */
+    int reserved[1];
 } biq_plan;
 
 biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan);
@@ -152,6 +162,11 @@ biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan);
  * keys into the matrix cores (the large-batch regime of Sec. IV-B where a plain GEMM on
  * unpacked weights wins). */
 biq_status biq_plan_get_lut(int m, int n, int q, int batch, int mu, biq_plan* plan);
+/* The library's mapping of the unpack_mfma kernel for a shape (q <= 4, else BIQ_EUNSUPPORTED),
+ * whichever side of the crossover the shape is on, for input_terms = 3 or 2 (see biq_plan):
+ * how a caller asks for the two-term variant, or times the matrix-core path below the
+ * crossover.  For biq_gemm_ex. */
+biq_status biq_plan_get_mfma(int m, int n, int q, int batch, int mu, int input_terms, biq_plan* plan);
 /* Validates a caller-filled plan (kernel, threads, chunks_per_tile, batch_tile,
  * tiles_per_split, rows_per_wg) against the shape and the device limits and fills in the
  * derived fields (chunk_splits, row_blocks, batch_tiles, lds_bytes). */
@@ -220,11 +235,9 @@ biq_status biq_query(const uint8_t* K, const float* alpha, const float* LUT, flo
  * For many input vectors (see biq_plan_get / biq_plan_get_lut) the default plan is the
  * unpack_mfma kernel instead: the "GEMM with unpacking" alternative of Sec. IV-B
  * (Algorithm 3), with the sign bits expanded to +-1 in registers and contracted on the
- * matrix cores against X in two fp16 terms per element (every input vector scaled by a
- * power of two so that its largest magnitude lies in [2^14, 2^15); the terms carry 22
- * significand bits, the scaling is undone on output); fp32 accumulation, same tolerance,
- * same determinism.  An input vector holding Inf or NaN gives non-finite outputs for that
- * vector.  It uses the first part of the workspace for the prepared X.
+ * matrix cores against X split exactly into three bf16 terms; fp32 accumulation, same
+ * tolerance, same determinism.  (biq_plan_get_mfma + biq_gemm_ex give the faster two-term
+ * variant, see biq_plan.input_terms.)  It uses the first part of the workspace for the split X.
  */
 biq_status biq_gemm(const uint8_t* K, const float* alpha, const float* X, float* Y,
                     int m, int n, int q, int batch, int mu,

@@ -15,7 +15,7 @@ BIQ_OK, BIQ_EINVAL, BIQ_EUNSUPPORTED, BIQ_EWORKSPACE, BIQ_EHIP = 0, -1, -2, -3, 
 
 EXPORTS = [
     "biq_status_str", "biq_version", "biq_key_row_stride", "biq_packed_bytes", "biq_num_chunks",
-    "biq_lut_bytes", "biq_workspace_bytes", "biq_plan_get", "biq_plan_get_lut", "biq_plan_check", "biq_plan_workspace_bytes",
+    "biq_lut_bytes", "biq_workspace_bytes", "biq_plan_get", "biq_plan_get_lut", "biq_plan_get_mfma", "biq_plan_check", "biq_plan_workspace_bytes",
     "biq_kernel_name", "biq_pack", "biq_unpack_keys", "biq_build_lut", "biq_query", "biq_gemm",
     "biq_gemm_ex", "biq_quantize", "biq_unpack_keys16", "biq_init", "biq_noalloc_scratch_bytes",
     "biq_gemm_noalloc", "biq_gemm_grouped", "biq_lstm_cell",
@@ -30,7 +30,7 @@ class BiqPlan(ctypes.Structure):
         ("batch_tile", ctypes.c_int), ("chunk_splits", ctypes.c_int), ("tiles_per_split", ctypes.c_int),
         ("rows_per_wg", ctypes.c_int), ("row_blocks", ctypes.c_int), ("batch_tiles", ctypes.c_int),
         ("lds_bytes", ctypes.c_int), ("row_mode", ctypes.c_int), ("xcd_skew", ctypes.c_int), ("wave_splits", ctypes.c_int), ("table_fill", ctypes.c_int),
-        ("reserved", ctypes.c_int * 2),
+        ("input_terms", ctypes.c_int), ("reserved", ctypes.c_int * 1),
     ]
 
     def as_dict(self):
@@ -76,6 +76,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "biq_workspace_bytes": (Z, [I, I, I, I, I]),
         "biq_plan_get": (I, [I, I, I, I, I, PL]),
         "biq_plan_get_lut": (I, [I, I, I, I, I, PL]),
+        "biq_plan_get_mfma": (I, [I, I, I, I, I, I, PL]),
         "biq_plan_check": (I, [I, I, I, I, I, PL]),
         "biq_plan_workspace_bytes": (Z, [PL, I, I]),
         "biq_kernel_name": (ctypes.c_char_p, [I]),
@@ -157,6 +158,13 @@ def biq_plan_get(m: int, n: int, q: int, batch: int, mu: int) -> BiqPlan:
 def biq_plan_get_lut(m: int, n: int, q: int, batch: int, mu: int) -> BiqPlan:
     plan = BiqPlan()
     _check(load_library().biq_plan_get_lut(m, n, q, batch, mu, ctypes.byref(plan)), "biq_plan_get_lut")
+    return plan
+
+
+def biq_plan_get_mfma(m: int, n: int, q: int, batch: int, mu: int, input_terms: int = 3) -> BiqPlan:
+    plan = BiqPlan()
+    _check(load_library().biq_plan_get_mfma(m, n, q, batch, mu, input_terms, ctypes.byref(plan)),
+           "biq_plan_get_mfma")
     return plan
 
 

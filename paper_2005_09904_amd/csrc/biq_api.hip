@@ -53,8 +53,8 @@ inline int rows_from(long long want, int step, int lo, int m) {
 }
 inline int ilog2(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
 
-// 16-byte pieces of prepared input per key group (16 MFMA steps): column tiles x fp16 terms x 64 lanes
-inline long long unpack_group_pieces(int batch_tile) { return 16ll * (batch_tile / 32) * kUnpackTerms * 64; }
+// 16-byte pieces of prepared input per key group (16 MFMA steps): column tiles x terms x 64 lanes
+inline long long unpack_group_pieces(int batch_tile, int terms) { return 16ll * (batch_tile / 32) * terms * 64; }
 
 // Unpack-MFMA plans: workgroups of 4 waves, key groups (32 key bytes of a row) instead of LUT tiles.
 bool plan_finish_unpack(biq_plan& pl, int m, int n, int q, int batch) {
@@ -62,6 +62,8 @@ bool plan_finish_unpack(biq_plan& pl, int m, int n, int q, int batch) {
     if (pl.batch_tile != 32 && pl.batch_tile != 64) return false;
     if (pl.chunks_per_tile != kUnpackGroupBytes) return false;
     if (pl.wave_splits == 0) pl.wave_splits = 1;
+    if (pl.input_terms == 0) pl.input_terms = 3;     // exact split unless the caller asks for two terms
+    if (pl.input_terms != 2 && pl.input_terms != 3) return false;
     const int ws = pl.wave_splits;
     if (ws != 1 && ws != 2 && ws != 4) return false;
     // (4 / ws) waves side by side x r row tiles of 32 rows per plane, at most 4 row tiles per wave
@@ -79,9 +81,9 @@ bool plan_finish_unpack(biq_plan& pl, int m, int n, int q, int batch) {
     pl.lds_bytes = ws == 1 ? 24 * 1024 : 96 * 1024;   // partial sums of the wave groups, transpose patches (UnpackGeom::LDS_BYTES)
     const long long tasks = (long long)pl.row_blocks * pl.chunk_splits * pl.batch_tiles;
     if (tasks > (1ll << 30)) return false;
-    // prepared input: 4 bytes per (padded column, padded element)
+    // prepared input: 2 bytes per term and (padded column, padded element)
     const long long xf = (long long)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split *
-                         unpack_group_pieces(pl.batch_tile) * 16;
+                         unpack_group_pieces(pl.batch_tile, pl.input_terms) * 16;
     if (xf > (1ll << 40)) return false;
     return true;
 }
@@ -107,7 +109,7 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
     const int C = ceil_div(n, mu);
     if (pl.kernel < 0 || pl.kernel >= KERNEL_COUNT) return false;
     if (pl.kernel == KERNEL_UNPACK_MFMA) return plan_finish_unpack(pl, m, n, q, batch);
-    if (pl.wave_splits != 0) return false;  // unpack_mfma only
+    if (pl.wave_splits != 0 || pl.input_terms != 0) return false;  // unpack_mfma only
     if (pl.table_fill != 0 && !(pl.table_fill == 1 && pl.kernel == KERNEL_GEMV8 && pl.row_mode == 0)) return false;
     if (pl.threads < 64 || pl.threads > 1024 || pl.threads % 64) return false;
     if (pl.kernel == KERNEL_GEMV8) {
@@ -176,8 +178,9 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
 // run times of both paths from rates measured on MI355X.  Table lookups: about 13e12 lookups/s
 // for the conflict-free kernels (mu = 8, mu <= 5, mu = 6 up to 4 input vectors); 6.5e12 for the
 // generic one, which also streams keys at no more than about 0.25 TB/s; plus 6 us of launch
-// and table build.  Unpack + MFMA: 2 * 2 flop per weight and padded input vector (two fp16
-// terms) at 1.28e15 flop/s, plus 9 us (input split, launches, combining partial sums).
+// and table build.  Unpack + MFMA with the exact split: 2 * 3 flop per weight and padded input
+// vector (three bf16 terms) at 1.45e15 flop/s, plus 9.5 us (input split, launches, combining
+// partial sums).
 bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
     const double weights = (double)q * m * n;
     const double lookups = weights / mu * batch;
@@ -186,8 +189,67 @@ bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
     if (!tuned && t_lut < weights / 8 / 0.25e12) t_lut = weights / 8 / 0.25e12;
     t_lut += 6e-6;
     const double padded = (double)((batch + 31) / 32) * 32;
-    const double t_mfma = 9e-6 + 4.0 * weights * padded / 1.28e15;
+    const double t_mfma = 9.5e-6 + 6.0 * weights * padded / 1.45e15;
     return t_mfma < t_lut;
+}
+
+// The mapping of the unpack + MFMA kernel - column tile (32 or 64 input vectors), row tiles per
+// wave and plane (r), wave groups along the contraction inside a workgroup (ws; partial sums
+// added in LDS) and workgroups along the contraction (S; partial sums through the workspace and
+// a second kernel) - is the candidate with the lowest estimated time.  The estimate: MFMAs per
+// wave x 33 clk at 2.1 GHz (measured rate of back-to-back MFMAs under load) x an issue-overhead
+// factor per accumulator shape (smallest for 4 x 2 tiles, more for fewer, where key expansion
+// and fragment loads are shared by fewer MFMAs) x rounds of workgroups over the 256 CUs, plus
+// fixed costs per launch, accumulator tile and round, the input split (per byte of padded X)
+// and the second kernel.  The constants (one set per number of input terms) are least-squares
+// fits to sweeps of 16 layer shapes x all valid mappings, on which the estimate's choice was the
+// fastest or within 5 % of it.
+struct UnpackCost {
+    double shape8, shape6, shape4x1, shape3x1, shape2x2, shape2x1, shape1x2, shape1x1;
+    double fix, per_tile, per_round, split_per_mb, second_kernel, second_per_mb, per_wave_group;
+};
+const UnpackCost kUnpackCost3 = {1.13, 1.16, 1.19, 1.22, 1.22, 1.30, 1.45, 1.65, 9.0, 0.25, 0.0, 0.0, 3.5, 0.4, 0.6};
+const UnpackCost kUnpackCost2 = {1.20, 1.20, 1.36, 1.29, 1.42, 1.67, 2.10, 2.27, 5.3, 1.0, 1.1, 1.65, 2.45, 0.1, 0.0};
+
+bool plan_unpack(biq_plan& pl, int m, int n, int q, int batch, int mu, int terms) {
+    if (q > 4 || (terms != 2 && terms != 3)) return false;
+    const UnpackCost& c = terms == 3 ? kUnpackCost3 : kUnpackCost2;
+    pl = biq_plan{};
+    pl.kernel = KERNEL_UNPACK_MFMA;
+    pl.threads = kUnpackThreads;
+    pl.chunks_per_tile = kUnpackGroupBytes;
+    pl.input_terms = terms;
+    const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
+    double best = 1e30;
+    for (int bt = 32; bt <= 64; bt += 32)
+        for (int ws = 1; ws <= 4; ws *= 2)
+            for (int r = 1; r <= 4; r *= 2)
+                for (int S = 1; S <= 16; S *= 2) {
+                    const int ct = bt / 32, rt = q * r;
+                    if (rt > 4 || S * ws > groups) continue;
+                    if (ws == 4 && rt * ct == 8) continue;   // would not fit the register file
+                    const int rows = (4 / ws) * 32 * r;
+                    const long long wgs = (long long)ceil_div(m, rows) * ceil_div(batch, bt) * S;
+                    if (wgs > 4ll * kNumCu && S > 1) continue;
+                    const int gpw = ceil_div(ceil_div(groups, S), ws);   // key groups per wave
+                    const double shape = rt * ct == 8 ? c.shape8 : rt * ct == 6 ? c.shape6 : rt == 4 ? c.shape4x1
+                                       : rt == 3 ? c.shape3x1 : (rt == 2 && ct == 2) ? c.shape2x2
+                                       : rt == 2 ? c.shape2x1 : ct == 2 ? c.shape1x2 : c.shape1x1;
+                    const double rounds = (double)ceil_div_ll(wgs, kNumCu);
+                    const double bpad_mb = (double)ceil_div(batch, bt) * bt * 4 / 1e6;   // MB per element of a vector
+                    double t = (double)terms * rt * ct * gpw * 16 * 33 * shape / 2100.0 * rounds;
+                    t += c.fix + c.per_tile * rt * ct * rounds + c.per_round * (rounds - 1.0) + c.split_per_mb * bpad_mb * n;
+                    if (S > 1) t += c.second_kernel + c.second_per_mb * (S + 1.0) * bpad_mb * m;
+                    if (ws > 1) t += c.per_wave_group * (ws - 1) * rt * ct / 4;
+                    if (t < best) {
+                        best = t;
+                        pl.batch_tile = bt;
+                        pl.wave_splits = ws;
+                        pl.rows_per_wg = rows;
+                        pl.tiles_per_split = ceil_div(groups, S);
+                    }
+                }
+    return plan_finish(pl, m, n, q, batch, mu);
 }
 
 // Default mapping.  Algorithm 2 leaves the tile sizes open; the choices here are:
@@ -205,51 +267,8 @@ bool plan_tuned(biq_plan& pl, int m, int n, int q, int batch, int mu, bool table
     pl = biq_plan{};
     if (!tables_given && q <= 4 && unpack_mfma_is_faster(m, n, q, batch, mu)) {
         // Many input vectors: the contraction is compute bound and the matrix cores beat the
-        // table lookups (the crossover of Sec. IV-B / Fig. 10).  The mapping - column tile (32 or
-        // 64 input vectors), row tiles per wave and plane (r), wave groups along the contraction
-        // inside a workgroup (ws; partial sums added in LDS) and workgroups along the contraction
-        // (S; partial sums through the workspace and a second kernel) - is the candidate with the
-        // lowest estimated time.  The estimate: MFMAs per wave x 33 clk at 2.1 GHz (measured rate
-        // of back-to-back MFMAs under load) x an issue-overhead factor per accumulator shape
-        // (1.2 for 4 x 2 tiles, more for fewer, where key expansion and fragment loads are shared
-        // by fewer MFMAs) x rounds of workgroups over the 256 CUs, plus fixed costs per launch,
-        // accumulator tile and round, the input split (per byte of padded X) and the second
-        // kernel; the constants are a least-squares fit to a sweep of 16 layer shapes x all valid
-        // mappings (443 timed plans), on which the estimate's choice was the fastest or within
-        // 5 % of it (mean loss 0.6 %).
-        pl.kernel = KERNEL_UNPACK_MFMA;
-        pl.threads = kUnpackThreads;
-        pl.chunks_per_tile = kUnpackGroupBytes;
-        const int groups = (int)((biq_key_row_stride(n) + kUnpackGroupBytes - 1) / kUnpackGroupBytes);
-        double best = 1e30;
-        for (int bt = 32; bt <= 64; bt += 32)
-            for (int ws = 1; ws <= 4; ws *= 2)
-                for (int r = 1; r <= 4; r *= 2)
-                    for (int S = 1; S <= 16; S *= 2) {
-                        const int ct = bt / 32, rt = q * r;
-                        if (rt > 4 || S * ws > groups) continue;
-                        if (ws == 4 && rt * ct == 8) continue;   // would not fit the register file
-                        const int rows = (4 / ws) * 32 * r;
-                        const long long wgs = (long long)ceil_div(m, rows) * ceil_div(batch, bt) * S;
-                        if (wgs > 4ll * kNumCu && S > 1) continue;
-                        const int gpw = ceil_div(ceil_div(groups, S), ws);   // key groups per wave
-                        const double shape = rt * ct >= 6 ? 1.20 : rt == 4 ? 1.36 : rt == 3 ? 1.29
-                                           : (rt == 2 && ct == 2) ? 1.42 : rt == 2 ? 1.67
-                                           : ct == 2 ? 2.10 : 2.27;
-                        const double rounds = (double)ceil_div_ll(wgs, kNumCu);
-                        const double bpad = (double)ceil_div(batch, bt) * bt;
-                        double t = kUnpackTerms * rt * ct * gpw * 16 * 33 * shape / 2100.0 * rounds;
-                        t += 5.3 + 1.0 * rt * ct * rounds + 1.1 * (rounds - 1.0) + 1.65 * bpad * n * 4 / 1e6;
-                        if (S > 1) t += 2.45 + (S + 1.0) * bpad * (double)m * 4 / 10e6;
-                        if (t < best) {
-                            best = t;
-                            pl.batch_tile = bt;
-                            pl.wave_splits = ws;
-                            pl.rows_per_wg = rows;
-                            pl.tiles_per_split = ceil_div(groups, S);
-                        }
-                    }
-        return plan_finish(pl, m, n, q, batch, mu);
+        // table lookups (the crossover of Sec. IV-B / Fig. 10); exact input split.
+        return plan_unpack(pl, m, n, q, batch, mu, 3);
     }
     if (mu == 8 && batch == 1 && q <= 4) {
         // GEMV: workgroups of 1024 threads, 128-chunk tiles, one workgroup per CU when the
@@ -434,15 +453,15 @@ bool plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
 }
 
 // Bytes of the prepared-input area at the start of the workspace (unpack-MFMA plans only): the
-// B fragments, then one scaling exponent per padded input vector.
+// B fragments, then (two terms) one scaling exponent per padded input vector.
 size_t plan_xfrag_bytes(const biq_plan& pl) {
     const size_t b = (size_t)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split *
-                     (size_t)unpack_group_pieces(pl.batch_tile) * 16;
+                     (size_t)unpack_group_pieces(pl.batch_tile, pl.input_terms) * 16;
     return (b + 255) & ~(size_t)255;
 }
 size_t plan_xf_bytes(const biq_plan& pl) {
     if (pl.kernel != KERNEL_UNPACK_MFMA) return 0;
-    const size_t e = (size_t)pl.batch_tiles * pl.batch_tile * sizeof(int);
+    const size_t e = pl.input_terms == 2 ? (size_t)pl.batch_tiles * pl.batch_tile * sizeof(int) : 0;
     return plan_xfrag_bytes(pl) + ((e + 255) & ~(size_t)255);
 }
 
@@ -514,8 +533,8 @@ bool plan_grouped(biq_plan& pl, int& kind, int m, int n, int q, int batch, int m
     return plan_finish(pl, m, n, q, batch, mu) && pl.chunk_splits == 1;
 }
 
-// Large-batch path: scale and split X into fp16 terms in MFMA operand order (workspace),
-// contract, and sum the partial results when the key groups were split over workgroups.
+// Large-batch path: split X into 16-bit terms in MFMA operand order (workspace), contract, and
+// sum the partial results when the key groups were split over workgroups.
 biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* alpha, const float* X,
                            float* Y, int m, int n, int q, int batch, void* workspace, hipStream_t s) {
     const int CT = pl.batch_tile / 32;
@@ -525,7 +544,8 @@ biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* al
     int* colexp = reinterpret_cast<int*>(reinterpret_cast<char*>(workspace) + plan_xfrag_bytes(pl));
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + plan_xf_bytes(pl));
 
-    if (launch_xsplit(CT, X, Xf, colexp, n, batch, steps, pl.batch_tiles * pl.batch_tile, s) != hipSuccess)
+    if (launch_xsplit(pl.input_terms, CT, X, Xf, colexp, n, batch, steps, pl.batch_tiles * pl.batch_tile, s) !=
+        hipSuccess)
         return BIQ_EHIP;
 
     UnpackParams up{};
@@ -546,7 +566,7 @@ biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* al
     up.tasks_per_xcd = ceil_div(up.ntasks, kNumXcd);
     const int grid = up.tasks_per_xcd * kNumXcd;
     const int rpw = pl.rows_per_wg / ((4 / pl.wave_splits) * 32);
-    const hipError_t e = launch_unpack(q, rpw, CT, pl.wave_splits, up, grid, pl.lds_bytes, s);
+    const hipError_t e = launch_unpack(pl.input_terms, q, rpw, CT, pl.wave_splits, up, grid, pl.lds_bytes, s);
     if (e != hipSuccess) return BIQ_EHIP;
     if (pl.chunk_splits > 1) {
         const long long count = (long long)batch * m;
@@ -688,6 +708,13 @@ biq_status biq_plan_get(int m, int n, int q, int batch, int mu, biq_plan* plan) 
 biq_status biq_plan_get_lut(int m, int n, int q, int batch, int mu, biq_plan* plan) {
     if (!plan || !shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
     return plan_default(*plan, m, n, q, batch, mu, true) ? BIQ_OK : BIQ_EUNSUPPORTED;
+}
+
+biq_status biq_plan_get_mfma(int m, int n, int q, int batch, int mu, int input_terms, biq_plan* plan) {
+    if (!plan || !shape_ok(m, n, q, batch, mu)) return BIQ_EINVAL;
+    if (input_terms != 2 && input_terms != 3) return BIQ_EINVAL;
+    if (q > 4) return BIQ_EUNSUPPORTED;
+    return plan_unpack(*plan, m, n, q, batch, mu, input_terms) ? BIQ_OK : BIQ_EUNSUPPORTED;
 }
 
 biq_status biq_plan_check(int m, int n, int q, int batch, int mu, biq_plan* plan) {

@@ -64,9 +64,11 @@ struct GroupParams;
 hipError_t launch_grouped(int kind, int q, const GroupParams& g, int grid, int lds, hipStream_t s);
 
 // ---- unpack + MFMA path ----
-hipError_t launch_xsplit(int ct, const float* X, mfma_u32x4* Xf, int* colexp, int n, int batch, int steps,
-                         int padded_batch, hipStream_t s);
-hipError_t launch_unpack(int q, int rpw, int ct, int ws, const UnpackParams& up, int grid, int lds, hipStream_t s);
+// (terms: 3 = exact split into bf16 terms, 2 = two scaled fp16 terms)
+hipError_t launch_xsplit(int terms, int ct, const float* X, mfma_u32x4* Xf, int* colexp, int n, int batch,
+                         int steps, int padded_batch, hipStream_t s);
+hipError_t launch_unpack(int terms, int q, int rpw, int ct, int ws, const UnpackParams& up, int grid, int lds,
+                         hipStream_t s);
 
 // ---- the small kernels ----
 // Y[i] = sum over the `splits` partial results [splits][count], in a fixed order.

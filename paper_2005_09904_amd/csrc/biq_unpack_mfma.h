@@ -3,33 +3,35 @@
 // For many input vectors the product is compute bound and the lookup tables stop paying off
 // (the crossover discussed with Fig. 10); the alternative the paper measures is to unpack the
 // sign bits and run an ordinary GEMM.  Here the unpacking happens in registers, straight into
-// the A operand of v_mfma_f32_32x32x16_f16, and nothing unpacked ever reaches memory:
-//   - a weight bit becomes the fp16 value +1.0 / -1.0 (bit set <-> +1, as in Algorithm 3; the
+// the A operand of a 32x32x16 MFMA, and nothing unpacked ever reaches memory:
+//   - a weight bit becomes the 16-bit float +1.0 / -1.0 (bit set <-> +1, as in Algorithm 3; the
 //     kernel forms the negated value, whose sign bit is the key bit, and negates alpha);
-//   - every input vector is scaled by a power of two 2^e (e per vector, from its largest
-//     magnitude, which lands in [2^14, 2^15)) and every scaled fp32 element is split once into
-//     two fp16 terms, x * 2^e = x0 + x1 + r with x0 = fp16(x * 2^e), x1 = fp16(x * 2^e - x0), both
-//     rounded to nearest: |r| <= 2^-22 |x * 2^e| (or 2^-25 absolutely, i.e. 2^-39 of the vector's
-//     largest magnitude, where x1 is subnormal).  +-1 * fp16 products are exact and the matrix
-//     cores accumulate in fp32; the epilogue multiplies by 2^-e.  The result thus differs from a
-//     plain fp32 evaluation of Eq. 2 by the order of the additions and by that input rounding,
-//     a quarter of fp32's own unit in the last place per element - below the rounding of the
-//     fp32 additions themselves, and 40 times inside the 1e-5 relative L2 bound in the worst case;
-//   - the two terms are two B operands multiplied with the same A operand: 2 MFMAs per 16
-//     weights x 32 input vectors, against 3 for an exact split into bf16 terms.
+//   - the fp32 inputs are split once into T terms of 16-bit floats, which are T B operands
+//     multiplied with the same A operand; +-1 * term products are exact and the matrix cores
+//     accumulate in fp32.
+// T = 3, the default: x = x0 + x1 + x2 with three bf16 terms (8 significand bits each, taken by
+//     truncation, so the sum is exact).  The result differs from a plain fp32 evaluation of
+//     Eq. 2 only by the order of the additions.
+// T = 2, on request (plan.input_terms = 2): every input vector is scaled by a power of two 2^e
+//     (e per vector, from its largest magnitude, which lands in [2^14, 2^15)) and every scaled
+//     element is split into two fp16 terms, x * 2^e = x0 + x1 + r with x0 = fp16(x * 2^e),
+//     x1 = fp16(x * 2^e - x0), both rounded to nearest: |r| <= 2^-22 |x * 2^e| (or 2^-25
+//     absolutely, i.e. 2^-39 of the vector's largest magnitude, where x1 is subnormal); the
+//     epilogue multiplies by 2^-e.  A third fewer MFMAs for an input rounding of a quarter of
+//     fp32's unit in the last place per element.
 // The kernel does not depend on mu: it reads the packed bitmap, which is the same for all mu.
 //
 // MFMA operand layout (32x32x16, wave of 64 lanes, lane = 32*h + r):
 //   A: lane holds row r of the tile, 8 consecutive k of half h     -> one key byte per lane
-//   B: lane holds column r, the same 8 k of half h                 -> 8 fp16 of one input vector
+//   B: lane holds column r, the same 8 k of half h                 -> 8 terms of one input vector
 //   C: lane holds column r, rows 8*(v/4) + 4*h + v%4 for v = 0..15
 // A lane loads 16 key bytes of its row at once: half 0 takes bytes [32g, 32g+16) of the row,
 // half 1 bytes [32g+16, 32g+32) ("key group" g).  Each of the lane's four key dwords feeds four
 // MFMA steps (see unpack_step for which bits go to which step): the k order of the contraction
 // is a permutation of the columns, which the B side follows.
 //
-// B operands are prepared by xsplit_kernel in exactly the order the main kernel consumes them:
-//   Xf[col_group][step][col_tile][term 0..1][lane] : 16 bytes (8 fp16)
+// B operands are prepared by xsplit3_kernel / xsplit2_kernel in exactly the order the main kernel consumes them:
+//   Xf[col_group][step][col_tile][term 0..T-1][lane] : 16 bytes (8 terms)
 // (step = MFMA step along the row, 16 per key group), so a wave's load of a fragment is one
 // contiguous KiB; the waves load their fragments straight into registers, a few steps ahead.
 #pragma once
@@ -40,12 +42,30 @@
 namespace biq {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t mfma_u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kUnpackThreads = 256;     // 4 waves
 constexpr int kUnpackGroupBytes = 32;   // key bytes of a row per key group (both halves)
-constexpr int kUnpackTerms = 2;         // fp16 terms per input element
+
+// What depends on the number of terms T: the MFMA operand type, two of its 1.0 in a dword, and
+// the instruction.
+template <int T> struct UnpackOperand;
+template <> struct UnpackOperand<3> {
+    typedef bf16x8 vec;
+    static constexpr uint32_t kOne2 = 0x3f803f80u;
+    static __device__ __forceinline__ f32x16 mfma(vec a, vec b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct UnpackOperand<2> {
+    typedef f16x8 vec;
+    static constexpr uint32_t kOne2 = 0x3c003c00u;
+    static __device__ __forceinline__ f32x16 mfma(vec a, vec b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+};
 
 // Time stamps of a trace build (-DBIQ_TRACE, never the product's): lane 0 of wave 0 of every
 // workgroup writes the 100 MHz wall clock into slot i of its entry.
@@ -66,7 +86,7 @@ struct UnpackParams {
     const uint8_t* K;        // [q][m][stride]
     const float* alpha;      // [q][m]
     const mfma_u32x4* Xf;    // prepared B operands (see above)
-    const int* colexp;       // e of every (padded) input vector: its B operands hold x * 2^e
+    const int* colexp;       // two terms: e of every (padded) input vector, its B operands hold x * 2^e
     float* out;              // Y [batch][m], or partials [splits][batch][m]
     int m, batch;
     uint32_t stride_bytes;
@@ -77,6 +97,17 @@ struct UnpackParams {
     int ntasks, tasks_per_xcd;
 };
 
+// Splits fp32 into three bf16 terms by truncation; returns them as the high halves' bit patterns.
+__device__ __forceinline__ void split3(float x, uint32_t& t0, uint32_t& t1, uint32_t& t2) {
+    const uint32_t b0 = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(b0);       // exact: the low 16 significand bits
+    const uint32_t b1 = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(b1);      // exact: at most 8 significand bits left
+    t0 = b0 >> 16;
+    t1 = b1 >> 16;
+    t2 = __float_as_uint(r2) >> 16;                 // exact in bf16
+}
+
 // Splits a scaled fp32 value into two fp16 terms, each rounded to nearest; the difference taken
 // in between is exact in fp32.  Returns the bit patterns.
 __device__ __forceinline__ void split2(float xs, uint32_t& t0, uint32_t& t1) {
@@ -86,19 +117,72 @@ __device__ __forceinline__ void split2(float xs, uint32_t& t0, uint32_t& t1) {
     t1 = __builtin_bit_cast(unsigned short, lo);
 }
 
-// Input vectors -> B fragments, one workgroup per (padded) input vector: largest magnitude -> e,
-// then the vector's fragments (two 16-byte pieces per MFMA step and half-wave, see the layout
-// above).  Vectors past the batch and elements past n are zero.  A vector that holds Inf or NaN
-// is left unscaled (e = 0) and gives non-finite results, as it would in any evaluation of Eq. 2.
-// A thread reads the 8 elements of its fragments once and keeps them in registers across the
-// reduction (kXsplitCached fragments per thread: n <= 32768; what is beyond is read twice).
+// Exact split: one thread per (col_group, step, col_tile, lane) writes the three 16-byte B
+// fragments of that lane (coalesced: a wave writes whole KiB).  Columns past the batch and
+// elements past n are zero.
+template <int CT>
+__global__ __launch_bounds__(256) void xsplit3_kernel(const float* __restrict__ X,
+                                                      mfma_u32x4* __restrict__ Xf, int n, int batch,
+                                                      int steps, long long total) {
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int lane = (int)(idx & 63);
+    long long rest = idx >> 6;
+    const int ct = (int)(rest % CT); rest /= CT;
+    const int step = (int)(rest % steps);   // MFMA step along the row: 16 per key group
+    const int cg = (int)(rest / steps);
+    const int col = (cg * CT + ct) * 32 + (lane & 31);
+    const int h = lane >> 5;
+    const int ks = step & 3;
+    // dword of the row this step works on, and its 2 x 4 consecutive elements (see unpack_step)
+    const long long dw = 8ll * (step >> 4) + 4 * h + ((step >> 2) & 3);
+    const long long j0 = 32 * dw + 8 * (ks >> 1) + 4 * (ks & 1);   // elements j0..j0+3 and j0+16..j0+19
+    float lo[4], hi[4];
+    if (col < batch && j0 + 20 <= n && (n & 3) == 0 && ((reinterpret_cast<uintptr_t>(X) & 15) == 0)) {
+        const float* src = X + (size_t)col * n + j0;
+        const float4 a = *reinterpret_cast<const float4*>(src);
+        const float4 b = *reinterpret_cast<const float4*>(src + 16);
+        lo[0] = a.x; lo[1] = a.y; lo[2] = a.z; lo[3] = a.w;
+        hi[0] = b.x; hi[1] = b.y; hi[2] = b.z; hi[3] = b.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            lo[i] = (col < batch && j0 + i < n) ? X[(size_t)col * n + j0 + i] : 0.0f;
+            hi[i] = (col < batch && j0 + 16 + i < n) ? X[(size_t)col * n + j0 + 16 + i] : 0.0f;
+        }
+    }
+    uint32_t t[3][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        split3(lo[i], t[0][2 * i], t[1][2 * i], t[2][2 * i]);
+        split3(hi[i], t[0][2 * i + 1], t[1][2 * i + 1], t[2][2 * i + 1]);
+    }
+    mfma_u32x4* dst = Xf + (idx >> 6) * (3 * 64) + lane;
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        mfma_u32x4 v;
+        v.x = t[s][0] | (t[s][1] << 16);
+        v.y = t[s][2] | (t[s][3] << 16);
+        v.z = t[s][4] | (t[s][5] << 16);
+        v.w = t[s][6] | (t[s][7] << 16);
+        dst[s * 64] = v;
+    }
+}
+
+// Two scaled terms: input vectors -> B fragments (two 16-byte pieces per MFMA step and
+// half-wave, see the layout above), one workgroup per (padded) input vector: largest magnitude
+// -> e, then the fragments.  Vectors past the batch and elements past n are zero.  A vector
+// that holds Inf or NaN is left unscaled (e = 0) and gives non-finite results, as it would in
+// any evaluation of Eq. 2.  A thread reads the 8 elements of its fragments once and keeps them
+// in registers across the reduction (kXsplitCached fragments per thread: n <= 32768; what is
+// beyond is read twice).
 // (Measured and dropped: several workgroups per vector, each reading the whole vector for the
 // maximum and writing a share of the fragments - slower from n = 4096 to 16384.)
 constexpr int kXsplitThreads = 1024;
 constexpr int kXsplitCached = 4;
 
 template <int CT>
-__global__ __launch_bounds__(kXsplitThreads) void xsplit_kernel(const float* __restrict__ X,
+__global__ __launch_bounds__(kXsplitThreads) void xsplit2_kernel(const float* __restrict__ X,
                                                                 mfma_u32x4* __restrict__ Xf,
                                                                 int* __restrict__ colexp, int n, int batch,
                                                                 int padded_batch, int steps) {
@@ -139,12 +223,12 @@ __global__ __launch_bounds__(kXsplitThreads) void xsplit_kernel(const float* __r
     auto store_fragment = [&](int f, const float (&x)[8], int e) {
         const int ks = f & 3, d = (f >> 2) & 3, h = (f >> 4) & 1, g = f >> 5;
         const int step = g * 16 + d * 4 + ks;  // MFMA step along the row: 16 per key group
-        uint32_t t[kUnpackTerms][8];
+        uint32_t t[2][8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) split2(ldexpf(x[i], e), t[0][i], t[1][i]);
-        mfma_u32x4* dst = Xf + (((size_t)cg * steps + step) * CT + ct) * (kUnpackTerms * 64) + 32 * h + lr;
+        mfma_u32x4* dst = Xf + (((size_t)cg * steps + step) * CT + ct) * (2 * 64) + 32 * h + lr;
 #pragma unroll
-        for (int s = 0; s < kUnpackTerms; ++s) {
+        for (int s = 0; s < 2; ++s) {
             mfma_u32x4 v;
             v.x = t[s][0] | (t[s][1] << 16);
             v.y = t[s][2] | (t[s][3] << 16);
@@ -198,13 +282,13 @@ __global__ __launch_bounds__(kXsplitThreads) void xsplit_kernel(const float* __r
     }
 }
 
-// MFMA step S (0..3) of key dword w -> the lane's 8 fp16 A elements, with the OPPOSITE sign:
+// MFMA step S (0..3) of key dword w -> the lane's 8 A elements (bf16 or fp16), with the OPPOSITE sign:
 // -1.0 where the bit is set, +1.0 otherwise (the sign bit is the key bit; the epilogue multiplies
 // by -alpha).  Element e = 2*i + hh is bit 8*(S/2) + 4*(S%2) + i + 16*hh of the dword: bits p
 // and p + 16 land in the sign positions 15 and 31 of one dword with a single shift.  `one2`
-// holds two fp16 1.0 (0x3c003c00) in a VGPR so that mask-and-merge is one v_and_or_b32.
-template <int S>
-__device__ __forceinline__ f16x8 unpack_step(uint32_t w, uint32_t one2) {
+// holds two 1.0 of the operand type in a VGPR so that mask-and-merge is one v_and_or_b32.
+template <int S, typename V>
+__device__ __forceinline__ V unpack_step(uint32_t w, uint32_t one2) {
     mfma_u32x4 d;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -212,27 +296,28 @@ __device__ __forceinline__ f16x8 unpack_step(uint32_t w, uint32_t one2) {
         const uint32_t a = p <= 15 ? (w << (15 - p)) : (w >> (p - 15));
         d[i] = (a & 0x80008000u) | one2;
     }
-    return __builtin_bit_cast(f16x8, d);
+    return __builtin_bit_cast(V, d);
 }
 
 // A workgroup's four waves form WS groups along the contraction ("wave splits"): group kg works
 // on its own contiguous part of the workgroup's key groups, with 4 / WS waves side by side along
 // the rows, and the WS partial accumulators are added through LDS in a fixed order at the end.
 // LDS holds only those partial sums and the epilogue's transpose patches.
-template <int CT, int WS>
+template <int CT, int WS, int T>
 struct UnpackGeom {
-    static constexpr int SPIECES = CT * kUnpackTerms * 64;                  // 16-byte pieces of B per MFMA step
+    static constexpr int SPIECES = CT * T * 64;                  // 16-byte pieces of B per MFMA step
     static constexpr int LDS_BYTES = (WS == 1 ? 24 : 96) * 1024;
 };
 
-template <int Q, int RPW, int CT, int WS>
+template <int Q, int RPW, int CT, int WS, int T>
 __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const UnpackParams p) {
-    using G = UnpackGeom<CT, WS>;
+    using G = UnpackGeom<CT, WS, T>;
+    using Op = UnpackOperand<T>;
+    using opvec = typename Op::vec;
     constexpr int RT = Q * RPW;                       // row tiles (32 key rows each) per wave
     constexpr int WROWS = 4 / WS;                     // waves side by side along the rows
     constexpr int SPIECES = G::SPIECES;
-    constexpr int T = kUnpackTerms;
-    constexpr int VPM = (8 + CT * T - 1) / (CT * T);  // expansion instructions to place per MFMA
+    constexpr int VPM = T == 3 ? 2 : (8 + CT * T - 1) / (CT * T);  // expansion instructions to place per MFMA
     static_assert((WS - 1) * WROWS * RT * CT * 4096 <= G::LDS_BYTES, "partial sums must fit");
     extern __shared__ __align__(16) mfma_u32x4 stage_buf[];  // partial sums, transpose patches
 
@@ -287,14 +372,14 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][c][v] = 0.0f;
 
-    uint32_t one2 = 0x3c003c00u;        // two fp16 1.0, kept in a VGPR (see unpack_step)
+    uint32_t one2 = Op::kOne2;          // two 1.0 of the operand type, kept in a VGPR (see unpack_step)
     asm volatile("" : "+v"(one2));
     BIQ_USTAMP(0);
 
     // ---- main loop: no LDS, no barrier.  The B fragments lie in Xf in the order of use, 16 bytes
     // per lane: a wave loads them straight into registers (1 KiB per request, the four waves of a
     // workgroup hit the same lines in the vector cache), three MFMA steps ahead in a ring of four.
-    // While the RT * CT * 2 MFMAs of a step issue, the next step's A operands are expanded from
+    // While the RT * CT * T MFMAs of a step issue, the next step's A operands are expanded from
     // the key bits and the fragments of the step three ahead are requested; the
     // sched_group_barrier sequence spells that interleaving out (left alone, the compiler puts a
     // step's expansion right in front of its MFMAs and the matrix pipe idles through it).
@@ -302,26 +387,26 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     const int nsteps = ngroups * 16;
     if (ngroups > 0) {
         const mfma_u32x4* xw = p.Xf + ((size_t)cg * steps_total + (size_t)ga * 16) * SPIECES + lane;
-        auto load_b = [&](int s, f16x8 (&b)[CT][T]) {
+        auto load_b = [&](int s, opvec (&b)[CT][T]) {
             const int sc = min(s, nsteps - 1);         // past the end: the last step again, unused
             const mfma_u32x4* src = xw + (size_t)sc * SPIECES;
 #pragma unroll
             for (int c = 0; c < CT; ++c)
 #pragma unroll
-                for (int tm = 0; tm < T; ++tm) b[c][tm] = __builtin_bit_cast(f16x8, src[(c * T + tm) * 64]);
+                for (int tm = 0; tm < T; ++tm) b[c][tm] = __builtin_bit_cast(opvec, src[(c * T + tm) * 64]);
         };
-        auto expand_a = [&](const mfma_u32x4 (&k)[RT], int step, f16x8 (&a)[RT]) {
+        auto expand_a = [&](const mfma_u32x4 (&k)[RT], int step, opvec (&a)[RT]) {
             const int d = step >> 2, ks = step & 3;    // step 0..15 within the key group
 #pragma unroll
             for (int t = 0; t < RT; ++t) {
                 const uint32_t w = k[t][d];
-                a[t] = ks == 0 ? unpack_step<0>(w, one2) : ks == 1 ? unpack_step<1>(w, one2)
-                     : ks == 2 ? unpack_step<2>(w, one2) : unpack_step<3>(w, one2);
+                a[t] = ks == 0 ? unpack_step<0, opvec>(w, one2) : ks == 1 ? unpack_step<1, opvec>(w, one2)
+                     : ks == 2 ? unpack_step<2, opvec>(w, one2) : unpack_step<3, opvec>(w, one2);
             }
         };
         mfma_u32x4 key[RT], keyn[RT];
-        f16x8 bfr[4][CT][T];
-        f16x8 af[2][RT];
+        opvec bfr[4][CT][T];
+        opvec af[2][RT];
         load_keys(ga, key);
         load_b(0, bfr[0]);
         load_b(1, bfr[1]);
@@ -344,8 +429,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                     for (int t = 0; t < RT; ++t)
 #pragma unroll
                         for (int c = 0; c < CT; ++c)
-                            acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[st & 1][t], bfr[st & 3][c][tm],
-                                                                                acc[t][c], 0, 0, 0);
+                            acc[t][c] = Op::mfma(af[st & 1][t], bfr[st & 3][c][tm], acc[t][c]);
 #pragma unroll
                 for (int i = 0; i < RT * CT * T; ++i) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
@@ -396,7 +480,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     }
 
     // ---- epilogue: scale by -alpha (the weights were unpacked with the opposite sign), add the
-    // planes (Eq. 2), undo the input vector's scaling, store.  An accumulator tile has one input vector per lane and its 32 rows
+    // planes (Eq. 2), undo the input vector's scaling (two terms), store.  An accumulator tile has one input vector per lane and its 32 rows
     // spread over 4 registers x 2 half-waves; stored like that, every 128-byte line of Y[b][m]
     // would be written by 8 separate instructions.  Each tile therefore goes through a 32 x 36
     // float patch of LDS (private to the wave) and leaves as 128 contiguous bytes per 8 lanes.
@@ -427,7 +511,8 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
         }
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
-            const int xe = -p.colexp[(cg * CT + c) * 32 + lr];   // the lane's input vector was scaled by 2^-xe
+            int xe = 0;                                            // two terms: the lane's input vector was scaled by 2^-xe
+            if constexpr (T == 2) xe = -p.colexp[(cg * CT + c) * 32 + lr];
             // tile -> patch[column lr][row]
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
@@ -437,7 +522,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                     float v = 0.0f;
 #pragma unroll
                     for (int i = 0; i < Q; ++i) v = fmaf(al[vq][i][e], acc[i * RPW + rp][c][4 * vq + e], v);
-                    y[e] = ldexpf(v, xe);
+                    y[e] = T == 2 ? ldexpf(v, xe) : v;
                 }
                 *reinterpret_cast<float4*>(patch + lr * TP + 8 * vq + 4 * h) = make_float4(y[0], y[1], y[2], y[3]);
             }

@@ -84,15 +84,15 @@ def test_default_plans_are_consistent(biq, mu):
         partial = p.chunk_splits * b * m * 4 if p.chunk_splits > 1 else 0
         if name == "unpack_mfma":
             # large batch: key groups of 32 bytes per row instead of LUT tiles, prepared input
-            # (two fp16 terms per element, padded to whole tiles, then one scaling exponent per padded
-            # input vector) at the start of the workspace
+            # (three bf16 terms per element - the exact split is the library's choice -, padded to
+            # whole tiles) at the start of the workspace
             assert p.threads == 256 and p.batch_tile in (32, 64)
             tiles = -(-biq.biq_key_row_stride(n) // p.chunks_per_tile)
-            pieces = 16 * (p.batch_tile // 32) * 2 * 64  # per key group: 16 MFMA steps
+            assert p.input_terms == 3
+            pieces = 16 * (p.batch_tile // 32) * 3 * 64  # per key group: 16 MFMA steps
             xf = p.batch_tiles * p.chunk_splits * p.tiles_per_split * pieces * 16
             xf = (xf + 255) // 256 * 256
-            assert xf >= 4 * b * n
-            xf += (p.batch_tiles * p.batch_tile * 4 + 255) // 256 * 256
+            assert xf >= 6 * b * n
             assert biq.biq_plan_workspace_bytes(p, m, b) == xf + partial
             assert biq.biq_workspace_bytes(m, n, q, b, mu) >= xf + partial
         else:
@@ -111,6 +111,40 @@ def test_default_plans_are_consistent(biq, mu):
         assert p.batch_tiles * p.batch_tile >= b
         assert 0 < p.lds_bytes <= 160 * 1024
         assert biq.biq_kernel_name(p.kernel) != "unknown"
+
+
+def test_mfma_plans_for_both_input_splits(biq):
+    """biq_plan_get_mfma: the matrix-core mapping on either side of the crossover, with the exact
+    three-term split or, on request only, the two-term one; workspace = prepared input (2 bytes
+    per term and padded element, plus one exponent per padded vector for two terms) + partials."""
+    for (m, n, q, b) in [(64, 128, 1, 1), (4096, 4096, 3, 32), (16384, 4096, 2, 128), (300, 1000, 4, 70)]:
+        for terms in (3, 2):
+            p = biq.biq_plan_get_mfma(m, n, q, b, 8, terms)
+            assert biq.biq_kernel_name(p.kernel) == "unpack_mfma" and p.input_terms == terms
+            groups = -(-biq.biq_key_row_stride(n) // 32)
+            assert p.chunk_splits * p.tiles_per_split >= groups
+            xf = p.batch_tiles * p.chunk_splits * p.tiles_per_split * 16 * (p.batch_tile // 32) * terms * 64 * 16
+            xf = (xf + 255) // 256 * 256
+            if terms == 2:
+                xf += (p.batch_tiles * p.batch_tile * 4 + 255) // 256 * 256
+            partial = p.chunk_splits * b * m * 4 if p.chunk_splits > 1 else 0
+            assert biq.biq_plan_workspace_bytes(p, m, b) == xf + partial
+            # a checked copy with the field cleared falls back to the exact split
+            c = biq.BiqPlan()
+            for k in ("kernel", "threads", "chunks_per_tile", "batch_tile", "tiles_per_split", "rows_per_wg",
+                      "wave_splits"):
+                setattr(c, k, getattr(p, k))
+            assert biq.biq_plan_check(m, n, q, b, 8, c).input_terms == 3
+    lib = biq.load_library()
+    import ctypes
+    plan = biq.BiqPlan()
+    assert lib.biq_plan_get_mfma(64, 64, 1, 1, 8, 4, ctypes.byref(plan)) == biq.BIQ_EINVAL
+    assert lib.biq_plan_get_mfma(64, 64, 5, 1, 8, 3, ctypes.byref(plan)) == biq.BIQ_EUNSUPPORTED
+    # the field belongs to the matrix-core kernel only
+    lut = biq.biq_plan_get_lut(512, 512, 1, 1, 8)
+    lut.input_terms = 2
+    with pytest.raises(Exception):
+        biq.biq_plan_check(512, 512, 1, 1, 8, lut)
 
 
 def test_argument_errors_are_reported_before_any_launch(biq):

@@ -384,14 +384,16 @@ def test_error_paths_on_device_buffers(biq):
     assert need >= 0
 
 
-def _unpack_plan(biq, q, batch_tile, groups_per_split, wave_splits=1, rpw=None):
+def _unpack_plan(biq, q, batch_tile, groups_per_split, wave_splits=1, rpw=None, terms=3):
     """Plan for the unpack-into-MFMA kernel (kernel 3): 256 threads, 32-byte key groups,
-    rows_per_wg = (4 / wave_splits) waves x rpw row tiles of 32 rows."""
+    rows_per_wg = (4 / wave_splits) waves x rpw row tiles of 32 rows; the inputs split into three
+    bf16 terms (exact, the library's choice) or two scaled fp16 terms."""
     if rpw is None:
         rpw = {1: 4, 2: 2}.get(q, 1)
     plan = _plan(biq, kernel=3, threads=256, ct=32, bt=batch_tile, tps=groups_per_split,
                  rows=(4 // wave_splits) * 32 * rpw)
     plan.wave_splits = wave_splits
+    plan.input_terms = terms
     return plan
 
 
@@ -422,15 +424,18 @@ def test_unpack_mfma_parity(biq, oracle, m, n, q, b, bt, gps, ws, rpw):
     B, alpha, X = _rand_inputs(m, n, q, b, seed=4200 + m + n + q + b)
     B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
     K = gpu_pack(biq, B_dev)
-    Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps, ws, rpw))
-    assert_within_tolerance(Y.cpu().numpy(), oracle.gemm_dense(B, alpha, X), alpha, X,
-                            what="unpack_mfma %s" % ((m, n, q, b, bt, gps, ws, rpw),))
+    ref = oracle.gemm_dense(B, alpha, X)
+    for terms in (3, 2):
+        Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps, ws, rpw, terms))
+        assert_within_tolerance(Y.cpu().numpy(), ref, alpha, X,
+                                what="unpack_mfma %s" % ((m, n, q, b, bt, gps, ws, rpw, terms),))
 
 
 def test_unpack_mfma_bit_exact_on_exact_inputs(biq, oracle):
-    """Small integer inputs: every partial sum is exactly representable and every scaled input is
-    the sum of its two fp16 terms, so any summation order, the split and the fp32 matrix-core
-    accumulation must reproduce Eq. 2 bit for bit."""
+    """Small integer inputs: every partial sum is exactly representable and every input is the sum
+    of its terms (three bf16 terms always; two scaled fp16 terms for these small integers), so any
+    summation order, the split and the fp32 matrix-core accumulation must reproduce Eq. 2 bit for
+    bit."""
     from paper_2005_09904_amd.workloads import Workload, make_exact_inputs
 
     m, n, q, b = 384, 1280, 3, 96
@@ -439,13 +444,43 @@ def test_unpack_mfma_bit_exact_on_exact_inputs(biq, oracle):
     B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
     K = gpu_pack(biq, B_dev)
     ref = oracle.gemm_dense(B, alpha, X)
-    for bt, gps, ws in ((64, 2, 1), (32, 5, 1), (64, 5, 2), (32, 3, 4)):
-        Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps, ws))
-        assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref), (bt, gps, ws)
+    for terms in (3, 2):
+        for bt, gps, ws in ((64, 2, 1), (32, 5, 1), (64, 5, 2), (32, 3, 4)):
+            Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps, ws, terms=terms))
+            assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref), (terms, bt, gps, ws)
+
+
+def test_unpack_mfma_exact_split_adds_no_input_error(biq, oracle):
+    """Three bf16 terms by truncation hold every bit of a finite fp32 input: with inputs that carry
+    all 24 significand bits the result must agree with the fp64 oracle as closely as the order of
+    fp32 additions allows, and better than the two-term variant, whose input rounding shows."""
+    m, n, q, b = 256, 2048, 2, 40
+    _say("unpack_mfma exact split")
+    B, alpha, X = _rand_inputs(m, n, q, b, seed=808)
+    B_dev, alpha_dev, X_dev = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, B_dev)
+    ref = oracle.gemm_dense(B, alpha, X)
+    err = {}
+    for terms in (3, 2):
+        Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=biq.biq_plan_get_mfma(m, n, q, b, 8, terms))
+        _, err[terms] = assert_within_tolerance(Y.cpu().numpy(), ref, alpha, X, what="terms=%d" % terms)
+    assert err[3] <= 5e-7 and err[2] <= 1e-6, err
+    # a one-hot contraction shows the inputs themselves: three terms return alpha * x bit for bit
+    Bh = -np.ones((1, 64, 256), dtype=np.int8)
+    Xh = np.zeros((32, 256), dtype=np.float32)
+    rng = np.random.default_rng(5)
+    hot = rng.integers(0, 256, size=32)
+    vals = rng.standard_normal(32).astype(np.float32) * np.float32(1.2345678)
+    Xh[np.arange(32), hot] = vals
+    ah = np.ones((1, 64), dtype=np.float32)
+    B_dev, alpha_dev, X_dev = device_inputs(Bh, ah, Xh)
+    K = gpu_pack(biq, B_dev)
+    Y = gpu_gemm(biq, K, alpha_dev, X_dev, 64, 256, 1, 8, plan=biq.biq_plan_get_mfma(64, 256, 1, 32, 8, 3)).cpu().numpy()
+    assert np.array_equal(Y, np.repeat(-vals[:, None], 64, axis=1))
 
 
 def test_unpack_mfma_input_scaling_covers_the_fp32_range(biq, oracle):
-    """Every input vector is scaled by its own power of two before it is split into fp16 terms:
+    """Two-term variant: every input vector is scaled by its own power of two before it is split into fp16 terms:
     vectors of very different magnitude (2^-120 .. 2^115, with subnormal elements, all zero), and vectors whose
     elements span 12 orders of magnitude, must all meet the bound, and with an error at the level
     of fp32 rounding (the split keeps 22 significand bits), not at the level of fp16."""
@@ -468,7 +503,8 @@ def test_unpack_mfma_input_scaling_covers_the_fp32_range(biq, oracle):
     K = gpu_pack(biq, B_dev)
     ref = oracle.gemm_dense(B, alpha, X)
     for bt, gps, ws in ((64, 6, 1), (32, 3, 2)):
-        Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8, plan=_unpack_plan(biq, q, bt, gps, ws)).cpu().numpy()
+        Y = gpu_gemm(biq, K, alpha_dev, X_dev, m, n, q, 8,
+                     plan=_unpack_plan(biq, q, bt, gps, ws, terms=2)).cpu().numpy()
         assert_within_tolerance(Y, ref, alpha, X, what="unpack_mfma scaling %s" % ((bt, gps, ws),))
         assert np.all(Y[7] == 0.0)
         err = np.sqrt(((Y - ref) ** 2).sum(axis=1)) / np.maximum(np.sqrt((ref ** 2).sum(axis=1)), 1e-300)
