@@ -444,6 +444,34 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     }
 
     BIQ_USTAMP(2);
+    // The epilogue's inputs are requested here, ahead of the exchange between the wave groups,
+    // all at once and without conditions (rows past m read row 0 and are never stored): -alpha
+    // of the lane's rows in every row tile, and (two terms) the exponents of its input vectors.
+    const bool vec_ok = ((p.m & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.out) & 15) == 0) &&
+                        ((reinterpret_cast<uintptr_t>(p.alpha) & 15) == 0);
+    float al[RPW][4][Q][4];
+    int xe[CT];
+    if (kg == 0) {
+#pragma unroll
+        for (int rp = 0; rp < RPW; ++rp)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int row = rbase + rp * 32 + 8 * vq + 4 * h;
+#pragma unroll
+                for (int i = 0; i < Q; ++i) {
+                    if (vec_ok) {
+                        const float4 a = *reinterpret_cast<const float4*>(p.alpha + (size_t)i * p.m + (row < p.m ? row : 0));
+                        al[rp][vq][i][0] = -a.x; al[rp][vq][i][1] = -a.y; al[rp][vq][i][2] = -a.z; al[rp][vq][i][3] = -a.w;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            al[rp][vq][i][e] = -p.alpha[(size_t)i * p.m + (row + e < p.m ? row + e : 0)];
+                    }
+                }
+            }
+#pragma unroll
+        for (int c = 0; c < CT; ++c) xe[c] = T == 2 ? -p.colexp[(cg * CT + c) * 32 + lr] : 0;
+    }
     // ---- sum over the wave groups: groups 1.. hand their accumulators to group 0 through LDS ----
     if constexpr (WS > 1) {
         float4* red = reinterpret_cast<float4*>(stage_buf);   // [WS - 1][WROWS][RT * CT * 4][64 lanes]
@@ -488,31 +516,11 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     constexpr int RED_FLOATS = (WS - 1) * WROWS * RT * CT * 1024;  // partial sums above, still being read
     static_assert((RED_FLOATS + WROWS * 32 * TP) * 4 <= G::LDS_BYTES, "transpose patches must fit");
     float* const patch = reinterpret_cast<float*>(stage_buf) + RED_FLOATS + wrow * (32 * TP);
-    const bool vec_ok = ((p.m & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.out) & 15) == 0) &&
-                        ((reinterpret_cast<uintptr_t>(p.alpha) & 15) == 0);
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) {
         const int row0 = rbase + rp * 32;                       // first row of this tile
-        float al[4][Q][4];                                      // -alpha of the lane's 16 rows
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-            const int row = row0 + 8 * vq + 4 * h;
-#pragma unroll
-            for (int i = 0; i < Q; ++i) {
-                if (vec_ok && row < p.m) {
-                    const float4 a = *reinterpret_cast<const float4*>(p.alpha + (size_t)i * p.m + row);
-                    al[vq][i][0] = -a.x; al[vq][i][1] = -a.y; al[vq][i][2] = -a.z; al[vq][i][3] = -a.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        al[vq][i][e] = row + e < p.m ? -p.alpha[(size_t)i * p.m + row + e] : 0.0f;
-                }
-            }
-        }
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
-            int xe = 0;                                            // two terms: the lane's input vector was scaled by 2^-xe
-            if constexpr (T == 2) xe = -p.colexp[(cg * CT + c) * 32 + lr];
             // tile -> patch[column lr][row]
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
@@ -521,8 +529,8 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                 for (int e = 0; e < 4; ++e) {
                     float v = 0.0f;
 #pragma unroll
-                    for (int i = 0; i < Q; ++i) v = fmaf(al[vq][i][e], acc[i * RPW + rp][c][4 * vq + e], v);
-                    y[e] = T == 2 ? ldexpf(v, xe) : v;
+                    for (int i = 0; i < Q; ++i) v = fmaf(al[rp][vq][i][e], acc[i * RPW + rp][c][4 * vq + e], v);
+                    y[e] = T == 2 ? ldexpf(v, xe[c]) : v;   // two terms: the lane's input vector was scaled by 2^-xe
                 }
                 *reinterpret_cast<float4*>(patch + lr * TP + 8 * vq + 4 * h) = make_float4(y[0], y[1], y[2], y[3]);
             }
