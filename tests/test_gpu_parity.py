@@ -541,12 +541,13 @@ def torch_equal(a, b):
 
 def test_hip_graph_replay_matches_eager(biq, oracle):
     """A sequence of biq_gemm calls (GEMV with chunk split + reduce, batched table kernel,
-    unpack_mfma with its input split and partial sums) captured into a HIP graph: every replay,
+    unpack_mfma with its input split and partial sums, with three and with two input terms)
+    captured into a HIP graph: every replay,
     with eager work in between, reproduces the eager results bit for bit.  The library records
     no memset nodes and allocates nothing, so its calls can be captured."""
     import torch
 
-    shapes = [(2048, 2048, 2, 1), (600, 1000, 3, 6), (1024, 2048, 2, 128)]
+    shapes = [(2048, 2048, 2, 1), (600, 1000, 3, 6), (1024, 2048, 2, 128), (1024, 2048, 2, 100)]
     s = torch.cuda.Stream()
     with torch.cuda.stream(s):
         calls, outs, refs = [], [], []
@@ -557,8 +558,8 @@ def test_hip_graph_replay_matches_eager(biq, oracle):
             Y = torch.zeros((b, m), dtype=torch.float32, device="cuda")
             ws = torch.empty(max(biq.biq_workspace_bytes(m, n, q, b, 8), 16), dtype=torch.uint8, device="cuda")
             plan = None
-            if i == 2:  # make sure the matrix-core path is in the graph whatever the planner prefers
-                plan = biq.biq_plan_check(m, n, q, b, 8, _unpack_plan(biq, q, 64, 4))
+            if i >= 2:  # make sure the matrix-core path is in the graph whatever the planner prefers
+                plan = biq.biq_plan_check(m, n, q, b, 8, _unpack_plan(biq, q, 64, 4, terms=3 if i == 2 else 2))
                 ws = torch.empty(biq.biq_plan_workspace_bytes(plan, m, b), dtype=torch.uint8, device="cuda")
             calls.append(biq.PreparedGemm(K, ad, Xd, Y, m, n, q, b, 8, workspace=ws, plan=plan))
             outs.append(Y)
