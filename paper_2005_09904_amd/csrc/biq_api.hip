@@ -179,7 +179,7 @@ bool plan_finish(biq_plan& pl, int m, int n, int q, int batch, int mu) {
 // for the conflict-free kernels (mu = 8, mu <= 5, mu = 6 up to 4 input vectors); 6.5e12 for the
 // generic one, which also streams keys at no more than about 0.25 TB/s; plus 6 us of launch
 // and table build.  Unpack + MFMA with the exact split: 2 * 3 flop per weight and padded input
-// vector (three bf16 terms) at 1.45e15 flop/s, plus 9.5 us (input split, launches, combining
+// vector (three bf16 terms) at 1.45e15 flop/s, plus 10 us (input split, launches, combining
 // partial sums).
 bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
     const double weights = (double)q * m * n;
@@ -189,7 +189,7 @@ bool unpack_mfma_is_faster(int m, int n, int q, int batch, int mu) {
     if (!tuned && t_lut < weights / 8 / 0.25e12) t_lut = weights / 8 / 0.25e12;
     t_lut += 6e-6;
     const double padded = (double)((batch + 31) / 32) * 32;
-    const double t_mfma = 9.5e-6 + 6.0 * weights * padded / 1.45e15;
+    const double t_mfma = 10e-6 + 6.0 * weights * padded / 1.45e15;
     return t_mfma < t_lut;
 }
 
