@@ -33,7 +33,7 @@ def log(msg: str) -> None:
 class Problem:
     """Device buffers of one workload; `copies` packed weight matrices used in rotation."""
 
-    def __init__(self, biq, torch, w, copies: int, real_first: bool = True, plan=None):
+    def __init__(self, biq, torch, w, copies: int, real_first: bool = True, plan=None, x_values: str = "fp32"):
         self.w = w
         dev = torch.device("cuda:0")
         self.key_bytes_padded = biq.biq_packed_bytes(w.m, w.n, w.q)
@@ -56,6 +56,10 @@ class Problem:
             self.host = None
             self.alpha = torch.rand((w.q, w.m), device=dev, generator=gen) * 0.95 + 0.05
             self.X = torch.randn((w.batch, w.n), device=dev, generator=gen)
+        if x_values == "fp16":      # fp32 inputs whose values came from half-precision arithmetic
+            self.X = self.X.half().float()
+        elif x_values == "bf16":
+            self.X = self.X.bfloat16().float()
         self.Y = torch.zeros((w.batch, w.m), dtype=torch.float32, device=dev)
         ws_bytes = biq.biq_workspace_bytes(w.m, w.n, w.q, w.batch, w.mu)
         if plan is not None:
@@ -360,18 +364,24 @@ def main() -> int:
             # the library's choice first; where that is the unpack + MFMA kernel (exact input
             # split), the lookup-table kernel on the same inputs as a second row and the two-term
             # variant of the matrix-core kernel, which only an explicit plan selects, as a third
-            plans = [None]
+            plans = [(None, "fp32")]
             if default.kernel != lut.kernel:
-                plans += [lut, biq.biq_plan_get_mfma(w.m, w.n, w.q, w.batch, w.mu, 2)]
-            for plan in plans:
+                plans += [(lut, "fp32"), (biq.biq_plan_get_mfma(w.m, w.n, w.q, w.batch, w.mu, 2), "fp32")]
+                if w.mu == 8:
+                    # the library's plan again on fp32 inputs that hold fp16 / bf16 values (activations
+                    # computed in half precision): the exact split has zero third (and second) terms
+                    # there and the kernel skips them
+                    plans += [(None, "fp16"), (None, "bf16")]
+            for plan, x_values in plans:
                 kname = biq.biq_kernel_name((plan or default).kernel)
                 terms = (plan or default).input_terms
                 copies = max(1, min(64, (512 * 1024 * 1024) // w.key_bytes + 1))
-                p = Problem(biq, torch, w, copies, real_first=False, plan=plan)
+                p = Problem(biq, torch, w, copies, real_first=False, plan=plan, x_values=x_values)
                 steps = 200 if w.lookups < 1e9 else 20
                 p.touch_all(torch)
                 t = time_steps(torch, p, steps, 5)
                 s = summarize(w, t)
+                s["input_values"] = x_values
                 s["key_copies_in_rotation"] = copies
                 s["kernel"] = kname
                 s["default_plan"] = plan is None
@@ -385,6 +395,9 @@ def main() -> int:
                     s["mfma_frac"] = s["mfma_TFLOPs"] / MFMA_F16_PEAK_TFLOPS
                     if terms == 2:
                         kname = "unpack_mfma, 2 input terms"
+                    elif x_values != "fp32":
+                        kname = "unpack_mfma, %s-valued inputs" % x_values
+                        del s["mfma_TFLOPs"], s["mfma_frac"]    # fewer terms are executed than counted above
                 elif w.batch > 1:
                     # batched table lookups are bounded by gathers from LDS (4 bytes per lookup)
                     s["lds_gather_GBps"] = 4.0 * w.lookups / t.median / 1e9

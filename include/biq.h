@@ -146,7 +146,10 @@ typedef struct {
     int input_terms;     /* unpack_mfma kernel: 16-bit terms every fp32 input is split into for the matrix
                             cores.  3 (0 is read as 3; what the library chooses): three bf16 terms, an
                             exact split - the result is that of an fp32 evaluation of Eq. 2 up to the
-                            order of the additions.  2: every input vector scaled by a power of two (its
+                            order of the additions; terms that are zero for all input vectors of a
+                            workgroup over a wave's whole part of the row are skipped, so inputs holding
+                            fp16 (bf16) values cost two thirds (one third) of the matrix instructions,
+                            with the same bits out.  2: every input vector scaled by a power of two (its
                             largest magnitude in [2^14, 2^15)) and split into two fp16 terms rounded to
                             nearest, 22 significand bits: a third fewer matrix instructions for an input
                             rounding of 2^-22 relative per element (2^-39 of the vector's largest

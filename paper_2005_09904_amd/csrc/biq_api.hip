@@ -453,7 +453,8 @@ bool plan_default(biq_plan& pl, int m, int n, int q, int batch, int mu, bool tab
 }
 
 // Bytes of the prepared-input area at the start of the workspace (unpack-MFMA plans only): the
-// B fragments, then (two terms) one scaling exponent per padded input vector.
+// B fragments, then one scaling exponent per padded input vector (two terms) or one count of
+// non-zero terms per MFMA step and column tile (three).
 size_t plan_xfrag_bytes(const biq_plan& pl) {
     const size_t b = (size_t)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split *
                      (size_t)unpack_group_pieces(pl.batch_tile, pl.input_terms) * 16;
@@ -461,7 +462,10 @@ size_t plan_xfrag_bytes(const biq_plan& pl) {
 }
 size_t plan_xf_bytes(const biq_plan& pl) {
     if (pl.kernel != KERNEL_UNPACK_MFMA) return 0;
-    const size_t e = pl.input_terms == 2 ? (size_t)pl.batch_tiles * pl.batch_tile * sizeof(int) : 0;
+    const size_t e = pl.input_terms == 2
+                         ? (size_t)pl.batch_tiles * pl.batch_tile * sizeof(int)
+                         : (size_t)pl.batch_tiles * pl.chunk_splits * pl.tiles_per_split * 16 * (pl.batch_tile / 32) *
+                               sizeof(int);
     return plan_xfrag_bytes(pl) + ((e + 255) & ~(size_t)255);
 }
 
@@ -553,6 +557,7 @@ biq_status run_unpack_mfma(const biq_plan& pl, const uint8_t* K, const float* al
     up.alpha = alpha;
     up.Xf = Xf;
     up.colexp = colexp;
+    up.nterms = colexp;   // the same area: exponents (two terms) or term counts (three)
     up.out = pl.chunk_splits > 1 ? partial : Y;
     up.m = m;
     up.batch = batch;

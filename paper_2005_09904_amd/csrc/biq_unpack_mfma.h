@@ -11,7 +11,10 @@
 //     accumulate in fp32.
 // T = 3, the default: x = x0 + x1 + x2 with three bf16 terms (8 significand bits each, taken by
 //     truncation, so the sum is exact).  The result differs from a plain fp32 evaluation of
-//     Eq. 2 only by the order of the additions.
+//     Eq. 2 only by the order of the additions.  Terms that are zero for all of a workgroup's
+//     input vectors over all of a wave's part of the row are skipped (their MFMAs and loads):
+//     inputs that carry fewer than 17 (9) significand bits - values that came from fp16 (bf16)
+//     arithmetic - cost two thirds (one third) of the matrix instructions, with the same bits out.
 // T = 2, on request (plan.input_terms = 2): every input vector is scaled by a power of two 2^e
 //     (e per vector, from its largest magnitude, which lands in [2^14, 2^15)) and every scaled
 //     element is split into two fp16 terms, x * 2^e = x0 + x1 + r with x0 = fp16(x * 2^e),
@@ -38,6 +41,8 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 namespace biq {
 
@@ -87,6 +92,8 @@ struct UnpackParams {
     const float* alpha;      // [q][m]
     const mfma_u32x4* Xf;    // prepared B operands (see above)
     const int* colexp;       // two terms: e of every (padded) input vector, its B operands hold x * 2^e
+    const int* nterms;       // three terms: per (column group, step, column tile), how many leading terms are
+                             // not all zero (1..3)
     float* out;              // Y [batch][m], or partials [splits][batch][m]
     int m, batch;
     uint32_t stride_bytes;
@@ -122,10 +129,10 @@ __device__ __forceinline__ void split2(float xs, uint32_t& t0, uint32_t& t1) {
 // elements past n are zero.
 template <int CT>
 __global__ __launch_bounds__(256) void xsplit3_kernel(const float* __restrict__ X,
-                                                      mfma_u32x4* __restrict__ Xf, int n, int batch,
-                                                      int steps, long long total) {
+                                                      mfma_u32x4* __restrict__ Xf, int* __restrict__ nterms,
+                                                      int n, int batch, int steps, long long total) {
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
+    if (idx >= total) return;              // (total is a multiple of 1024: whole workgroups only)
     const int lane = (int)(idx & 63);
     long long rest = idx >> 6;
     const int ct = (int)(rest % CT); rest /= CT;
@@ -157,16 +164,23 @@ __global__ __launch_bounds__(256) void xsplit3_kernel(const float* __restrict__ 
         split3(lo[i], t[0][2 * i], t[1][2 * i], t[2][2 * i]);
         split3(hi[i], t[0][2 * i + 1], t[1][2 * i + 1], t[2][2 * i + 1]);
     }
-    mfma_u32x4* dst = Xf + (idx >> 6) * (3 * 64) + lane;
+    mfma_u32x4 v[3];
+    uint32_t any[3];
 #pragma unroll
     for (int s = 0; s < 3; ++s) {
-        mfma_u32x4 v;
-        v.x = t[s][0] | (t[s][1] << 16);
-        v.y = t[s][2] | (t[s][3] << 16);
-        v.z = t[s][4] | (t[s][5] << 16);
-        v.w = t[s][6] | (t[s][7] << 16);
-        dst[s * 64] = v;
+        v[s].x = t[s][0] | (t[s][1] << 16);
+        v[s].y = t[s][2] | (t[s][3] << 16);
+        v[s].z = t[s][4] | (t[s][5] << 16);
+        v[s].w = t[s][6] | (t[s][7] << 16);
+        any[s] = (v[s].x | v[s].y | v[s].z | v[s].w) & 0x7fff7fffu;   // zero of either sign does not count
     }
+    mfma_u32x4* dst = Xf + (idx >> 6) * (3 * 64) + lane;
+#pragma unroll
+    for (int s = 0; s < 3; ++s) dst[s * 64] = v[s];
+    // how many leading terms this wave's (step, column tile) pair needs
+    const bool need3 = __builtin_amdgcn_ballot_w64(any[2] != 0u) != 0ull;
+    const bool need2 = __builtin_amdgcn_ballot_w64(any[1] != 0u) != 0ull;
+    if (lane == 0) nterms[idx >> 6] = need3 ? 3 : need2 ? 2 : 1;
 }
 
 // Two scaled terms: input vectors -> B fragments (two 16-byte pieces per MFMA step and
@@ -317,7 +331,6 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     constexpr int RT = Q * RPW;                       // row tiles (32 key rows each) per wave
     constexpr int WROWS = 4 / WS;                     // waves side by side along the rows
     constexpr int SPIECES = G::SPIECES;
-    constexpr int VPM = T == 3 ? 2 : (8 + CT * T - 1) / (CT * T);  // expansion instructions to place per MFMA
     static_assert((WS - 1) * WROWS * RT * CT * 4096 <= G::LDS_BYTES, "partial sums must fit");
     extern __shared__ __align__(16) mfma_u32x4 stage_buf[];  // partial sums, transpose patches
 
@@ -387,13 +400,15 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     const int nsteps = ngroups * 16;
     if (ngroups > 0) {
         const mfma_u32x4* xw = p.Xf + ((size_t)cg * steps_total + (size_t)ga * 16) * SPIECES + lane;
-        auto load_b = [&](int s, opvec (&b)[CT][T]) {
+        // the first `cnt` terms of step s (cnt is a constant wherever this is called)
+        auto load_b = [&](int s, opvec (&b)[CT][T], int cnt) {
             const int sc = min(s, nsteps - 1);         // past the end: the last step again, unused
             const mfma_u32x4* src = xw + (size_t)sc * SPIECES;
 #pragma unroll
             for (int c = 0; c < CT; ++c)
 #pragma unroll
-                for (int tm = 0; tm < T; ++tm) b[c][tm] = __builtin_bit_cast(opvec, src[(c * T + tm) * 64]);
+                for (int tm = 0; tm < T; ++tm)
+                    if (tm < cnt) b[c][tm] = __builtin_bit_cast(opvec, src[(c * T + tm) * 64]);
         };
         auto expand_a = [&](const mfma_u32x4 (&k)[RT], int step, opvec (&a)[RT]) {
             const int d = step >> 2, ks = step & 3;    // step 0..15 within the key group
@@ -404,42 +419,76 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                      : ks == 2 ? unpack_step<2, opvec>(w, one2) : unpack_step<3, opvec>(w, one2);
             }
         };
+        // Three terms: how many leading terms are not all zero anywhere in this wave's key groups
+        // for this workgroup's input vectors = the largest of the counts xsplit3_kernel left for
+        // them (16 * CT per key group, contiguous; lane l looks at the l-th 16 bytes, then the
+        // largest over the wave).  Decided once per wave: each count gets a loop of its own; the
+        // first three steps' fragments are requested with all T terms before the count is known.
+        // The counts are requested first and looked at last: the keys and the first fragments
+        // (all T terms) are on their way meanwhile, and loads return in order.
+        int nt_wave = T;
+        int4 cnt = make_int4(1, 1, 1, 1);
+        if constexpr (T == 3) {
+            const int4* f = reinterpret_cast<const int4*>(p.nterms + ((size_t)cg * steps_total + 16 * (size_t)ga) * CT);
+            const int pieces = ngroups * 4 * CT;       // 16-byte pieces holding this wave's counts
+            cnt = f[min(lane, pieces - 1)];
+            for (int i = lane + 64; i < pieces; i += 64) {     // more than 16 / CT key groups per wave
+                const int4 v = f[i];
+                cnt = make_int4(max(cnt.x, v.x), max(cnt.y, v.y), max(cnt.z, v.z), max(cnt.w, v.w));
+            }
+        }
         mfma_u32x4 key[RT], keyn[RT];
         opvec bfr[4][CT][T];
         opvec af[2][RT];
         load_keys(ga, key);
-        load_b(0, bfr[0]);
-        load_b(1, bfr[1]);
-        load_b(2, bfr[2]);
+        load_b(0, bfr[0], T);
+        load_b(1, bfr[1], T);
+        load_b(2, bfr[2], T);
+        if constexpr (T == 3) {
+            const int r = max(max(cnt.x, cnt.y), max(cnt.z, cnt.w));
+            nt_wave = __builtin_amdgcn_ballot_w64(r >= 3) != 0ull ? 3 : __builtin_amdgcn_ballot_w64(r >= 2) != 0ull ? 2 : 1;
+        }
         BIQ_USTAMP(1);
-        for (int gi = 0; gi < ngroups; ++gi) {
-            // The first step's operands are expanded here, not during the last step of the group
-            // before: written there, the compiler moves the expansion up to where the keys are
-            // loaded and waits for them on the spot.
-            expand_a(key, 0, af[0]);
-            __builtin_amdgcn_sched_barrier(0);
-            load_keys(ga + gi + 1, keyn);
+        // The whole walk over the wave's key groups with NT of the T terms.
+        auto walk = [&](auto ntc) {
+            constexpr int NT = decltype(ntc)::value;
+            constexpr int VPM = NT == 3 ? 2 : (8 + CT * NT - 1) / (CT * NT);  // expansion instructions to place per MFMA
+            for (int gi = 0; gi < ngroups; ++gi) {
+                // The first step's operands are expanded here, not during the last step of the group
+                // before: written there, the compiler moves the expansion up to where the keys are
+                // loaded and waits for them on the spot.
+                expand_a(key, 0, af[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                load_keys(ga + gi + 1, keyn);
 #pragma unroll
-            for (int st = 0; st < 16; ++st) {
-                load_b(gi * 16 + st + 3, bfr[(st + 3) & 3]);
-                if (st + 1 < 16) expand_a(key, st + 1, af[(st + 1) & 1]);
+                for (int st = 0; st < 16; ++st) {
+                    load_b(gi * 16 + st + 3, bfr[(st + 3) & 3], NT);
+                    if (st + 1 < 16) expand_a(key, st + 1, af[(st + 1) & 1]);
 #pragma unroll
-                for (int tm = 0; tm < T; ++tm)
+                    for (int tm = 0; tm < NT; ++tm)
 #pragma unroll
-                    for (int t = 0; t < RT; ++t)
+                        for (int t = 0; t < RT; ++t)
 #pragma unroll
-                        for (int c = 0; c < CT; ++c)
-                            acc[t][c] = Op::mfma(af[st & 1][t], bfr[st & 3][c][tm], acc[t][c]);
+                            for (int c = 0; c < CT; ++c)
+                                acc[t][c] = Op::mfma(af[st & 1][t], bfr[st & 3][c][tm], acc[t][c]);
 #pragma unroll
-                for (int i = 0; i < RT * CT * T; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
-                    if (i < CT * T) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);       // global load
-                    if (VPM * i < RT * 8) __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);  // VALU
+                    for (int i = 0; i < RT * CT * NT; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
+                        if (i < CT * NT) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);      // global load
+                        if (VPM * i < RT * 8) __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);  // VALU
+                    }
+                    __builtin_amdgcn_sched_barrier(0);   // a step's instructions stay in the step
                 }
-                __builtin_amdgcn_sched_barrier(0);   // a step's instructions stay in the step
-            }
 #pragma unroll
-            for (int t = 0; t < RT; ++t) key[t] = keyn[t];
+                for (int t = 0; t < RT; ++t) key[t] = keyn[t];
+            }
+        };
+        if constexpr (T == 3) {
+            if (nt_wave >= 3) walk(std::integral_constant<int, 3>{});
+            else if (nt_wave == 2) walk(std::integral_constant<int, 2>{});
+            else walk(std::integral_constant<int, 1>{});
+        } else {
+            walk(std::integral_constant<int, T>{});
         }
     }
 

@@ -93,6 +93,8 @@ def test_default_plans_are_consistent(biq, mu):
             xf = p.batch_tiles * p.chunk_splits * p.tiles_per_split * pieces * 16
             xf = (xf + 255) // 256 * 256
             assert xf >= 6 * b * n
+            # ... and one count of non-zero terms per MFMA step and column tile
+            xf += (p.batch_tiles * p.chunk_splits * p.tiles_per_split * 16 * (p.batch_tile // 32) * 4 + 255) // 256 * 256
             assert biq.biq_plan_workspace_bytes(p, m, b) == xf + partial
             assert biq.biq_workspace_bytes(m, n, q, b, mu) >= xf + partial
         else:
@@ -127,6 +129,8 @@ def test_mfma_plans_for_both_input_splits(biq):
             xf = (xf + 255) // 256 * 256
             if terms == 2:
                 xf += (p.batch_tiles * p.batch_tile * 4 + 255) // 256 * 256
+            else:
+                xf += (p.batch_tiles * p.chunk_splits * p.tiles_per_split * 16 * (p.batch_tile // 32) * 4 + 255) // 256 * 256
             partial = p.chunk_splits * b * m * 4 if p.chunk_splits > 1 else 0
             assert biq.biq_plan_workspace_bytes(p, m, b) == xf + partial
             # a checked copy with the field cleared falls back to the exact split

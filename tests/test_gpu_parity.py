@@ -479,6 +479,41 @@ def test_unpack_mfma_exact_split_adds_no_input_error(biq, oracle):
     assert np.array_equal(Y, np.repeat(-vals[:, None], 64, axis=1))
 
 
+def test_unpack_mfma_skips_zero_terms_without_changing_the_result(biq, oracle):
+    """Exact split: terms that are zero for all of a workgroup's input vectors over a wave's part
+    of the row are skipped.  Inputs that carry 11 (fp16-valued) or 8 (bf16-valued) significand
+    bits take the two-term and one-term loops; one full-precision element anywhere in a wave's
+    share (here: in some input vectors, in some column ranges only) brings the third term back
+    for that wave alone.  Every variant must meet the bound, and agree bit for bit with the
+    same call on inputs where a harmless full-precision element forces all three terms."""
+    import torch
+
+    m, n, q, b = 384, 2048, 2, 96
+    _say("unpack_mfma zero-term skipping")
+    B, alpha, X = _rand_inputs(m, n, q, b, seed=911)
+    X16 = X.astype(np.float16).astype(np.float32)
+    Xb = torch.from_numpy(X).bfloat16().float().numpy()
+    Xmix = X16.copy()
+    Xmix[5, 700:900] = X[5, 700:900]          # full precision in one vector, one stretch of columns
+    Xmix[70:, :256] = Xb[70:, :256]
+    B_dev, alpha_dev, _ = device_inputs(B, alpha, X)
+    K = gpu_pack(biq, B_dev)
+    for name, Xv in (("fp16-valued", X16), ("bf16-valued", Xb), ("mixed", Xmix)):
+        ref = oracle.gemm_dense(B, alpha, Xv)
+        for bt, gps, ws in ((64, 8, 1), (32, 3, 2), (32, 4, 4)):
+            plan = _unpack_plan(biq, q, bt, gps, ws, terms=3)
+            Xd = torch.from_numpy(Xv).cuda()
+            Y = gpu_gemm(biq, K, alpha_dev, Xd, m, n, q, 8, plan=plan).cpu().numpy()
+            assert_within_tolerance(Y, ref, alpha, Xv, what="%s %s" % (name, (bt, gps, ws)))
+            # the same inputs plus one extra input vector of full precision in the same column
+            # group: all three terms everywhere; the first b vectors must not change by a bit
+            Xfull = np.concatenate([Xv, X[:1] * np.float32(1.0000001)], axis=0)
+            if (b + 1 - 1) // bt == (b - 1) // bt:      # the extra vector shares the last column group only
+                Yf = gpu_gemm(biq, K, alpha_dev, torch.from_numpy(Xfull).cuda(), m, n, q, 8,
+                              plan=_unpack_plan(biq, q, bt, gps, ws, terms=3)).cpu().numpy()
+                assert np.array_equal(Yf[:b], Y), (name, bt, gps, ws)
+
+
 def test_unpack_mfma_input_scaling_covers_the_fp32_range(biq, oracle):
     """Two-term variant: every input vector is scaled by its own power of two before it is split into fp16 terms:
     vectors of very different magnitude (2^-120 .. 2^115, with subnormal elements, all zero), and vectors whose
