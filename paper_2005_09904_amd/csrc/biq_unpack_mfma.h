@@ -401,13 +401,14 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
     if (ngroups > 0) {
         const mfma_u32x4* xw = p.Xf + ((size_t)cg * steps_total + (size_t)ga * 16) * SPIECES + lane;
         // the first `cnt` terms of step s (cnt is a constant wherever this is called)
-        auto load_b = [&](int s, opvec (&b)[CT][T], int cnt) {
+        auto load_b = [&](int s, auto& b, int cnt) {   // b: opvec [CT][T] or [CT][fewer]
+            constexpr int TD = sizeof(b[0]) / sizeof(b[0][0]);
             const int sc = min(s, nsteps - 1);         // past the end: the last step again, unused
             const mfma_u32x4* src = xw + (size_t)sc * SPIECES;
 #pragma unroll
             for (int c = 0; c < CT; ++c)
 #pragma unroll
-                for (int tm = 0; tm < T; ++tm)
+                for (int tm = 0; tm < TD; ++tm)
                     if (tm < cnt) b[c][tm] = __builtin_bit_cast(opvec, src[(c * T + tm) * 64]);
         };
         auto expand_a = [&](const mfma_u32x4 (&k)[RT], int step, opvec (&a)[RT]) {
@@ -450,9 +451,14 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
         }
         BIQ_USTAMP(1);
         // The whole walk over the wave's key groups with NT of the T terms.
-        auto walk = [&](auto ntc) {
+        // The walk over the wave's key groups with NT of the T terms, fragments requested R - 1
+        // steps ahead in a ring `rg` of R slots whose first three are filled.
+        auto walk_ring = [&](auto ntc, auto rc, auto& rg) {
             constexpr int NT = decltype(ntc)::value;
+            constexpr int R = decltype(rc)::value;
             constexpr int VPM = NT == 3 ? 2 : (8 + CT * NT - 1) / (CT * NT);  // expansion instructions to place per MFMA
+#pragma unroll
+            for (int j = 3; j + 1 < R; ++j) load_b(j, rg[j], NT);
             for (int gi = 0; gi < ngroups; ++gi) {
                 // The first step's operands are expanded here, not during the last step of the group
                 // before: written there, the compiler moves the expansion up to where the keys are
@@ -462,7 +468,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                 load_keys(ga + gi + 1, keyn);
 #pragma unroll
                 for (int st = 0; st < 16; ++st) {
-                    load_b(gi * 16 + st + 3, bfr[(st + 3) & 3], NT);
+                    load_b(gi * 16 + st + R - 1, rg[(st + R - 1) & (R - 1)], NT);
                     if (st + 1 < 16) expand_a(key, st + 1, af[(st + 1) & 1]);
 #pragma unroll
                     for (int tm = 0; tm < NT; ++tm)
@@ -470,7 +476,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                         for (int t = 0; t < RT; ++t)
 #pragma unroll
                             for (int c = 0; c < CT; ++c)
-                                acc[t][c] = Op::mfma(af[st & 1][t], bfr[st & 3][c][tm], acc[t][c]);
+                                acc[t][c] = Op::mfma(af[st & 1][t], rg[st & (R - 1)][c][tm], acc[t][c]);
 #pragma unroll
                     for (int i = 0; i < RT * CT * NT; ++i) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
@@ -481,6 +487,24 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                 }
 #pragma unroll
                 for (int t = 0; t < RT; ++t) key[t] = keyn[t];
+            }
+        };
+        // With two or three terms, three steps ahead cover the latency of the fragments (measured:
+        // a ring of 8 is no faster); with one term a step is a third as long and the ring grows
+        // to 8 slots of one term, which takes fewer registers still.
+        auto walk = [&](auto ntc) {
+            constexpr int NT = decltype(ntc)::value;
+            if constexpr (NT > 1 || T == 1) {
+                walk_ring(ntc, std::integral_constant<int, 4>{}, bfr);
+            } else {
+                opvec ring[8][CT][NT];
+#pragma unroll
+                for (int j = 0; j < 3; ++j)
+#pragma unroll
+                    for (int c = 0; c < CT; ++c)
+#pragma unroll
+                        for (int tm = 0; tm < NT; ++tm) ring[j][c][tm] = bfr[j][c][tm];
+                walk_ring(ntc, std::integral_constant<int, 8>{}, ring);
             }
         };
         if constexpr (T == 3) {
