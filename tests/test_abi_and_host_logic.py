@@ -115,6 +115,46 @@ def test_default_plans_are_consistent(biq, mu):
         assert biq.biq_kernel_name(p.kernel) != "unknown"
 
 
+def test_plans_hold_their_invariants_on_random_shapes(biq):
+    """Planner invariants on a few thousand random shapes (host logic only, nothing is launched):
+    every plan the library hands out passes its own check unchanged, covers all rows, chunks and
+    input vectors, fits the LDS, and asks for exactly the workspace its fields imply."""
+    from hypothesis import given, settings, strategies as st
+
+    dims = st.one_of(st.integers(1, 300), st.integers(1, 20000), st.sampled_from([512, 1024, 2048, 4096, 16384, 65536]))
+
+    @settings(max_examples=1500, deadline=None, derandomize=True)
+    @given(m=dims, n=dims, q=st.integers(1, 6), b=st.one_of(st.integers(1, 40), st.sampled_from([64, 128, 256, 1000])),
+           mu=st.integers(1, 10))
+    def check(m, n, q, b, mu):
+        for getter in (biq.biq_plan_get, biq.biq_plan_get_lut):
+            p = getter(m, n, q, b, mu)
+            name = biq.biq_kernel_name(p.kernel)
+            assert name != "unknown"
+            assert 0 < p.lds_bytes <= 160 * 1024 and p.threads % 64 == 0 and 64 <= p.threads <= 1024
+            assert p.row_blocks * p.rows_per_wg >= m > (p.row_blocks - 1) * p.rows_per_wg
+            assert p.batch_tiles * p.batch_tile >= b > (p.batch_tiles - 1) * p.batch_tile
+            unit = biq.biq_key_row_stride(n) if name == "unpack_mfma" else biq.biq_num_chunks(n, mu)
+            tiles = -(-unit // p.chunks_per_tile)
+            assert p.chunk_splits * p.tiles_per_split >= tiles > (p.chunk_splits - 1) * p.tiles_per_split
+            # the plan checks as it stands
+            c = biq.BiqPlan()
+            for k, _ in biq.BiqPlan._fields_:
+                if k != "reserved":
+                    setattr(c, k, getattr(p, k))
+            c = biq.biq_plan_check(m, n, q, b, mu, c)
+            assert c.as_dict() == p.as_dict()
+            if name != "unpack_mfma":
+                partial = p.chunk_splits * b * m * 4 if p.chunk_splits > 1 else 0
+                assert biq.biq_plan_workspace_bytes(p, m, b) == partial
+                assert p.input_terms == 0 and p.wave_splits == 0
+            else:
+                assert getter is biq.biq_plan_get and q <= 4 and p.input_terms == 3
+            assert biq.biq_workspace_bytes(m, n, q, b, mu) >= biq.biq_plan_workspace_bytes(p, m, b)
+
+    check()
+
+
 def test_mfma_plans_for_both_input_splits(biq):
     """biq_plan_get_mfma: the matrix-core mapping on either side of the crossover, with the exact
     three-term split or, on request only, the two-term one; workspace = prepared input (2 bytes
