@@ -678,6 +678,52 @@ def test_random_shapes_default_plans(biq, oracle):
     assert {"query_generic", "gemv8", "gemv8_half", "gemm8x2", "gemm8x2_half", "unpack_mfma"} <= seen, seen
 
 
+def test_random_matrix_core_plans(biq, oracle):
+    """Seeded random shapes x random valid mappings of the matrix-core kernel (column tile, row
+    tiles per wave, wave groups, key groups per split) x both input splits, with inputs of
+    mixed precision so that the one-, two- and three-term loops all occur."""
+    import torch
+
+    rng = np.random.default_rng(4242)
+    done = 0
+    for case in range(400):
+        if done == 36:
+            break
+        q = int(rng.integers(1, 5))
+        m = int(rng.integers(1, 600))
+        n = int(rng.choice([int(rng.integers(1, 260)), int(rng.integers(260, 3000)), int(rng.integers(3000, 9000))]))
+        b = int(rng.choice([1, 7, 31, 32, 33, 64, 65, 100, 130]))
+        while m * n * q * b > 50_000_000:
+            m = max(1, m // 2)
+        bt = int(rng.choice([32, 64]))
+        ws = int(rng.choice([1, 2, 4]))
+        r = int(rng.choice([1, 2, 4]))
+        groups = -(-biq.biq_key_row_stride(n) // 32)
+        gps = int(rng.integers(1, groups + 1))
+        terms = int(rng.choice([3, 3, 2]))
+        plan = _unpack_plan(biq, q, bt, gps, ws, r, terms)
+        try:
+            plan = biq.biq_plan_check(m, n, q, b, 8, plan)
+        except biq.BiqError:
+            continue                                   # not a valid mapping (register file, q * r > 4)
+        done += 1
+        _say("matrix-core case %d: m=%d n=%d q=%d b=%d bt=%d ws=%d r=%d gps=%d terms=%d" % (
+            case, m, n, q, b, bt, ws, r, gps, terms))
+        B, alpha, X = _rand_inputs(m, n, q, b, 5200 + case)
+        kind = case % 3                               # full precision / fp16-valued / bf16-valued, one vector mixed in
+        if kind == 1:
+            X = X.astype(np.float16).astype(np.float32)
+        elif kind == 2:
+            X = torch.from_numpy(X).bfloat16().float().numpy()
+            if b > 40:
+                X[b - 1, n // 2:] = X[b - 1, n // 2:] * np.float32(1.0009765625)   # more bits in one vector's second half
+        Bd, ad, Xd = device_inputs(B, alpha, X)
+        K = gpu_pack(biq, Bd)
+        Y = gpu_gemm(biq, K, ad, Xd, m, n, q, 8, plan=plan).cpu().numpy()
+        assert_within_tolerance(Y, oracle.gemm_dense(B, alpha, X), alpha, X, "matrix-core case %d" % case)
+    assert done == 36
+
+
 @pytest.mark.parametrize("mu", [1, 2, 3, 4, 5, 6])
 def test_wide_kernel_plans(biq, oracle, mu):
     """query_wide (32 lanes per row, conflict-free gathers for mu <= 6) with explicit plans:
