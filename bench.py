@@ -371,7 +371,8 @@ def main() -> int:
                     # the library's plan again on fp32 inputs that hold fp16 / bf16 values (activations
                     # computed in half precision): the exact split has zero third (and second) terms
                     # there and the kernel skips them
-                    plans += [(None, "fp16"), (None, "bf16")]
+                    plans += [(None, "fp16"), (None, "bf16"),
+                              (biq.biq_plan_get_mfma(w.m, w.n, w.q, w.batch, w.mu, 2), "fp16")]
             for plan, x_values in plans:
                 kname = biq.biq_kernel_name((plan or default).kernel)
                 terms = (plan or default).input_terms
@@ -393,10 +394,10 @@ def main() -> int:
                     s["input_terms"] = terms
                     s["mfma_TFLOPs"] = 2.0 * terms * w.q * w.m * w.n * padded / t.median / 1e12
                     s["mfma_frac"] = s["mfma_TFLOPs"] / MFMA_F16_PEAK_TFLOPS
-                    if terms == 2:
+                    if terms == 2 and x_values == "fp32":
                         kname = "unpack_mfma, 2 input terms"
                     elif x_values != "fp32":
-                        kname = "unpack_mfma, %s-valued inputs" % x_values
+                        kname = "unpack_mfma%s, %s-valued inputs" % (", 2 input terms" if terms == 2 else "", x_values)
                         del s["mfma_TFLOPs"], s["mfma_frac"]    # fewer terms are executed than counted above
                 elif w.batch > 1:
                     # batched table lookups are bounded by gathers from LDS (4 bytes per lookup)

@@ -154,7 +154,8 @@ typedef struct {
                             nearest, 22 significand bits: a third fewer matrix instructions for an input
                             rounding of 2^-22 relative per element (2^-39 of the vector's largest
                             magnitude where the second term is subnormal), the scaling undone on
-                            output; an input vector holding Inf or NaN gives non-finite outputs for that
+                            output; a second term that is zero for all input vectors of a workgroup
+                            (inputs holding fp16 values) is skipped; an input vector holding Inf or NaN gives non-finite outputs for that
                             vector.  Only on request                                              */
     int reserved[1];
 } biq_plan;

@@ -21,7 +21,8 @@
 //     x1 = fp16(x * 2^e - x0), both rounded to nearest: |r| <= 2^-22 |x * 2^e| (or 2^-25
 //     absolutely, i.e. 2^-39 of the vector's largest magnitude, where x1 is subnormal); the
 //     epilogue multiplies by 2^-e.  A third fewer MFMAs for an input rounding of a quarter of
-//     fp32's unit in the last place per element.
+//     fp32's unit in the last place per element.  A second term that is zero for all of a
+//     workgroup's input vectors (inputs holding fp16 values) is skipped here too.
 // The kernel does not depend on mu: it reads the packed bitmap, which is the same for all mu.
 //
 // MFMA operand layout (32x32x16, wave of 64 lanes, lane = 32*h + r):
@@ -91,7 +92,8 @@ struct UnpackParams {
     const uint8_t* K;        // [q][m][stride]
     const float* alpha;      // [q][m]
     const mfma_u32x4* Xf;    // prepared B operands (see above)
-    const int* colexp;       // two terms: e of every (padded) input vector, its B operands hold x * 2^e
+    const int* colexp;       // two terms: per (padded) input vector e (its B operands hold x * 2^e) and the
+                             // second-term flag, packed as (e + kExpBias) | kExpSecondTerm
     const int* nterms;       // three terms: per (column group, step, column tile), how many leading terms are
                              // not all zero (1..3)
     float* out;              // Y [batch][m], or partials [splits][batch][m]
@@ -194,6 +196,8 @@ __global__ __launch_bounds__(256) void xsplit3_kernel(const float* __restrict__ 
 // maximum and writing a share of the fragments - slower from n = 4096 to 16384.)
 constexpr int kXsplitThreads = 1024;
 constexpr int kXsplitCached = 4;
+// an input vector's word in `colexp`: e + kExpBias (e = -113 .. 140), and whether its second term is non-zero anywhere
+constexpr int kExpBias = 1024, kExpMask = 0xfff, kExpSecondTerm = 1 << 16;
 
 template <int CT>
 __global__ __launch_bounds__(kXsplitThreads) void xsplit2_kernel(const float* __restrict__ X,
@@ -234,24 +238,27 @@ __global__ __launch_bounds__(kXsplitThreads) void xsplit2_kernel(const float* __
             }
         }
     };
-    auto store_fragment = [&](int f, const float (&x)[8], int e) {
-        const int ks = f & 3, d = (f >> 2) & 3, h = (f >> 4) & 1, g = f >> 5;
-        const int step = g * 16 + d * 4 + ks;  // MFMA step along the row: 16 per key group
+    // the two terms of a fragment's 8 scaled elements as 16-byte pieces; returns the bits of the second
+    auto split_fragment = [&](const float (&x)[8], int e, mfma_u32x4 (&v)[2]) -> uint32_t {
         uint32_t t[2][8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) split2(ldexpf(x[i], e), t[0][i], t[1][i]);
-        mfma_u32x4* dst = Xf + (((size_t)cg * steps + step) * CT + ct) * (2 * 64) + 32 * h + lr;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            mfma_u32x4 v;
-            v.x = t[s][0] | (t[s][1] << 16);
-            v.y = t[s][2] | (t[s][3] << 16);
-            v.z = t[s][4] | (t[s][5] << 16);
-            v.w = t[s][6] | (t[s][7] << 16);
-            dst[s * 64] = v;
+            v[s].x = t[s][0] | (t[s][1] << 16);
+            v[s].y = t[s][2] | (t[s][3] << 16);
+            v[s].z = t[s][4] | (t[s][5] << 16);
+            v[s].w = t[s][6] | (t[s][7] << 16);
         }
+        return (v[1].x | v[1].y | v[1].z | v[1].w) & 0x7fff7fffu;    // zero of either sign does not count
     };
-
+    auto store_fragment = [&](int f, const mfma_u32x4 (&v)[2]) {
+        const int ks = f & 3, d = (f >> 2) & 3, h = (f >> 4) & 1, g = f >> 5;
+        const int step = g * 16 + d * 4 + ks;  // MFMA step along the row: 16 per key group
+        mfma_u32x4* dst = Xf + (((size_t)cg * steps + step) * CT + ct) * (2 * 64) + 32 * h + lr;
+        dst[0] = v[0];
+        dst[64] = v[1];
+    };
     auto fold_max = [](uint32_t mb, const float (&x)[8]) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) mb = max(mb, __float_as_uint(x[i]) & 0x7fffffffu);
@@ -282,17 +289,28 @@ __global__ __launch_bounds__(kXsplitThreads) void xsplit2_kernel(const float* __
     // [2^14, 2^15); zero and subnormal vectors scale as if the maximum were 2^-126
     const int ex = (int)(mb >> 23);
     const int e = ex == 255 ? 0 : 141 - max(ex, 1);
-    if (tid == 0) colexp[col] = e;
 
+    // The terms of the held fragments, and whether any second term is non-zero (inputs that hold
+    // fp16 values have none: the main kernel then skips that term) - found before any store is
+    // issued, since the barrier would wait for stores in flight.  What is not held counts as non-zero.
+    mfma_u32x4 pieces[kXsplitCached][2];
+    uint32_t second = nfrag > kXsplitThreads * kXsplitCached ? 1u : 0u;
+#pragma unroll
+    for (int i = 0; i < kXsplitCached; ++i)
+        if (tid + kXsplitThreads * i < nfrag) second |= split_fragment(held[i], e, pieces[i]);
+    const int need2 = __syncthreads_or(second != 0u);
+    if (tid == 0) colexp[col] = (e + kExpBias) | (need2 ? kExpSecondTerm : 0);
 #pragma unroll
     for (int i = 0; i < kXsplitCached; ++i) {
         const int f = tid + kXsplitThreads * i;
-        if (f < nfrag) store_fragment(f, held[i], e);
+        if (f < nfrag) store_fragment(f, pieces[i]);
     }
     for (int f = tid + kXsplitThreads * kXsplitCached; f < nfrag; f += kXsplitThreads) {
         float x[8];
+        mfma_u32x4 v[2];
         load_fragment(f, x);
-        store_fragment(f, x, e);
+        split_fragment(x, e, v);
+        store_fragment(f, v);
     }
 }
 
@@ -429,6 +447,8 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
         // (all T terms) are on their way meanwhile, and loads return in order.
         int nt_wave = T;
         int4 cnt = make_int4(1, 1, 1, 1);
+        int colword = kExpSecondTerm;
+        if constexpr (T == 2) colword = p.colexp[cg * CT * 32 + (lane & (CT * 32 - 1))];   // the workgroup's input vectors
         if constexpr (T == 3) {
             const int4* f = reinterpret_cast<const int4*>(p.nterms + ((size_t)cg * steps_total + 16 * (size_t)ga) * CT);
             const int pieces = ngroups * 4 * CT;       // 16-byte pieces holding this wave's counts
@@ -449,6 +469,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
             const int r = max(max(cnt.x, cnt.y), max(cnt.z, cnt.w));
             nt_wave = __builtin_amdgcn_ballot_w64(r >= 3) != 0ull ? 3 : __builtin_amdgcn_ballot_w64(r >= 2) != 0ull ? 2 : 1;
         }
+        if constexpr (T == 2) nt_wave = __builtin_amdgcn_ballot_w64((colword & kExpSecondTerm) != 0) != 0ull ? 2 : 1;
         BIQ_USTAMP(1);
         // The whole walk over the wave's key groups with NT of the T terms.
         // The walk over the wave's key groups with NT of the T terms, fragments requested R - 1
@@ -507,13 +528,9 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                 walk_ring(ntc, std::integral_constant<int, 8>{}, ring);
             }
         };
-        if constexpr (T == 3) {
-            if (nt_wave >= 3) walk(std::integral_constant<int, 3>{});
-            else if (nt_wave == 2) walk(std::integral_constant<int, 2>{});
-            else walk(std::integral_constant<int, 1>{});
-        } else {
-            walk(std::integral_constant<int, T>{});
-        }
+        if (T == 3 && nt_wave >= 3) walk(std::integral_constant<int, T>{});
+        else if (nt_wave >= 2) walk(std::integral_constant<int, 2>{});
+        else walk(std::integral_constant<int, 1>{});
     }
 
     BIQ_USTAMP(2);
@@ -543,7 +560,7 @@ __global__ __launch_bounds__(kUnpackThreads) void unpack_mfma_kernel(const Unpac
                 }
             }
 #pragma unroll
-        for (int c = 0; c < CT; ++c) xe[c] = T == 2 ? -p.colexp[(cg * CT + c) * 32 + lr] : 0;
+        for (int c = 0; c < CT; ++c) xe[c] = T == 2 ? kExpBias - (p.colexp[(cg * CT + c) * 32 + lr] & kExpMask) : 0;
     }
     // ---- sum over the wave groups: groups 1.. hand their accumulators to group 0 through LDS ----
     if constexpr (WS > 1) {

@@ -505,6 +505,11 @@ def test_unpack_mfma_skips_zero_terms_without_changing_the_result(biq, oracle):
             Xd = torch.from_numpy(Xv).cuda()
             Y = gpu_gemm(biq, K, alpha_dev, Xd, m, n, q, 8, plan=plan).cpu().numpy()
             assert_within_tolerance(Y, ref, alpha, Xv, what="%s %s" % (name, (bt, gps, ws)))
+            # two scaled fp16 terms: the second one is zero for fp16- and bf16-valued vectors and is
+            # skipped where a whole column group has none; exact on such inputs up to summation order
+            Y2 = gpu_gemm(biq, K, alpha_dev, Xd, m, n, q, 8,
+                          plan=_unpack_plan(biq, q, bt, gps, ws, terms=2)).cpu().numpy()
+            assert_within_tolerance(Y2, ref, alpha, Xv, what="%s %s two terms" % (name, (bt, gps, ws)))
             # the same inputs plus one extra input vector of full precision in the same column
             # group: all three terms everywhere; the first b vectors must not change by a bit
             Xfull = np.concatenate([Xv, X[:1] * np.float32(1.0000001)], axis=0)
