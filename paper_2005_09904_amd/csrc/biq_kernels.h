@@ -75,26 +75,61 @@ __global__ __launch_bounds__(256) void unpack_keys_kernel(const uint32_t* __rest
 // =====================================================================================
 // biq_build_lut: X [batch][n] -> LUT [C][2^MU][batch] in device memory (Sec. III-B).
 // One thread per (chunk, VEC adjacent input vectors, group of 16 keys); VEC = 4 (16-byte
-// stores) when the batch is a multiple of 4 and LUT is 16-byte aligned, else 1.
+// stores) when the batch is a multiple of 4 and LUT is 16-byte aligned, else 1.  A workgroup
+// owns a box of 2^lta vector groups x 2^lth key groups x 2^ltc chunks (256 threads, vector
+// groups fastest: a wave's stores are contiguous runs of the table).  The box's inputs -
+// MU floats per (chunk, vector), 32-byte pieces scattered over X - go through LDS once per
+// workgroup: read by each thread on its own they cost the address unit one cache line per lane
+// and load, 16 times over for the 16 key groups, and that, not the 64 MiB of stores, set the
+// time (n = 4096, 128 vectors, mu = 8: 22.9 us; a plain fill of the table takes 11.3).
 // =====================================================================================
+constexpr int kLutStageFloats = 4096;   // largest box: 256 (chunk, vector group) pairs x 4 vectors x 4 floats
+
 template <int MU, int VEC>
 __global__ __launch_bounds__(256) void build_lut_kernel(const float* __restrict__ X,
                                                         float* __restrict__ LUT, int n, int batch,
-                                                        int C) {
+                                                        int C, int lta, int lth, int ltc, int a_tiles,
+                                                        int h_tiles) {
     constexpr int E = 1 << MU;
     constexpr int HG = (MU > 4) ? (1 << (MU - 4)) : 1;  // groups of 16 keys per table
     constexpr int LN = (MU > 4) ? 16 : E;               // keys per group
+    constexpr int XW = MU <= 8 ? 8 : 10;                // elements table16 / table16_wide take
+    __shared__ float xs[kLutStageFloats];
     const int bv = batch / VEC;                         // VEC divides batch
-    const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long long total = (long long)C * HG * bv;
-    if (gid >= total) return;
-    const int a = (int)(gid % bv) * VEC;
-    const long long rest = gid / bv;
-    const int h = (int)(rest % HG);
-    const int c = (int)(rest / HG);
+    const int tid = threadIdx.x;
+    int box = blockIdx.x;
+    const int A0 = (box % a_tiles) << lta; box /= a_tiles;
+    const int H0 = (box % h_tiles) << lth;
+    const int C0 = (box / h_tiles) << ltc;
+    // stage: xs[chunk in box][vector in box][MU], zeros past n, C and the batch
+    const int nvec = VEC << lta;
+    const int staged = (nvec * MU) << ltc;
+    for (int e = tid; e < staged; e += 256) {
+        const int j = e % MU;
+        const int r = e / MU;
+        const int vec = A0 * VEC + r % nvec;
+        const int c = C0 + r / nvec;
+        const long long col = (long long)c * MU + j;
+        xs[e] = (vec < batch && c < C && col < n) ? X[(size_t)vec * n + col] : 0.0f;
+    }
+    __syncthreads();
+    const int ta = tid & ((1 << lta) - 1);
+    const int th = (tid >> lta) & ((1 << lth) - 1);
+    const int tc = tid >> (lta + lth);
+    const int a = (A0 + ta) * VEC;
+    const int h = H0 + th;
+    const int c = C0 + tc;
+    if (A0 + ta >= bv || h >= HG || c >= C) return;
     float ent[VEC][16];
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) chunk_table16<MU>(X, n, batch, a + v, c, (uint32_t)h, ent[v]);
+    for (int v = 0; v < VEC; ++v) {
+        const float* src = xs + ((tc * nvec) + ta * VEC + v) * MU;
+        float x[XW];
+#pragma unroll
+        for (int j = 0; j < XW; ++j) x[j] = j < MU ? src[j] : 0.0f;
+        if constexpr (MU <= 8) table16(x, (uint32_t)h, ent[v]);
+        else table16_wide(x, (uint32_t)h, ent[v]);
+    }
     float* dst = LUT + ((size_t)c * E + (size_t)h * 16) * batch + a;
 #pragma unroll
     for (int l = 0; l < LN; ++l) {

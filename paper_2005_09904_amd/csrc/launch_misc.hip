@@ -60,16 +60,26 @@ hipError_t launch_unpack_keys(int mu, bool wide_keys, const uint32_t* K, void* k
 hipError_t launch_build_lut(int mu, const float* X, float* LUT, int n, int batch, int C, hipStream_t s) {
     const int HG = mu > 4 ? (1 << (mu - 4)) : 1;
     const bool vec4 = (batch % 4 == 0) && ((reinterpret_cast<uintptr_t>(LUT) & 15) == 0);
-    const long long total = (long long)C * HG * (vec4 ? batch / 4 : batch);
-    const unsigned grid = (unsigned)((total + 255) / 256);
+    const int bv = vec4 ? batch / 4 : batch;
+    // box of a workgroup: up to 64 vector groups, then key groups, then chunks, 256 threads in all
+    int lta = 0, lth = 0;
+    while (lta < 6 && (1 << lta) < bv) ++lta;
+    while (lta + lth < 8 && (1 << lth) < HG) ++lth;
+    const int ltc = 8 - lta - lth;
+    const long long a_tiles = ((long long)bv + (1 << lta) - 1) >> lta;
+    const long long h_tiles = ((long long)HG + (1 << lth) - 1) >> lth;
+    const long long c_tiles = ((long long)C + (1 << ltc) - 1) >> ltc;
+    const long long boxes = a_tiles * h_tiles * c_tiles;
+    if (boxes > 0x7fffffffll) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)boxes;
 #define BIQ_LUT_CASE(MU)                                                                           \
     case MU:                                                                                       \
         if (vec4)                                                                                  \
             hipLaunchKernelGGL((build_lut_kernel<MU, 4>), dim3(grid), dim3(256), 0, s, X, LUT, n,  \
-                               batch, C);                                                          \
+                               batch, C, lta, lth, ltc, (int)a_tiles, (int)h_tiles);               \
         else                                                                                       \
             hipLaunchKernelGGL((build_lut_kernel<MU, 1>), dim3(grid), dim3(256), 0, s, X, LUT, n,  \
-                               batch, C);                                                          \
+                               batch, C, lta, lth, ltc, (int)a_tiles, (int)h_tiles);               \
         break;
     switch (mu) {
         BIQ_LUT_CASE(1) BIQ_LUT_CASE(2) BIQ_LUT_CASE(3) BIQ_LUT_CASE(4) BIQ_LUT_CASE(5)
